@@ -1,0 +1,293 @@
+/*
+ * CPU oracle for the cloud-side verification step of FlexSpec
+ * (Alg. 2 step 2 and the KV-session / rollback paragraph of Sec. IV-C).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file defines what the GPU library must
+ * compute; it is slow on purpose, shares no code with the GPU path and must
+ * never be called from it.  Everything floating point is fp64; weights are
+ * widened exactly from their storage type (fp32 or bf16 bit patterns).
+ *
+ * What is written out here:
+ *   - orc_forward : the target model M_t' scoring a block of new tokens on top
+ *                   of a restored per-user KV cache (Alg. 2 "q <- M_t'(x_draft,
+ *                   context)"; Sec. IV-C: KV pairs are computed only for the
+ *                   newly received tokens).  Llama-style pre-norm decoder,
+ *                   textbook definitions, no blocking or fusion.
+ *   - orc_sample  : the acceptance loop of Alg. 2 (greedy: longest prefix with
+ *                   draft == argmax) and, for temperature > 0, the speculative
+ *                   sampling rule of the works the paper builds on (accept with
+ *                   probability min(1, p/q), on rejection resample from the
+ *                   normalised positive part of p - q, bonus token from p when
+ *                   every draft is accepted), which keeps the output law equal
+ *                   to the target model's (Sec. II, Regime B of Sec. V).
+ *   - orc_rollback: the KV rollback of Sec. IV-C (positions from the first
+ *                   rejected draft onward are discarded).
+ *
+ * Parity pins for every function live in tests/test_oracle_*.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+  int n_layers, d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int weights_bf16; /* 1: weight arrays hold bf16 bit patterns (uint16_t), 0: float */
+  double rms_eps, rope_theta;
+} orc_model;
+
+/* All matrices are [out_features][in_features], row-major. */
+typedef struct {
+  const void *embed;             /* [vocab][d_model]                          */
+  const void *final_norm;        /* [d_model]                                 */
+  const void *lm_head;           /* [vocab][d_model]                          */
+  const void *const *attn_norm;  /* per layer [d_model]                       */
+  const void *const *w_qkv;      /* per layer [(H+2*Hkv)*hd][d_model]: Wq|Wk|Wv */
+  const void *const *w_o;        /* per layer [d_model][H*hd]                 */
+  const void *const *mlp_norm;   /* per layer [d_model]                       */
+  const void *const *w_gate_up;  /* per layer [2*d_ffn][d_model]: gate|up     */
+  const void *const *w_down;     /* per layer [d_model][d_ffn]                */
+} orc_weights;
+
+static inline double widen(const void *w, int bf16, size_t idx) {
+  if (bf16) {
+    uint32_t bits = ((uint32_t)((const uint16_t *)w)[idx]) << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+  }
+  return (double)((const float *)w)[idx];
+}
+
+/* y[m][o] = sum_k x[m][k] * W[o][k]   (x: [n][in], y: [n][out]) */
+static void linear(const void *W, int bf16, int out, int in, const double *x, int n, double *y) {
+#pragma omp parallel for schedule(static)
+  for (int o = 0; o < out; ++o) {
+    for (int m = 0; m < n; ++m) {
+      double acc = 0.0;
+      for (int k = 0; k < in; ++k) acc += x[(size_t)m * in + k] * widen(W, bf16, (size_t)o * in + k);
+      y[(size_t)m * out + o] = acc;
+    }
+  }
+}
+
+/* RMSNorm: y = x * g / sqrt(mean(x^2) + eps) */
+static void rmsnorm(const double *x, const void *g, int bf16, int d, double eps, int n, double *y) {
+  for (int m = 0; m < n; ++m) {
+    double ss = 0.0;
+    for (int k = 0; k < d; ++k) ss += x[(size_t)m * d + k] * x[(size_t)m * d + k];
+    double r = 1.0 / sqrt(ss / d + eps);
+    for (int k = 0; k < d; ++k) y[(size_t)m * d + k] = x[(size_t)m * d + k] * r * widen(g, bf16, k);
+  }
+}
+
+/* Rotary embedding, half-split pairing (i, i + hd/2), angle = pos * theta^(-2i/hd). */
+static void rope(double *vec, int hd, int pos, double theta) {
+  int half = hd / 2;
+  for (int i = 0; i < half; ++i) {
+    double ang = (double)pos * pow(theta, -2.0 * i / hd);
+    double c = cos(ang), s = sin(ang);
+    double a = vec[i], b = vec[i + half];
+    vec[i] = a * c - b * s;
+    vec[i + half] = a * s + b * c;
+  }
+}
+
+/*
+ * Score n new tokens that sit at positions L .. L+n-1 of one user's session.
+ *   kc, vc : the session's KV cache, [n_layers][cap][n_kv_heads][head_dim] doubles;
+ *            positions < L hold the restored context, positions L..L+n-1 are
+ *            written here (the KV pairs of the newly received tokens).
+ *   logits : [n][vocab], row i = target logits for the token FOLLOWING tokens[i].
+ *   hidden : optional [n][d_model], final residual stream before the last norm.
+ * Query i attends to keys 0 .. L+i (context plus the block up to itself).
+ * Returns 0, or -1 on bad arguments / out of memory.
+ */
+int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
+                const int32_t *tokens, int n, double *logits, double *hidden) {
+  const int d = mo->d_model, H = mo->n_heads, Hkv = mo->n_kv_heads, hd = mo->head_dim;
+  const int F = mo->d_ffn, V = mo->vocab, bf = mo->weights_bf16;
+  if (n <= 0 || L < 0 || L + n > cap || H % Hkv != 0 || hd % 2 != 0) return -1;
+  for (int i = 0; i < n; ++i)
+    if (tokens[i] < 0 || tokens[i] >= V) return -1;
+  const int qdim = H * hd, kvdim = Hkv * hd, qkvdim = qdim + 2 * kvdim, group = H / Hkv;
+  double *h = malloc(sizeof(double) * n * d), *a = malloc(sizeof(double) * n * d);
+  double *qkv = malloc(sizeof(double) * n * qkvdim), *att = malloc(sizeof(double) * n * qdim);
+  double *gu = malloc(sizeof(double) * n * 2 * F), *act = malloc(sizeof(double) * n * F);
+  double *upd = malloc(sizeof(double) * n * d), *sc = malloc(sizeof(double) * (L + n));
+  if (!h || !a || !qkv || !att || !gu || !act || !upd || !sc) return -1;
+
+  for (int i = 0; i < n; ++i)
+    for (int k = 0; k < d; ++k) h[(size_t)i * d + k] = widen(w->embed, bf, (size_t)tokens[i] * d + k);
+
+  for (int l = 0; l < mo->n_layers; ++l) {
+    double *kl = kc + (size_t)l * cap * kvdim, *vl = vc + (size_t)l * cap * kvdim;
+    rmsnorm(h, w->attn_norm[l], bf, d, mo->rms_eps, n, a);
+    linear(w->w_qkv[l], bf, qkvdim, d, a, n, qkv);
+    for (int i = 0; i < n; ++i) {
+      double *row = qkv + (size_t)i * qkvdim;
+      int pos = L + i;
+      for (int hh = 0; hh < H; ++hh) rope(row + hh * hd, hd, pos, mo->rope_theta);
+      for (int hh = 0; hh < Hkv; ++hh) rope(row + qdim + hh * hd, hd, pos, mo->rope_theta);
+      memcpy(kl + (size_t)pos * kvdim, row + qdim, sizeof(double) * kvdim);
+      memcpy(vl + (size_t)pos * kvdim, row + qdim + kvdim, sizeof(double) * kvdim);
+    }
+    for (int i = 0; i < n; ++i) {
+      int nkeys = L + i + 1; /* causal inside the block: keys 0 .. L+i */
+      for (int hh = 0; hh < H; ++hh) {
+        const double *qv = qkv + (size_t)i * qkvdim + hh * hd;
+        int kvh = hh / group;
+        double mx = -INFINITY;
+        for (int j = 0; j < nkeys; ++j) {
+          const double *kv = kl + (size_t)j * kvdim + kvh * hd;
+          double s = 0.0;
+          for (int e = 0; e < hd; ++e) s += qv[e] * kv[e];
+          sc[j] = s / sqrt((double)hd);
+          if (sc[j] > mx) mx = sc[j];
+        }
+        double den = 0.0;
+        for (int j = 0; j < nkeys; ++j) { sc[j] = exp(sc[j] - mx); den += sc[j]; }
+        double *o = att + (size_t)i * qdim + hh * hd;
+        for (int e = 0; e < hd; ++e) o[e] = 0.0;
+        for (int j = 0; j < nkeys; ++j) {
+          const double *vv = vl + (size_t)j * kvdim + kvh * hd;
+          double p = sc[j] / den;
+          for (int e = 0; e < hd; ++e) o[e] += p * vv[e];
+        }
+      }
+    }
+    linear(w->w_o[l], bf, d, qdim, att, n, upd);
+    for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
+    rmsnorm(h, w->mlp_norm[l], bf, d, mo->rms_eps, n, a);
+    linear(w->w_gate_up[l], bf, 2 * F, d, a, n, gu);
+    for (int i = 0; i < n; ++i)
+      for (int f = 0; f < F; ++f) {
+        double g = gu[(size_t)i * 2 * F + f], u = gu[(size_t)i * 2 * F + F + f];
+        act[(size_t)i * F + f] = g / (1.0 + exp(-g)) * u; /* silu(g) * u */
+      }
+    linear(w->w_down[l], bf, d, F, act, n, upd);
+    for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
+  }
+  if (hidden) memcpy(hidden, h, sizeof(double) * n * d);
+  rmsnorm(h, w->final_norm, bf, d, mo->rms_eps, n, a);
+  linear(w->lm_head, bf, V, d, a, n, logits);
+  free(h); free(a); free(qkv); free(att); free(gu); free(act); free(upd); free(sc);
+  return 0;
+}
+
+typedef struct {
+  int32_t tau;          /* accepted drafts, 0..gamma                                        */
+  int32_t next_token;   /* correction token (tau < gamma) or bonus token (tau == gamma)     */
+  int32_t used_residual;/* 1 if next_token was drawn from the residual distribution         */
+  int32_t pad_;
+  double accept_margin; /* min over tested drafts of |u_i - min(1, p/q)|; +inf if none      */
+  double cdf_margin;    /* distance of u_sample from the chosen token's CDF edges (normalised) */
+} orc_sample_out;
+
+static void softmax_row(const double *lg, int V, double T, double *p) {
+  double mx = -INFINITY, den = 0.0;
+  for (int x = 0; x < V; ++x) if (lg[x] / T > mx) mx = lg[x] / T;
+  for (int x = 0; x < V; ++x) { p[x] = exp(lg[x] / T - mx); den += p[x]; }
+  for (int x = 0; x < V; ++x) p[x] /= den;
+}
+
+static int argmax_row(const double *lg, int V) { /* lowest index wins ties */
+  int best = 0;
+  for (int x = 1; x < V; ++x) if (lg[x] > lg[best]) best = x;
+  return best;
+}
+
+/* Smallest x whose inclusive running sum of mass exceeds u * total; the last
+ * index with positive mass if rounding leaves none. */
+static int inverse_cdf(const double *mass, int V, double u, double *margin) {
+  double total = 0.0;
+  for (int x = 0; x < V; ++x) total += mass[x];
+  double target = u * total, run = 0.0;
+  int pick = -1, last_pos = 0;
+  double lo = 0.0, hi = 0.0;
+  for (int x = 0; x < V; ++x) {
+    if (mass[x] > 0.0) last_pos = x;
+    double prev = run;
+    run += mass[x];
+    if (pick < 0 && run > target) { pick = x; lo = prev; hi = run; }
+  }
+  if (pick < 0) { pick = last_pos; lo = hi = total; }
+  if (margin) {
+    double a = fabs(target - lo), b = fabs(hi - target);
+    *margin = (a < b ? a : b) / total;
+  }
+  return pick;
+}
+
+/*
+ * Accept / reject one request's drafts and emit the next token.
+ *   logits : [gamma+1][V] target logits; row i scores the token after input row i
+ *            (row 0 = after last_token, row i = after draft i).
+ *   q      : [gamma][V] draft probabilities, q[i-1] is the law draft i was drawn from
+ *            (ignored when T == 0).
+ *   u_acc  : [gamma] uniforms in [0,1); u_smp: one uniform for the emitted token.
+ *   a_out  : optional [gamma], acceptance probabilities of the drafts that were tested.
+ * T == 0 is greedy decoding (Alg. 2): accept while draft == argmax, emit argmax.
+ */
+int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
+               const float *u_acc, float u_smp, double T, orc_sample_out *out, double *a_out) {
+  if (V <= 0 || gamma < 0 || T < 0.0) return -1;
+  out->tau = 0; out->used_residual = 0; out->accept_margin = INFINITY; out->cdf_margin = INFINITY;
+  if (T == 0.0) {
+    int tau = 0;
+    while (tau < gamma && draft[tau] == argmax_row(logits + (size_t)tau * V, V)) ++tau;
+    out->tau = tau;
+    out->next_token = argmax_row(logits + (size_t)tau * V, V);
+    return 0;
+  }
+  double *p = malloc(sizeof(double) * V), *r = malloc(sizeof(double) * V);
+  if (!p || !r) return -1;
+  int tau = 0;
+  for (int i = 1; i <= gamma; ++i) {
+    int dtok = draft[i - 1];
+    if (dtok < 0 || dtok >= V) { free(p); free(r); return -1; }
+    softmax_row(logits + (size_t)(i - 1) * V, V, T, p);
+    double qd = (double)q[(size_t)(i - 1) * V + dtok];
+    double ratio = p[dtok] / qd;              /* qd == 0 gives +inf (or NaN for 0/0) */
+    double a = (ratio >= 1.0) ? 1.0 : ratio;
+    if (!(a == a)) a = 0.0;                   /* p = q = 0: a token the draft cannot have produced */
+    if (a_out) a_out[i - 1] = a;
+    double mg = fabs((double)u_acc[i - 1] - a);
+    if (mg < out->accept_margin) out->accept_margin = mg;
+    if ((double)u_acc[i - 1] < a) ++tau; else break;
+  }
+  out->tau = tau;
+  softmax_row(logits + (size_t)tau * V, V, T, p);
+  if (tau < gamma) {
+    double Z = 0.0;
+    for (int x = 0; x < V; ++x) {
+      double dlt = p[x] - (double)q[(size_t)tau * V + x];
+      r[x] = dlt > 0.0 ? dlt : 0.0;
+      Z += r[x];
+    }
+    if (Z > 0.0) {
+      out->used_residual = 1;
+      out->next_token = inverse_cdf(r, V, (double)u_smp, &out->cdf_margin);
+      free(p); free(r);
+      return 0;
+    }
+  }
+  out->next_token = inverse_cdf(p, V, (double)u_smp, &out->cdf_margin);
+  free(p); free(r);
+  return 0;
+}
+
+/*
+ * KV rollback: after tau of gamma drafts were accepted on top of L cached
+ * positions, positions [0, L+1+tau) stay valid (context, the pending token and
+ * the accepted drafts); everything from the first rejected draft onward is
+ * discarded.  pages_released counts the pages (page_size positions each) that
+ * covered the appended block but hold no valid position any more.
+ */
+int orc_rollback(int L, int gamma, int tau, int page_size, int32_t *new_len, int32_t *pages_released) {
+  if (L < 0 || gamma < 0 || tau < 0 || tau > gamma || page_size <= 0) return -1;
+  int keep = L + 1 + tau, written = L + 1 + gamma;
+  *new_len = keep;
+  *pages_released = (written + page_size - 1) / page_size - (keep + page_size - 1) / page_size;
+  return 0;
+}

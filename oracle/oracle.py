@@ -1,0 +1,172 @@
+"""ctypes front end of the CPU oracle (flexspec_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: the oracle defines what the verification step of
+Alg. 2 (step 2) and the KV rollback of Sec. IV-C must compute.  Only tests,
+the smoke check and the benchmark's cpu_baseline leg may import this module;
+the GPU library never does, and this module imports nothing from it.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "flexspec_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP over output features only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+class _Model(C.Structure):
+    _fields_ = [(n, C.c_int) for n in ("n_layers", "d_model", "n_heads", "n_kv_heads", "head_dim", "d_ffn",
+                                       "vocab", "weights_bf16")] + [("rms_eps", C.c_double), ("rope_theta", C.c_double)]
+
+
+class _Weights(C.Structure):
+    _fields_ = [("embed", C.c_void_p), ("final_norm", C.c_void_p), ("lm_head", C.c_void_p)] + [
+        (n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down")]
+
+
+class _SampleOut(C.Structure):
+    _fields_ = [("tau", C.c_int32), ("next_token", C.c_int32), ("used_residual", C.c_int32), ("pad_", C.c_int32),
+                ("accept_margin", C.c_double), ("cdf_margin", C.c_double)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_forward.restype = C.c_int
+        _lib.orc_sample.restype = C.c_int
+        _lib.orc_rollback.restype = C.c_int
+    return _lib
+
+
+@dataclass
+class SampleResult:
+    tau: int
+    next_token: int
+    used_residual: bool
+    accept_margin: float
+    cdf_margin: float
+    accept_prob: np.ndarray
+
+
+def _model_struct(cfg) -> _Model:
+    return _Model(cfg.n_layers, cfg.d_model, cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, cfg.d_ffn, cfg.vocab,
+                  1 if cfg.dtype == "bf16" else 0, float(cfg.rms_eps), float(cfg.rope_theta))
+
+
+def _weights_struct(cfg, w):
+    """w: dict of numpy arrays (float32, or uint16 holding bf16 bits), [out][in] row-major."""
+    want = np.uint16 if cfg.dtype == "bf16" else np.float32
+    keep = []
+
+    def ptr(a):
+        a = np.ascontiguousarray(a)
+        assert a.dtype == want, (a.dtype, want)
+        keep.append(a)
+        return a.ctypes.data
+
+    def per_layer(name):
+        arr = (C.c_void_p * cfg.n_layers)(*[ptr(w[f"{name}.{l}"]) for l in range(cfg.n_layers)])
+        keep.append(arr)
+        return C.cast(arr, C.POINTER(C.c_void_p))
+
+    ws = _Weights(ptr(w["embed"]), ptr(w["final_norm"]), ptr(w["lm_head"]),
+                  per_layer("attn_norm"), per_layer("w_qkv"), per_layer("w_o"),
+                  per_layer("mlp_norm"), per_layer("w_gate_up"), per_layer("w_down"))
+    return ws, keep
+
+
+def new_cache(cfg, cap: int):
+    """Empty per-session KV cache: two [n_layers][cap][n_kv_heads][head_dim] fp64 arrays."""
+    shape = (cfg.n_layers, cap, cfg.n_kv_heads, cfg.head_dim)
+    return np.zeros(shape, np.float64), np.zeros(shape, np.float64)
+
+
+def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False):
+    """Target forward over tokens placed at positions L.. on top of cache (kc, vc); appends their KV.
+
+    Returns logits [n][vocab] fp64 (and the pre-norm hidden state if asked).  Alg. 2 step 2.
+    """
+    tokens = np.ascontiguousarray(tokens, np.int32)
+    n = int(tokens.shape[0])
+    assert kc.dtype == np.float64 and vc.dtype == np.float64 and kc.flags.c_contiguous and vc.flags.c_contiguous
+    cap = kc.shape[1]
+    logits = np.empty((n, cfg.vocab), np.float64)
+    hidden = np.empty((n, cfg.d_model), np.float64) if want_hidden else None
+    ms = _model_struct(cfg)
+    ws, keep = _weights_struct(cfg, w)
+    rc = lib().orc_forward(C.byref(ms), C.byref(ws), C.c_void_p(kc.ctypes.data), C.c_void_p(vc.ctypes.data),
+                           C.c_int(cap), C.c_int(L), C.c_void_p(tokens.ctypes.data), C.c_int(n),
+                           C.c_void_p(logits.ctypes.data),
+                           C.c_void_p(hidden.ctypes.data) if want_hidden else C.c_void_p(0))
+    del keep
+    if rc != 0:
+        raise ValueError("orc_forward rejected its arguments")
+    return (logits, hidden) if want_hidden else logits
+
+
+def sample(logits, draft, q, u_acc, u_smp: float, T: float) -> SampleResult:
+    """Acceptance loop + correction/bonus token for one request (Alg. 2 step 2; speculative sampling for T>0)."""
+    logits = np.ascontiguousarray(logits, np.float64)
+    gamma = int(len(draft))
+    V = int(logits.shape[1])
+    assert logits.shape[0] == gamma + 1
+    draft = np.ascontiguousarray(draft, np.int32)
+    u_acc = np.ascontiguousarray(u_acc, np.float32)
+    if T > 0 and gamma > 0:
+        q = np.ascontiguousarray(q, np.float32)
+        assert q.shape == (gamma, V)
+        qp = C.c_void_p(q.ctypes.data)
+    else:
+        qp = C.c_void_p(0)
+    out = _SampleOut()
+    a = np.full(gamma, np.nan, np.float64)
+    rc = lib().orc_sample(C.c_void_p(logits.ctypes.data), C.c_int(V), C.c_int(gamma), C.c_void_p(draft.ctypes.data),
+                          qp, C.c_void_p(u_acc.ctypes.data), C.c_float(float(u_smp)), C.c_double(float(T)),
+                          C.byref(out), C.c_void_p(a.ctypes.data))
+    if rc != 0:
+        raise ValueError("orc_sample rejected its arguments")
+    return SampleResult(out.tau, out.next_token, bool(out.used_residual), out.accept_margin, out.cdf_margin, a)
+
+
+def rollback(L: int, gamma: int, tau: int, page_size: int):
+    """KV rollback of Sec. IV-C: returns (new valid length, pages released)."""
+    nl, pr = C.c_int32(), C.c_int32()
+    rc = lib().orc_rollback(C.c_int(L), C.c_int(gamma), C.c_int(tau), C.c_int(page_size), C.byref(nl), C.byref(pr))
+    if rc != 0:
+        raise ValueError("orc_rollback rejected its arguments")
+    return nl.value, pr.value
+
+
+@dataclass
+class VerifyResult:
+    logits: np.ndarray
+    sample: SampleResult
+    new_len: int
+    pages_released: int
+
+
+def verify(cfg, w, kc, vc, L: int, last_token: int, draft, q, u_acc, u_smp: float, T: float) -> VerifyResult:
+    """One request of the verification step: score [last_token, drafts], accept/reject, roll back."""
+    toks = np.concatenate([[last_token], np.asarray(draft, np.int64)]).astype(np.int32)
+    logits = forward(cfg, w, kc, vc, L, toks)
+    s = sample(logits, draft, q, u_acc, u_smp, T)
+    nl, pr = rollback(L, len(draft), s.tau, cfg.page_size)
+    return VerifyResult(logits, s, nl, pr)

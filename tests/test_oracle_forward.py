@@ -1,0 +1,215 @@
+"""Pins for the oracle's target-model forward over a draft block (CPU only).
+
+orc_forward scores new tokens on top of a restored KV cache (Alg. 2 step 2, Sec. IV-C).  It is
+checked against library routines (a full-sequence causal decoder assembled from torch's fp64
+embedding / rms_norm / linear / scaled_dot_product_attention / silu, with rotary embedding done as
+complex multiplication), against closed forms for specially built weights, and against invariants
+of the KV session (incremental == one shot, stale slots beyond the valid length are never read).
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import oracle
+from paper_2601_00644_amd import synth
+
+
+def _weights64(cfg, w):
+    if cfg.dtype == "bf16":
+        return {k: torch.from_numpy(synth.bits_to_f32(v).astype(np.float64)) for k, v in w.items()}
+    return {k: torch.from_numpy(v.astype(np.float64)) for k, v in w.items()}
+
+
+def library_full_forward(cfg, w, tokens):
+    """Uncached causal decoder over a whole token sequence, from torch library ops in fp64."""
+    W = _weights64(cfg, w)
+    n = len(tokens)
+    H, Hkv, hd = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim
+    x = F.embedding(torch.as_tensor(np.asarray(tokens), dtype=torch.long), W["embed"])
+    pos = torch.arange(n, dtype=torch.float64)
+    inv = cfg.rope_theta ** (-torch.arange(0, hd, 2, dtype=torch.float64) / hd)
+    rot = torch.polar(torch.ones(n, hd // 2, dtype=torch.float64), pos[:, None] * inv[None, :])  # e^{i pos w}
+
+    def rope(t):  # t: [n, heads, hd]; pairs (i, i + hd/2) form one complex number
+        c = torch.complex(t[..., : hd // 2], t[..., hd // 2:]) * rot[:, None, :]
+        return torch.cat([c.real, c.imag], dim=-1)
+
+    for l in range(cfg.n_layers):
+        a = F.rms_norm(x, (cfg.d_model,), W[f"attn_norm.{l}"], cfg.rms_eps)
+        qkv = F.linear(a, W[f"w_qkv.{l}"])
+        q, k, v = qkv.split([H * hd, Hkv * hd, Hkv * hd], dim=-1)
+        q, k, v = rope(q.view(n, H, hd)), rope(k.view(n, Hkv, hd)), v.reshape(n, Hkv, hd)
+        o = F.scaled_dot_product_attention(q.transpose(0, 1)[None], k.transpose(0, 1)[None], v.transpose(0, 1)[None],
+                                           is_causal=True, enable_gqa=True)[0]
+        x = x + F.linear(o.transpose(0, 1).reshape(n, H * hd), W[f"w_o.{l}"])
+        m = F.rms_norm(x, (cfg.d_model,), W[f"mlp_norm.{l}"], cfg.rms_eps)
+        g, u = F.linear(m, W[f"w_gate_up.{l}"]).split([cfg.d_ffn, cfg.d_ffn], dim=-1)
+        x = x + F.linear(F.silu(g) * u, W[f"w_down.{l}"])
+    return F.linear(F.rms_norm(x, (cfg.d_model,), W["final_norm"], cfg.rms_eps), W["lm_head"]).numpy()
+
+
+def _cfg_and_weights(name, seed=1, std=0.08):
+    cfg = synth.MODELS[name]
+    w = synth.weights_to_numpy(cfg, synth.make_weights(cfg, seed, std=std))
+    return cfg, w
+
+
+@pytest.mark.parametrize("name", ["minif32", "mini64", "tiny"])
+def test_cached_block_forward_equals_library_full_causal_forward(name):
+    # weights with std 0.08 make attention and the MLP matter (with 0.02 the residual stream dominates)
+    cfg, w = _cfg_and_weights(name)
+    rng = np.random.default_rng(7)
+    L, n = 37, 6
+    toks = rng.integers(0, cfg.vocab, L + n).astype(np.int32)
+    want = library_full_forward(cfg, w, toks)
+    kc, vc = oracle.new_cache(cfg, L + n)
+    ctx_logits = oracle.forward(cfg, w, kc, vc, 0, toks[:L])          # "prefill": fills positions 0..L-1
+    blk_logits = oracle.forward(cfg, w, kc, vc, L, toks[L:])          # the draft block on the restored cache
+    scale = np.abs(want).max()
+    assert np.abs(ctx_logits - want[:L]).max() < 1e-9 * scale
+    assert np.abs(blk_logits - want[L:]).max() < 1e-9 * scale
+
+
+def test_token_by_token_equals_block():
+    cfg, w = _cfg_and_weights("minif32")
+    rng = np.random.default_rng(8)
+    toks = rng.integers(0, cfg.vocab, 20).astype(np.int32)
+    kc, vc = oracle.new_cache(cfg, 20)
+    one = oracle.forward(cfg, w, kc, vc, 0, toks)
+    kc2, vc2 = oracle.new_cache(cfg, 20)
+    rows = [oracle.forward(cfg, w, kc2, vc2, i, toks[i:i + 1])[0] for i in range(20)]
+    assert np.abs(np.stack(rows) - one).max() < 1e-10
+    assert np.abs(kc - kc2).max() < 1e-12 and np.abs(vc - vc2).max() < 1e-12
+
+
+def test_in_block_causality():
+    # logits of rows 0..j do not depend on the drafts after j
+    cfg, w = _cfg_and_weights("minif32")
+    rng = np.random.default_rng(9)
+    ctx = rng.integers(0, cfg.vocab, 11).astype(np.int32)
+    blk = rng.integers(0, cfg.vocab, 7).astype(np.int32)
+    kc, vc = oracle.new_cache(cfg, 32)
+    oracle.forward(cfg, w, kc, vc, 0, ctx)
+    full = oracle.forward(cfg, w, kc.copy(), vc.copy(), 11, blk)
+    for j in (0, 3):
+        part = oracle.forward(cfg, w, kc.copy(), vc.copy(), 11, blk[: j + 1])
+        assert np.array_equal(part, full[: j + 1])
+
+
+def test_stale_slots_beyond_valid_length_are_never_read():
+    # after a rollback the discarded positions still hold old values; a later call must ignore them
+    cfg, w = _cfg_and_weights("minif32")
+    rng = np.random.default_rng(10)
+    toks = rng.integers(0, cfg.vocab, 16).astype(np.int32)
+    kc, vc = oracle.new_cache(cfg, 24)
+    oracle.forward(cfg, w, kc, vc, 0, toks[:10])
+    k1, v1 = kc.copy(), vc.copy()
+    k1[:, 10:] = np.nan
+    v1[:, 10:] = np.nan
+    k2, v2 = kc.copy(), vc.copy()
+    k2[:, 10:] = 123.0
+    v2[:, 10:] = -7.0
+    a = oracle.forward(cfg, w, k1, v1, 10, toks[10:14])
+    b = oracle.forward(cfg, w, k2, v2, 10, toks[10:14])
+    assert np.isfinite(a).all() and np.array_equal(a, b)
+
+
+def test_verify_rollback_verify_equals_fresh_forward():
+    cfg, w = _cfg_and_weights("minif32")
+    rng = np.random.default_rng(11)
+    ctx = rng.integers(0, cfg.vocab, 9).astype(np.int32)
+    kc, vc = oracle.new_cache(cfg, 40)
+    oracle.forward(cfg, w, kc, vc, 0, ctx)
+    L, last, seq = 9, int(rng.integers(0, cfg.vocab)), list(ctx)
+    for rnd in range(3):
+        gamma = 4
+        d = rng.integers(0, cfg.vocab, gamma).astype(np.int32)
+        q = np.stack([synth.random_law(cfg.vocab, 2.0, 5, rnd * 10 + i).numpy() for i in range(gamma)])
+        r = oracle.verify(cfg, w, kc, vc, L, last, d, q, rng.uniform(0, 0.6, gamma), rng.uniform(), 1.0)
+        assert r.new_len == L + 1 + r.sample.tau
+        seq += [last] + list(d[: r.sample.tau])
+        L, last = r.new_len, r.sample.next_token
+        assert len(seq) == L
+    # the session now equals a fresh forward over the accepted sequence: same cache, same next-step logits
+    kf, vf = oracle.new_cache(cfg, 40)
+    oracle.forward(cfg, w, kf, vf, 0, np.array(seq, np.int32))
+    assert np.abs(kc[:, :L] - kf[:, :L]).max() < 1e-10 and np.abs(vc[:, :L] - vf[:, :L]).max() < 1e-10
+    nxt_a = oracle.forward(cfg, w, kc, vc, L, np.array([last], np.int32))
+    nxt_b = oracle.forward(cfg, w, kf, vf, L, np.array([last], np.int32))
+    assert np.abs(nxt_a - nxt_b).max() < 1e-10
+
+
+def test_closed_form_no_mixing_layers():
+    # W_o = 0 and W_down = 0 switch both sub-layers off: logits = RMSNorm(E[x]) W_lm^T, row by row
+    cfg, w = _cfg_and_weights("minif32")
+    w = dict(w)
+    for l in range(cfg.n_layers):
+        w[f"w_o.{l}"] = np.zeros_like(w[f"w_o.{l}"])
+        w[f"w_down.{l}"] = np.zeros_like(w[f"w_down.{l}"])
+    toks = np.array([5, 999, 0, 17], np.int32)
+    kc, vc = oracle.new_cache(cfg, 8)
+    got = oracle.forward(cfg, w, kc, vc, 2, toks)
+    e = w["embed"][toks].astype(np.float64)
+    nrm = e / np.sqrt((e * e).mean(1, keepdims=True) + cfg.rms_eps) * w["final_norm"].astype(np.float64)
+    want = nrm @ w["lm_head"].astype(np.float64).T
+    assert np.abs(got - want).max() < 1e-12
+
+
+def test_closed_form_uniform_attention_averages_values_over_the_causal_range():
+    # one layer, W_q = 0 -> all scores equal -> each head outputs the mean of V over keys 0..L+i.
+    # With W_o = identity and the MLP switched off the hidden state is E[x] + that mean.
+    cfg = dataclasses.replace(synth.MODELS["minif32"], n_layers=1, n_heads=4, n_kv_heads=2, head_dim=32, d_model=128)
+    w = synth.weights_to_numpy(cfg, synth.make_weights(cfg, 2, std=0.1))
+    qd, kvd = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    w["w_qkv.0"][:qd] = 0.0
+    w["w_o.0"] = np.eye(cfg.d_model, dtype=np.float32)
+    w["w_down.0"] = np.zeros_like(w["w_down.0"])
+    rng = np.random.default_rng(12)
+    L, n = 5, 4
+    kc, vc = oracle.new_cache(cfg, L + n)
+    kc[:, :L] = rng.normal(size=kc[:, :L].shape)
+    vc[:, :L] = rng.normal(size=vc[:, :L].shape)
+    toks = rng.integers(0, cfg.vocab, n).astype(np.int32)
+    _, hidden = oracle.forward(cfg, w, kc, vc, L, toks, want_hidden=True)
+    e = w["embed"][toks].astype(np.float64)
+    a = e / np.sqrt((e * e).mean(1, keepdims=True) + cfg.rms_eps) * w["attn_norm.0"].astype(np.float64)
+    v_new = a @ w["w_qkv.0"][qd + kvd:].astype(np.float64).T                       # [n, kvd]
+    assert np.abs(vc[0, L:L + n].reshape(n, kvd) - v_new).max() < 1e-12            # V append
+    group = cfg.n_heads // cfg.n_kv_heads
+    for i in range(n):
+        vals = vc[0, : L + i + 1]                                                  # keys 0 .. L+i
+        mean = vals.mean(0)                                                        # [Hkv, hd]
+        att = np.concatenate([mean[h // group] for h in range(cfg.n_heads)])
+        assert np.abs(hidden[i] - (e[i] + att)).max() < 1e-12
+
+
+def test_rope_is_a_rotation():
+    # rotary embedding preserves the norm of every key head written into the cache, and position 0 is
+    # not rotated at all (the relative-position property itself is pinned by the library comparison above)
+    cfg, w = _cfg_and_weights("minif32")
+    rng = np.random.default_rng(13)
+    toks = rng.integers(0, cfg.vocab, 12).astype(np.int32)
+    k0, v0 = oracle.new_cache(cfg, 12)
+    oracle.forward(cfg, w, k0, v0, 0, toks)
+    e = w["embed"][toks].astype(np.float64)
+    a = e / np.sqrt((e * e).mean(1, keepdims=True) + cfg.rms_eps) * w["attn_norm.0"].astype(np.float64)
+    qd, kvd = cfg.n_heads * cfg.head_dim, cfg.n_kv_heads * cfg.head_dim
+    k_plain = (a @ w["w_qkv.0"][qd:qd + kvd].astype(np.float64).T).reshape(12, cfg.n_kv_heads, cfg.head_dim)
+    assert np.abs(np.linalg.norm(k0[0], axis=-1) - np.linalg.norm(k_plain, axis=-1)).max() < 1e-12
+    assert np.abs(k0[0, 0] - k_plain[0]).max() < 1e-12
+    assert np.abs(k0[0, 5] - k_plain[5]).max() > 1e-3       # later positions are rotated
+
+
+def test_bf16_weights_are_widened_exactly():
+    cfg = synth.MODELS["mini64"]
+    wt = synth.make_weights(cfg, 3, std=0.05)
+    w16 = synth.weights_to_numpy(cfg, wt)
+    cfg32 = synth.with_dtype(cfg, "f32")
+    w32 = {k: v.float().numpy() for k, v in wt.items()}
+    toks = np.array([1, 2, 3000, 7], np.int32)
+    a = oracle.forward(cfg, w16, *oracle.new_cache(cfg, 4), 0, toks)
+    b = oracle.forward(cfg32, w32, *oracle.new_cache(cfg32, 4), 0, toks)
+    assert np.array_equal(a, b)

@@ -1,0 +1,232 @@
+"""Pins for the oracle's acceptance / resampling step (CPU only).
+
+The oracle is checked against what speculative sampling fixes, not against itself:
+the emitted tokens follow the target law (brute force over a tiny vocabulary), every
+draft is accepted when p == q, greedy mode is the longest argmax-matching prefix
+(Alg. 2), and hand-worked cases from tests/golden/.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle import oracle
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def _driver():
+    lib_path = os.path.join(HERE, "_brute_force.so")
+    src = os.path.join(HERE, "brute_force_sampler.c")
+    olib = oracle.build()
+    if not os.path.exists(lib_path) or os.path.getmtime(lib_path) < max(os.path.getmtime(src), os.path.getmtime(olib)):
+        subprocess.check_call(["gcc", "-O2", "-fPIC", "-shared", "-o", lib_path, src, olib,
+                               f"-Wl,-rpath,{os.path.dirname(olib)}", "-lm"])
+    lib = C.CDLL(lib_path)
+    lib.brute_force.restype = C.c_int
+    return lib
+
+
+def _level_offset(V, n):
+    return sum(V ** k for k in range(n))
+
+
+def _random_tables(V, gamma, seed, peaky):
+    """Target / draft laws for every prefix of length 0..gamma (rows of a prefix-coded table)."""
+    rng = np.random.default_rng(seed)
+    rows = _level_offset(V, gamma + 1)
+    p = rng.dirichlet(np.full(V, peaky), size=rows)
+    q = rng.dirichlet(np.full(V, peaky), size=rows)
+    q = np.maximum(q, 1e-3)
+    q /= q.sum(1, keepdims=True)
+    return p, q.astype(np.float32)
+
+
+@pytest.mark.parametrize("V,gamma,N,T", [(5, 1, 400, 1.0), (4, 2, 128, 1.0), (3, 3, 40, 1.0), (4, 2, 96, 0.7),
+                                         (6, 0, 4000, 1.3)])
+def test_output_law_equals_target_bruteforce(V, gamma, N, T):
+    p, q = _random_tables(V, gamma, seed=10 * V + gamma, peaky=2.0)
+    # the sampler sees logits and a temperature: hand it T * log p so that softmax(logits / T) == p
+    logits = T * np.log(p)
+    hist = np.zeros(_level_offset(V, gamma + 2), np.float64)
+    rc = _driver().brute_force(C.c_int(V), C.c_int(gamma), C.c_int(N), C.c_double(T),
+                               C.c_void_p(logits.ctypes.data), C.c_void_p(q.ctypes.data), C.c_void_p(hist.ctypes.data))
+    assert rc == 0
+    assert abs(hist.sum() - 1.0) < 1e-6      # q is stored in fp32
+    # a midpoint grid with N points misplaces at most 0.5/N of mass per uniform the step consumes
+    tol = 0.5 * (gamma + 1) / N
+    # mass[prefix] = P(the emitted sequence starts with prefix)
+    def emitted_mass(prefix):
+        n = len(prefix)
+        total = 0.0
+        for m in range(n, gamma + 2):      # sequences of length m that extend prefix
+            ext = m - n
+            base = 0
+            for t in prefix:
+                base = base * V + t
+            for e in range(V ** ext):
+                total += hist[_level_offset(V, m) + base * V ** ext + e]
+        return total
+
+    checked = 0
+    for n in range(0, gamma + 1):          # position n+1 of the emitted sequence, given n emitted tokens
+        for code in range(V ** n):
+            prefix = []
+            c = code
+            for _ in range(n):
+                prefix.insert(0, c % V)
+                c //= V
+            joint = np.array([emitted_mass(prefix + [b]) for b in range(V)])
+            # only draft sequences that start with this prefix can emit it, so the grid error scales with
+            # the draft chain's probability of the prefix
+            wq, c2 = 1.0, 0
+            for k, t in enumerate(prefix):
+                wq *= float(q[_level_offset(V, k) + c2][t])
+                c2 = c2 * V + t
+            if joint.sum() < 8 * tol * wq:
+                continue                  # prefix accepted too rarely for the grid to resolve
+            cond = joint / joint.sum()
+            want = p[_level_offset(V, n) + code]
+            assert np.abs(cond - want).max() < 2 * tol * wq / joint.sum() + 1e-9, (prefix, cond, want)
+            checked += 1
+    print("prefixes checked:", checked)
+    assert checked >= (1 if gamma == 0 else 1 + V)      # the root and most one-token prefixes at least
+
+
+def test_first_token_law_when_draft_is_wrong_everywhere():
+    # a draft law that puts almost everything on one token the target dislikes: output must still follow p
+    V, gamma, N = 4, 1, 2000
+    p = np.tile(np.array([0.05, 0.15, 0.3, 0.5]), (1 + V, 1))
+    q = np.tile(np.array([0.97, 0.01, 0.01, 0.01], np.float32), (1 + V, 1))
+    hist = np.zeros(_level_offset(V, 3), np.float64)
+    lg = np.log(p)
+    assert _driver().brute_force(C.c_int(V), C.c_int(gamma), C.c_int(N), C.c_double(1.0), C.c_void_p(lg.ctypes.data),
+                                 C.c_void_p(q.ctypes.data), C.c_void_p(hist.ctypes.data)) == 0
+    first = np.array([hist[1 + b] + hist[1 + V + b * V: 1 + V + (b + 1) * V].sum() for b in range(V)])
+    assert np.abs(first - p[0]).max() < 3.0 / N
+
+
+def test_all_accepted_when_p_equals_q():
+    # equal logits over a power-of-two vocabulary give p = 1/V exactly, and q = 1/V is exact in fp32
+    V, gamma = 64, 6
+    logits = np.zeros((gamma + 1, V))
+    q = np.full((gamma, V), 1.0 / V, np.float32)
+    rng = np.random.default_rng(0)
+    for trial in range(50):
+        d = rng.integers(0, V, gamma)
+        u = rng.integers(0, 1 << 24, gamma) / float(1 << 24)
+        if trial == 0:
+            u[:] = 1.0 - 2.0 ** -24        # the largest uniform the generator can emit
+        if trial == 1:
+            u[:] = 0.0
+        r = oracle.sample(logits, d, q, u, 0.5, 1.0)
+        assert r.tau == gamma and not r.used_residual
+        assert r.next_token == 32             # bonus token from p: cumulative 33/64 is the first > 0.5
+    # also when the draft law is a hair below the target everywhere it matters
+    r = oracle.sample(logits, d, q * np.float32(0.999), u, 0.0, 1.0)
+    assert r.tau == gamma and r.next_token == 0
+
+
+def test_greedy_is_longest_argmax_prefix():
+    V, gamma = 11, 5
+    rng = np.random.default_rng(3)
+    for trial in range(200):
+        logits = rng.normal(size=(gamma + 1, V))
+        am = logits.argmax(1)
+        d = am[:gamma].copy()
+        k = rng.integers(0, gamma + 1)      # first mismatch position (gamma = none)
+        if k < gamma:
+            d[k] = (am[k] + 1 + rng.integers(0, V - 1)) % V
+            d[k + 1:] = rng.integers(0, V, gamma - k - 1)
+        r = oracle.sample(logits, d, None, np.zeros(gamma), 0.3, 0.0)
+        want_tau = k
+        # drafts after the first mismatch may match by luck, they must not count
+        assert r.tau == want_tau and r.next_token == am[want_tau]
+
+
+def test_greedy_ties_take_lowest_index():
+    logits = np.array([[0.0, 2.0, 2.0, 1.0], [3.0, 3.0, 3.0, 3.0]])
+    r = oracle.sample(logits, [1], None, [0.0], 0.0, 0.0)
+    assert r.tau == 1 and r.next_token == 0
+    r = oracle.sample(logits, [2], None, [0.0], 0.0, 0.0)
+    assert r.tau == 0 and r.next_token == 1
+
+
+def test_small_temperature_with_one_hot_draft_reproduces_greedy():
+    V, gamma = 9, 4
+    rng = np.random.default_rng(5)
+    for trial in range(100):
+        logits = rng.normal(size=(gamma + 1, V)) * 3
+        d = logits.argmax(1)[:gamma].copy()
+        k = rng.integers(0, gamma + 1)
+        if k < gamma:
+            d[k] = (d[k] + 1) % V
+        q = np.zeros((gamma, V), np.float32)
+        q[np.arange(gamma), d] = 1.0
+        u = rng.uniform(0.001, 0.999, gamma)
+        g = oracle.sample(logits, d, None, u, 0.5, 0.0)
+        s = oracle.sample(logits, d, q, u, rng.uniform(0.001, 0.999), 1e-3)
+        assert (s.tau, s.next_token) == (g.tau, g.next_token)
+
+
+def _golden_cases():
+    path = os.path.join(HERE, "golden", "sampler_worked_cases.txt")
+    for line in open(path):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        name, p, q, d, ua, us, tau, nxt = [f.strip() for f in line.split("|")]
+        rows = lambda s: np.array([[float(x) for x in r.split(",")] for r in s.split(";")])
+        yield name, rows(p), rows(q).astype(np.float32), [int(x) for x in d.split(",")], \
+            [float(x) for x in ua.split(",")], float(us), int(tau), int(nxt)
+
+
+@pytest.mark.parametrize("case", list(_golden_cases()), ids=lambda c: c[0])
+def test_hand_worked_cases(case):
+    name, p, q, d, ua, us, tau, nxt = case
+    for T in (1.0, 0.5):
+        r = oracle.sample(T * np.log(p), d, q, ua, us, T)
+        assert (r.tau, r.next_token) == (tau, nxt), name
+
+
+def test_zero_draft_request_is_plain_sampling():
+    # gamma = 0: one row, the emitted token is an ordinary inverse-CDF draw from p
+    p = np.array([[0.125, 0.125, 0.25, 0.5]])
+    lg = np.log(p)
+    for u, want in [(0.0, 0), (0.124, 0), (0.126, 1), (0.3, 2), (0.51, 3), (0.999, 3)]:
+        r = oracle.sample(lg, [], None, [], u, 1.0)
+        assert r.tau == 0 and r.next_token == want
+
+
+def test_margins_report_distance_to_thresholds():
+    p = np.array([[0.5, 0.3, 0.2], [0.25, 0.25, 0.5]])
+    q = np.array([[0.2, 0.5, 0.3]], np.float32)
+    r = oracle.sample(np.log(p), [1], q, [0.59], 0.60, 1.0)      # a = 0.6
+    assert abs(r.accept_margin - 0.01) < 1e-6
+    assert abs(r.cdf_margin - 0.10) < 1e-6                          # 0.60 sits 0.10 above the edge at 0.5
+    assert abs(r.accept_prob[0] - 0.6) < 1e-6
+
+
+def test_rollback_worked_cases():
+    path = os.path.join(HERE, "golden", "rollback_worked_cases.txt")
+    n = 0
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        L, g, tau, page, new_len, rel = [int(x) for x in line.split()]
+        assert oracle.rollback(L, g, tau, page) == (new_len, rel), line
+        n += 1
+    assert n >= 10
+
+
+def test_accept_test_is_strict():
+    # equal logits over two tokens give p = 1/2 exactly; a draft law that is certain of its token gives
+    # ratio exactly 1/2: the draft is accepted iff u < 1/2
+    logits = np.zeros((2, 2))
+    q = np.array([[1.0, 0.0]], np.float32)
+    assert oracle.sample(logits, [0], q, [0.5], 0.1, 1.0).tau == 0
+    assert oracle.sample(logits, [0], q, [0.5 - 2.0 ** -24], 0.1, 1.0).tau == 1
+    # rejected: residual is max(0, p - q) = (0, 1/2) -> token 1 for every u_sample
+    assert oracle.sample(logits, [0], q, [0.5], 0.0, 1.0).next_token == 1
