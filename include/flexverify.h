@@ -1,0 +1,220 @@
+/*
+ * flexverify — the cloud-side verification step of FlexSpec (Alg. 2 step 2, Sec. IV-C)
+ * for one AMD MI355X (gfx950).
+ *
+ * One call of fsv_verify() does, for a whole batch of edge requests, what Alg. 2 does
+ * between "receive x_draft and restore KV cache" and "transmit x_verified": the target
+ * model scores the pending token and the gamma_b received draft tokens of every request in
+ * one pass on top of that user's persistent KV session (Sec. IV-C: KV pairs are computed
+ * only for the newly received tokens), the drafts are accepted or rejected, the correction
+ * (or bonus) token is chosen, and the KV pairs of rejected positions are rolled back.
+ *
+ * Conventions
+ *   - Plain C ABI.  Every pointer is marked HOST or DEVICE.  Device memory is owned by the
+ *     caller unless stated otherwise; the library owns only what fsv_create() allocates
+ *     (re-tiled weights and a workspace sized from fsv_model_desc).
+ *   - Calls that take a stream enqueue their work on that HIP stream (hipStream_t passed as
+ *     void*, NULL = the null stream) and return without waiting for the GPU; results are
+ *     valid once the stream has been synchronised.  No call reads device memory back to the
+ *     host; where the host needs values to size launches it takes HOST copies from the caller.
+ *   - Every function that can fail returns 0 (FSV_OK) or a negative fsv_status.  On failure
+ *     nothing has been launched.  No exceptions cross the boundary.
+ *   - Random numbers are inputs (uniforms in [0,1)), never drawn inside the library.
+ *   - A context is not thread safe: calls on one context must not overlap (they share its
+ *     workspace), neither on the host nor on different streams.
+ */
+#ifndef FLEXVERIFY_H
+#define FLEXVERIFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct fsv_ctx fsv_ctx;
+
+typedef enum { FSV_F32 = 0, FSV_BF16 = 1 } fsv_dtype;
+
+typedef enum {
+  FSV_OK = 0,
+  FSV_E_INVALID_ARG = -1, /* NULL pointer, negative size, inconsistent CSR, token id out of range ...   */
+  FSV_E_CAPACITY = -2,    /* batch, gamma, pages or rows beyond what the context was created for        */
+  FSV_E_UNSUPPORTED = -3, /* shape the kernels do not cover (see fsv_create)                            */
+  FSV_E_HIP = -4,         /* a HIP runtime call failed (allocation, launch)                             */
+  FSV_E_NO_MODEL = -5     /* a model call on a sampler-only context                                     */
+} fsv_status;
+
+/*
+ * Target model M_t' (Llama-style pre-norm decoder: RMSNorm, rotary embedding with half-split
+ * pairing (i, i + head_dim/2), grouped-query attention, SwiGLU MLP, untied LM head, no biases)
+ * and the capacity of the context.
+ */
+typedef struct {
+  int32_t n_layers;          /* 0 = sampler-only context (fsv_sample / fsv_rollback only)            */
+  int32_t d_model, n_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  int32_t dtype;             /* fsv_dtype of weights, activations and KV cache                        */
+  float rms_eps, rope_theta;
+  int32_t page_size;         /* positions per KV page; must be 16                                     */
+  int32_t max_batch;         /* requests per call                                                     */
+  int32_t max_gamma;         /* drafts per request, <= 16                                             */
+  int32_t max_pages_per_req; /* columns of the page table                                             */
+  int32_t max_rows;          /* sum over requests of (gamma_b + 1); 0 = max_batch * (max_gamma + 1)   */
+} fsv_model_desc;
+
+/*
+ * Weights.  DEVICE pointers to row-major [out_features][in_features] matrices of the model's
+ * dtype; the per-layer members are HOST arrays of n_layers DEVICE pointers.  fsv_create() reads
+ * them once (it copies fp32 weights and re-tiles bf16 matrices into the operand order of the
+ * matrix cores); the caller may free all of them when fsv_create() has returned.
+ */
+typedef struct {
+  const void *embed;             /* [vocab][d_model]                                          */
+  const void *final_norm;        /* [d_model]                                                 */
+  const void *lm_head;           /* [vocab][d_model]                                          */
+  const void *const *attn_norm;  /* [d_model]                                                 */
+  const void *const *w_qkv;      /* [(n_heads + 2 n_kv_heads) head_dim][d_model]: Wq | Wk | Wv */
+  const void *const *w_o;        /* [d_model][n_heads head_dim]                               */
+  const void *const *mlp_norm;   /* [d_model]                                                 */
+  const void *const *w_gate_up;  /* [2 d_ffn][d_model]: gate | up                             */
+  const void *const *w_down;     /* [d_model][d_ffn]                                          */
+} fsv_weights;
+
+/*
+ * One batch of requests.  B = batch, G = total drafts, M = G + B rows.  Request b has
+ * gamma_b = draft_offsets[b+1] - draft_offsets[b] drafts; its input rows are the pending token
+ * last_token[b] at position seq_lens[b] followed by its drafts at the next positions.
+ *
+ * KV pools: k_pool and v_pool each hold n_layers * num_pages * n_kv_heads page tiles of
+ * page_size * head_dim elements, indexed [layer][physical page][kv head].  Inside a tile
+ *   FSV_F32 : [position in page][head_dim] for both pools;
+ *   FSV_BF16: the order in which the matrix cores consume it, see fsv_kv_import().
+ * Use fsv_kv_import()/fsv_kv_export() to move sessions in and out; do not index tiles directly.
+ * The call appends the KV pairs of all M rows (positions seq_lens[b] .. seq_lens[b]+gamma_b).
+ */
+typedef struct {
+  int32_t batch;
+  int32_t num_pages;                 /* physical pages per layer in each pool                         */
+  const int32_t *seq_lens;           /* DEVICE [B]   L_b, cached positions before the call            */
+  const int32_t *seq_lens_host;      /* HOST   [B]   same values                                      */
+  const int32_t *last_token;         /* DEVICE [B]                                                    */
+  const int32_t *draft_offsets;      /* DEVICE [B+1] CSR over drafts                                  */
+  const int32_t *draft_offsets_host; /* HOST   [B+1] same values                                      */
+  const int32_t *draft_tokens;       /* DEVICE [G]                                                    */
+  const float *draft_probs;          /* DEVICE [G][vocab] q_{b,i}(.), the law draft i was drawn from;
+                                        may be NULL when every temperature is 0                       */
+  const float *u_accept;             /* DEVICE [G]   uniforms in [0,1) for the acceptance tests       */
+  const float *u_sample;             /* DEVICE [B]   uniform for the correction / bonus token         */
+  const float *temperature;          /* DEVICE [B]   T_b > 0: speculative sampling on softmax(l/T_b);
+                                                     T_b = 0: greedy (argmax match, Alg. 2)          */
+  const float *temperature_host;     /* HOST   [B]   same values (NULL = all positive)                */
+  const int32_t *page_table;         /* DEVICE [B][max_pages_per_req] physical page of each logical
+                                        page; must cover positions < seq_lens[b] + gamma_b + 1        */
+  void *k_pool, *v_pool;             /* DEVICE, read and written                                      */
+} fsv_batch;
+
+typedef struct {
+  int32_t *accepted_len;   /* DEVICE [B] tau_b in [0, gamma_b]                                        */
+  int32_t *next_token;     /* DEVICE [B] correction token (tau_b < gamma_b) or bonus token            */
+  int32_t *new_seq_lens;   /* DEVICE [B] seq_lens[b] + 1 + tau_b: valid KV positions after rollback   */
+  int32_t *pages_released; /* DEVICE [B] tail pages that hold no valid position any more              */
+  uint32_t *flags;         /* DEVICE [B] bit0: some tested draft had |u - min(1,p/q)| < 1e-4;
+                                         bit1: the emitted token's CDF edge is within 1e-6 of u_sample;
+                                         bit2: the token was drawn from the residual max(0, p - q)    */
+  float *logits_out;       /* DEVICE [M][vocab] fp32 target logits, or NULL                           */
+} fsv_result;
+
+/*
+ * Create a context: validate the description, copy / re-tile the weights, allocate the workspace.
+ * Supported shapes: page_size 16; head_dim 64 or 128 for FSV_BF16 (any even head_dim for FSV_F32);
+ * n_heads a multiple of n_kv_heads with n_heads / n_kv_heads * (max_gamma + 1) <= 96;
+ * d_model, d_ffn and n_heads*head_dim multiples of 128 for FSV_BF16.
+ * weights may be NULL only when n_layers == 0.
+ */
+int fsv_create(const fsv_model_desc *desc, const fsv_weights *weights, fsv_ctx **out);
+void fsv_destroy(fsv_ctx *ctx);
+
+/*
+ * The verification step (Alg. 2 step 2 with the KV append / rollback of Sec. IV-C) for a batch.
+ * For T_b > 0 the acceptance rule is speculative sampling, which keeps the law of the emitted
+ * tokens equal to the target model's (Sec. II; Regime B of Sec. V): draft i is accepted iff
+ * u_i < min(1, p_{i-1}(d_i) / q_i(d_i)) with p = softmax(logits / T_b); after the first rejection
+ * at i = tau+1 the token is drawn by inverse CDF (ascending token id, first id whose inclusive
+ * running mass exceeds u_sample * total) from max(0, p_tau - q_{tau+1}); when all drafts pass,
+ * from p_gamma.  For T_b = 0: accept while d_i == argmax, emit the argmax (lowest id on ties).
+ */
+int fsv_verify(fsv_ctx *ctx, const fsv_batch *batch, const fsv_result *result, void *stream);
+
+/*
+ * The accept / resample step alone on caller-provided target logits (DEVICE [M][vocab], row
+ * draft_offsets[b] + b + i scores the token after input row i of request b; dtype FSV_BF16 or
+ * FSV_F32).  Uses from batch: batch, draft_offsets(+_host), draft_tokens, draft_probs, u_accept,
+ * u_sample, temperature(+_host).  Writes accepted_len, next_token, flags.
+ */
+int fsv_sample(fsv_ctx *ctx, const void *logits, int32_t logits_dtype, const fsv_batch *batch,
+               const fsv_result *result, void *stream);
+
+/*
+ * KV rollback alone (Sec. IV-C): from seq_lens, draft_offsets and accepted_len (DEVICE [B])
+ * compute new_seq_lens and pages_released.  Discarded positions keep stale bytes that no later
+ * call reads; the caller returns released pages to its allocator.
+ */
+int fsv_rollback(fsv_ctx *ctx, const fsv_batch *batch, const int32_t *accepted_len,
+                 const fsv_result *result, void *stream);
+
+/*
+ * Restore / save a user's KV session (Alg. 2 "restore KV cache").  src_k / src_v (dst for
+ * export) are DEVICE arrays [n_layers][n_pos][n_kv_heads][head_dim] of the model's dtype holding
+ * positions pos0 .. pos0+n_pos-1; page_table_row is the DEVICE page-table row of the request.
+ * For FSV_BF16 a K tile stores element (t, e) (position t in page, feature e) at
+ * ((e/16*2 + (e%16)/8)*16 + t)*8 + e%8 and a V tile at ((e/32*2 + (t%8)/4)*32 + e%32)*8 + 4*(t/8) + t%4.
+ */
+int fsv_kv_import(fsv_ctx *ctx, void *k_pool, void *v_pool, int32_t num_pages, const int32_t *page_table_row,
+                  int32_t pos0, int32_t n_pos, const void *src_k, const void *src_v, void *stream);
+int fsv_kv_export(fsv_ctx *ctx, const void *k_pool, const void *v_pool, int32_t num_pages,
+                  const int32_t *page_table_row, int32_t pos0, int32_t n_pos, void *dst_k, void *dst_v,
+                  void *stream);
+
+/*
+ * Single kernels of the step, exposed for parity tests and roofline measurements.
+ * fsv_linear: y[M][N] (fp32, DEVICE) = x[M][K] (model dtype, row-major, DEVICE) times the re-tiled
+ *   weight matrix `which` of `layer` (FSV_W_* below; layer ignored for FSV_W_LM_HEAD), through the
+ *   same weight-streaming GEMM kernel fsv_verify uses.  M <= max_rows.
+ * fsv_attention: out[M][n_heads*head_dim] (fp32, DEVICE) for queries q[M][n_heads][head_dim] (model
+ *   dtype, already rotated) over the paged KV of `layer`; row i of request b attends to positions
+ *   0 .. seq_lens[b] + i.  Uses from batch: batch, num_pages, seq_lens(+_host), draft_offsets(+_host),
+ *   page_table, k_pool, v_pool.
+ */
+enum { FSV_W_QKV = 0, FSV_W_O = 1, FSV_W_GATE_UP = 2, FSV_W_DOWN = 3, FSV_W_LM_HEAD = 4 };
+int fsv_linear(fsv_ctx *ctx, int32_t which, int32_t layer, const void *x, int32_t M, float *y, void *stream);
+int fsv_attention(fsv_ctx *ctx, int32_t layer, const void *q, const fsv_batch *batch, float *out, void *stream);
+
+/*
+ * Per-kernel timing with HIP events on the call's stream.  fsv_profile_enable(ctx, 1) makes every
+ * later fsv_verify / fsv_sample / fsv_linear / fsv_attention record an event pair around each launch
+ * of the kernel classes below (bounded ring, oldest dropped); fsv_profile_read() waits for the
+ * recorded events and returns, per class, the number of launches and their summed duration, then
+ * clears the ring.  Returns the number of classes written (<= cap).
+ */
+enum { FSV_K_GEMM_QKV = 0, FSV_K_GEMM_O, FSV_K_GEMM_GATE_UP, FSV_K_GEMM_DOWN, FSV_K_GEMM_LM_HEAD,
+       FSV_K_ATTENTION, FSV_K_ATTN_COMBINE, FSV_K_SAMPLE_STATS, FSV_K_SAMPLE_ACCEPT, FSV_K_SAMPLE_SELECT,
+       FSV_K_NORM, FSV_K_ROPE_APPEND, FSV_K_OTHER, FSV_K_COUNT };
+typedef struct {
+  int32_t kernel_class; /* FSV_K_*                       */
+  int32_t launches;
+  double total_ms;      /* sum of event-to-event times   */
+  double bytes;         /* algorithmic bytes of those launches as the host computed them at launch  */
+} fsv_kernel_time;
+int fsv_profile_enable(fsv_ctx *ctx, int32_t on);
+int fsv_profile_read(fsv_ctx *ctx, fsv_kernel_time *out, int32_t cap);
+const char *fsv_kernel_class_name(int32_t kernel_class);
+
+const char *fsv_strerror(int status);
+/* Last failure's detail message for this context (HOST string owned by the context). */
+const char *fsv_last_error(const fsv_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLEXVERIFY_H */

@@ -1,0 +1,135 @@
+// Internal declarations shared by the translation units of libflexverify (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+#include <vector>
+
+#include "flexverify.h"
+
+#define FSV_WAVE 64
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;   // one MFMA A/B operand (8 bf16 per lane)
+typedef __attribute__((ext_vector_type(16))) float f32x16_t;   // one 32x32 MFMA accumulator
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+// ---- sampler geometry -------------------------------------------------------------------------
+// A vocabulary row is cut into sub-blocks of SBK ids (256 threads x 8 consecutive ids) and chunks
+// of SPC sub-blocks; the statistics kernel keeps one (max, sum) pair per chunk, the mass kernel one
+// sum per sub-block.
+#define FSV_SBK 2048
+#define FSV_SPC 4
+#define FSV_CHUNK (FSV_SBK * FSV_SPC)
+
+struct fsv_prof_rec {
+  int cls;
+  double bytes;
+  hipEvent_t e0, e1;
+};
+
+struct fsv_layer_w {
+  // fp32 path: plain copies [out][in]; bf16 path: re-tiled matrices, plain gains
+  void *attn_norm = nullptr, *w_qkv = nullptr, *w_o = nullptr, *mlp_norm = nullptr, *w_gate_up = nullptr,
+       *w_down = nullptr;
+};
+
+struct fsv_ctx {
+  fsv_model_desc d{};
+  int max_rows = 0;
+  int group = 1;          // query heads per KV head
+  int nc = 0;             // vocabulary chunks per row
+  int nsb = 0;            // vocabulary sub-blocks per row
+  std::string err;
+
+  // weights (library-owned)
+  void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
+  std::vector<fsv_layer_w> layers;
+  float *inv_freq = nullptr;        // [head_dim/2] rotary frequencies (bf16 path)
+
+  // row map, built per call on the device
+  int32_t *row_req = nullptr, *row_idx = nullptr, *row_pos = nullptr, *row_tok = nullptr;
+
+  // sampler workspace
+  float *pmax = nullptr;    // [max_rows][nc]
+  double *psum = nullptr;   // [max_rows][nc]
+  int32_t *parg = nullptr;  // [max_rows][nc]
+  double *bsum = nullptr;   // [max_batch][nsb]
+  int32_t *tau_ws = nullptr;   // [max_batch]
+  double *rowstat = nullptr;   // [max_batch][2]: max (as double), 1/S of the row the token is drawn from
+  int32_t *acc_scratch = nullptr;  // [max_batch] accepted_len when the caller passes none
+
+  // model workspace (both paths)
+  float *x = nullptr;       // [rows_pad][d_model] residual stream, fp32
+  float *logits = nullptr;  // [max_rows][vocab] fp32 when the caller passes no logits_out
+  void *buf_a = nullptr, *buf_qkv = nullptr, *buf_q = nullptr, *buf_att = nullptr, *buf_gu = nullptr,
+       *buf_act = nullptr, *buf_part = nullptr;
+  size_t part_bytes = 0;
+  void *attn_part = nullptr;    // split-KV partial results
+  size_t attn_part_bytes = 0;
+  int attn_max_splits = 0;
+
+  // profiling
+  bool prof_on = false;
+  std::vector<fsv_prof_rec> prof;
+};
+
+#define FSV_FAIL(ctx, code, ...)                                   \
+  do {                                                             \
+    char _b[512];                                                  \
+    snprintf(_b, sizeof _b, __VA_ARGS__);                          \
+    if (ctx) (ctx)->err = _b;                                      \
+    return (code);                                                 \
+  } while (0)
+
+#define FSV_HIP(ctx, call)                                                                  \
+  do {                                                                                      \
+    hipError_t _e = (call);                                                                 \
+    if (_e != hipSuccess) FSV_FAIL(ctx, FSV_E_HIP, "%s: %s", #call, hipGetErrorString(_e)); \
+  } while (0)
+
+// scoped event pair around one kernel class (no-op unless profiling is on)
+struct fsv_prof_scope {
+  fsv_ctx *c;
+  hipStream_t s;
+  fsv_prof_rec r{};
+  bool on;
+  fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes) : c(ctx), s(st), on(ctx->prof_on) {
+    if (!on) return;
+    if (c->prof.size() >= 8192) { on = false; return; }
+    r.cls = cls;
+    r.bytes = bytes;
+    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) { on = false; return; }
+    (void)hipEventRecord(r.e0, s);
+  }
+  ~fsv_prof_scope() {
+    if (!on) return;
+    (void)hipEventRecord(r.e1, s);
+    c->prof.push_back(r);
+  }
+};
+
+static inline int fsv_ceil_div(int a, int b) { return (a + b - 1) / b; }
+
+// ---- entry points of the other translation units ----------------------------------------------
+// sampler.hip
+int fsv_launch_build_rows(fsv_ctx *c, const fsv_batch *b, int M, hipStream_t s);
+int fsv_launch_sampler(fsv_ctx *c, const void *logits, int logits_dtype, const fsv_batch *b, const fsv_result *r,
+                       int M, bool with_rollback, hipStream_t s);
+int fsv_launch_rollback(fsv_ctx *c, const fsv_batch *b, const int32_t *accepted, const fsv_result *r, hipStream_t s);
+// path_f32.hip
+int fsv_f32_create(fsv_ctx *c, const fsv_weights *w);
+int fsv_f32_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);
+int fsv_f32_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float *y, hipStream_t s);
+int fsv_f32_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s);
+int fsv_f32_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,
+                    void *k_lin, void *v_lin, bool import, hipStream_t s);
+// path_bf16.hip
+int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
+int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);
+int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float *y, hipStream_t s);
+int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s);
+int fsv_bf16_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,
+                     void *k_lin, void *v_lin, bool import, hipStream_t s);
+void fsv_free_weights(fsv_ctx *c);

@@ -1,0 +1,140 @@
+"""GPU parity of the accept / resample step (fsv_sample) against the oracle on identical logits.
+
+Logits are seeded inputs (the rejection-sampling configuration: bf16 logits ~ N(0,3), fp32 draft
+laws from noised logits, ragged gamma), so both sides see the same bits.  Bar: accepted lengths and
+emitted tokens match exactly, except draws the oracle places within 1e-4 of an acceptance threshold
+(or within 1e-6 of a CDF edge), which are counted.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2601_00644_amd import synth
+from tests.helpers import compare_decisions
+
+pytestmark = pytest.mark.gpu
+
+
+def _ctx(vocab, max_batch, max_gamma):
+    from paper_2601_00644_amd import flexverify as fv
+    cfg = synth.ModelCfg("sampler", 0, 0, 0, 0, 0, 0, vocab, "bf16")
+    return fv, fv.Context(cfg, None, max_batch, max_gamma, sampler_only=True)
+
+
+def _run(fv, ctx, case, temperature=None):
+    B = len(case.draft_offsets) - 1
+    temp = case.temperature if temperature is None else np.asarray(temperature, np.float32)
+    dev = "cuda"
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device=dev)
+    batch = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs.to(dev),
+                           t(case.u_accept), t(case.u_sample), t(temp), None, None, None, 0, None,
+                           np.ascontiguousarray(case.draft_offsets), np.ascontiguousarray(temp))
+    res = fv.DeviceResult.alloc(B)
+    ctx.sample(case.logits.to(dev), batch, res)
+    torch.cuda.synchronize()
+    return res.accepted_len.cpu().numpy(), res.next_token.cpu().numpy(), res.flags.cpu().numpy()
+
+
+def _oracle(case, temperature=None):
+    B = len(case.draft_offsets) - 1
+    out = []
+    lg = case.logits.float().numpy().astype(np.float64)
+    q = case.draft_probs.numpy()
+    for b in range(B):
+        o, e = int(case.draft_offsets[b]), int(case.draft_offsets[b + 1])
+        T = float(case.temperature[b] if temperature is None else temperature[b])
+        s = oracle.sample(lg[o + b: e + b + 1], case.draft_tokens[o:e], q[o:e], case.u_accept[o:e],
+                          float(case.u_sample[b]), T)
+        out.append(type("R", (), {"sample": s})())
+    return out
+
+
+@pytest.mark.parametrize("vocab,batch,gmax,sigma,dtype,seed", [
+    (4096, 5, 4, 0.5, "bf16", 1),          # exactly two sub-blocks
+    (5000, 9, 8, 0.7, "bf16", 2),          # ragged tail, vector loads still aligned
+    (5003, 7, 6, 1.0, "f32", 3),           # odd vocabulary: scalar loads
+    (30000, 6, 16, 0.3, "f32", 4),         # several chunks, gamma at the maximum
+    (152064, 12, 16, 1.5, "bf16", 5),      # the full vocabulary of the sampling configuration
+])
+def test_sampler_matches_oracle(vocab, batch, gmax, sigma, dtype, seed):
+    fv, ctx = _ctx(vocab, batch, 16)
+    case = synth.make_sampler_case(batch, 1, gmax, vocab, sigma, 0.7, seed, logits_dtype=dtype)
+    tau, nxt, flags = _run(fv, ctx, case)
+    exp = _oracle(case)
+    bad, excused, flagged = compare_decisions(exp, tau, nxt)
+    print(f"V={vocab} B={batch}: acceptance {tau.sum()}/{case.draft_offsets[-1]}, flagged {flagged}, excused {excused}")
+    assert not bad, bad
+    # the library's own residual flag agrees with the oracle wherever the decision matched
+    for b, e in enumerate(exp):
+        if int(tau[b]) == e.sample.tau and e.sample.accept_margin > 1e-4:
+            assert bool(flags[b] & 4) == e.sample.used_residual
+    ctx.close()
+
+
+def test_greedy_and_mixed_temperatures():
+    vocab, batch = 9000, 10
+    fv, ctx = _ctx(vocab, batch, 16)
+    case = synth.make_sampler_case(batch, 0, 6, vocab, 0.2, 1.0, 11, logits_dtype="bf16")
+    # bf16 logits over 9000 ids do tie: the lowest id must win on both sides
+    temp = np.array([0.0, 1.0] * 5, np.float32)
+    # make drafts of greedy requests follow the argmax for a while
+    lg = case.logits.float().numpy()
+    for b in range(0, batch, 2):
+        o, e = int(case.draft_offsets[b]), int(case.draft_offsets[b + 1])
+        for i in range(e - o):
+            if i < 2:
+                case.draft_tokens[o + i] = int(lg[o + b + i].argmax())
+    tau, nxt, flags = _run(fv, ctx, case, temp)
+    exp = _oracle(case, temp)
+    bad, excused, flagged = compare_decisions(exp, tau, nxt)
+    assert not bad, bad
+    for b in range(0, batch, 2):
+        assert int(tau[b]) == exp[b].sample.tau and int(nxt[b]) == exp[b].sample.next_token   # integer work: exact
+        assert flags[b] == 0
+    ctx.close()
+
+
+def test_all_accepted_when_p_equals_q_and_zero_residual_falls_back_to_p():
+    vocab, batch, gamma = 4096, 4, 5
+    fv, ctx = _ctx(vocab, batch, 16)
+    off = np.arange(batch + 1, dtype=np.int32) * gamma
+    G, M = batch * gamma, batch * (gamma + 1)
+    logits = torch.zeros((M, vocab), dtype=torch.float32)           # p = 1/4096 exactly
+    q = torch.full((G, vocab), 1.0 / vocab, dtype=torch.float32)
+    q[gamma:2 * gamma] *= 1.0 + 2.0 ** -10                           # request 1: q a hair above p everywhere
+    rng = np.random.default_rng(0)
+    u = (rng.integers(0, 1 << 24, G) / float(1 << 24)).astype(np.float32)
+    u[:gamma] = 1.0 - 2.0 ** -24
+    u[gamma] = 1.0 - 2.0 ** -24                                      # request 1 rejects its first draft
+    case = synth.SamplerCase(logits, q, rng.integers(0, vocab, G).astype(np.int32), off, u,
+                             np.array([0.5, 0.25, 0.0, 0.999], np.float32), np.ones(batch, np.float32))
+    tau, nxt, flags = _run(fv, ctx, case)
+    exp = _oracle(case)
+    assert list(tau) == [gamma, 0, gamma, gamma]
+    assert [e.sample.tau for e in exp] == list(tau)
+    assert [e.sample.next_token for e in exp] == list(nxt)
+    assert nxt[0] == 2048 and nxt[1] == 1024 and nxt[2] == 0
+    assert not (flags[1] & 4) and not exp[1].sample.used_residual    # no residual mass: drawn from p
+    ctx.close()
+
+
+def test_empty_batch_and_capacity_errors():
+    fv, ctx = _ctx(4096, 4, 8)
+    case = synth.make_sampler_case(4, 1, 4, 4096, 0.5, 0.7, 21)
+    # gamma beyond the context's capacity is refused on the host, nothing is launched
+    big = synth.make_sampler_case(4, 9, 9, 4096, 0.5, 0.7, 22)
+    with pytest.raises(fv.FsvError) as ei:
+        _run(fv, ctx, big)
+    assert ei.value.status == -2
+    big5 = synth.make_sampler_case(5, 1, 2, 4096, 0.5, 0.7, 23)
+    with pytest.raises(fv.FsvError) as ei:
+        _run(fv, ctx, big5)
+    assert ei.value.status == -2
+    # an empty batch is a no-op
+    empty = synth.SamplerCase(case.logits[:0], case.draft_probs[:0], np.zeros(0, np.int32), np.zeros(1, np.int32),
+                              np.zeros(0, np.float32), np.zeros(0, np.float32), np.zeros(0, np.float32))
+    B0 = fv.DeviceBatch(None, None, torch.zeros(1, dtype=torch.int32, device="cuda"), None, None, None, None, None,
+                        None, None, None, 0, None, np.zeros(1, np.int32), None)
+    ctx.sample(torch.zeros((1, 4096), device="cuda"), B0, fv.DeviceResult.alloc(1))
+    ctx.close()
