@@ -1,0 +1,154 @@
+#!/usr/bin/env python3
+"""Benchmark of the verification step (Alg. 2 step 2 + KV append / rollback, Sec. IV-C) on one MI355X.
+
+One step = one fsv_verify() call on the 8B-shape, batch-16 workload (ragged gamma 1..8, contexts
+512..4096, paged KV, temperature 0.8): target forward over every request's pending token and
+drafts, acceptance tests, correction / bonus token, rollback.  All inputs are resident in HBM
+before the timed region.  Prints ONE JSON line (see README for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def log(msg):
+    print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
+
+
+def cpu_baseline(cfg, wl, req, weights, seed, budget_rows=9):
+    """The oracle, as it stands, verifying ONE request of the same workload on the host cores.
+
+    The request's drafts and draft laws are produced by stepping the oracle itself (untimed), so the
+    oracle consumes nothing the GPU library computed; only its verify call is timed.
+    """
+    import torch
+    from oracle import oracle
+    from paper_2601_00644_amd import synth
+    # the request with the most drafts that still fits the row budget (about 10-30 s of CPU work at 8B shapes)
+    cand = [b for b in range(req.batch) if 1 <= int(req.gammas[b]) + 1 <= budget_rows]
+    if not cand:
+        cand = [int(np.argmin(req.gammas))]
+    b = max(cand, key=lambda i: (int(req.gammas[i]), -int(req.seq_lens[i])))
+    L, g, o = int(req.seq_lens[b]), int(req.gammas[b]), int(req.draft_offsets[b])
+    t0 = time.time()
+    wn = synth.weights_to_numpy(cfg, weights)
+    k, v = synth.make_kv_context(cfg, L, seed, b, device="cuda")
+    kc, vc = oracle.new_cache(cfg, L + g + 1)
+    kc[:, :L] = synth.kv_to_f64(k)
+    vc[:, :L] = synth.kv_to_f64(v)
+    del k, v
+    log(f"cpu_baseline: request {b} (L={L}, gamma={g}); host copies ready in {time.time() - t0:.1f}s")
+    tok, T = int(req.last_token[b]), float(req.temperature[b])
+    q = np.zeros((g, cfg.vocab), np.float32)
+    d = np.zeros(g, np.int32)
+    k2, v2 = kc.copy(), vc.copy()
+    for i in range(g):
+        lg = oracle.forward(cfg, wn, k2, v2, L + i, np.array([tok], np.int32))[0]
+        qi = synth.draft_law(torch.from_numpy(lg), T, wl.sigma, seed, o + i)
+        tok = synth.draw_from(qi, float(req.u_draft[o + i]))
+        q[i], d[i] = qi.numpy(), tok
+    del k2, v2
+    log(f"cpu_baseline: drafts stepped by the oracle in {time.time() - t0:.1f}s; timing its verify call")
+    t1 = time.time()
+    r = oracle.verify(cfg, wn, kc, vc, L, int(req.last_token[b]), d, q, req.u_accept[o:o + g], float(req.u_sample[b]), T)
+    dt = time.time() - t1
+    cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    log(f"cpu_baseline: {g} drafts verified in {dt:.2f}s (tau={r.sample.tau}) on {cores} threads")
+    return {"value": g / dt, "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
+            "sample": f"request {b} of the batch alone (context {L}, gamma {g}, {g + 1} rows): {dt:.2f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3_8b_b16")
+    ap.add_argument("--seed", type=int, default=1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (one extra untimed pass)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (requests are independent; see DESIGN.md for how the step "
+              "would shard); rerun with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2601_00644_amd import flexverify as fv
+    from paper_2601_00644_amd import synth, workload
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    wl = synth.WORKLOADS[args.workload]
+    cfg = synth.MODELS[wl.model]
+    log(f"workload {wl.name}: model {cfg.name}, generating weights on the device")
+    weights = synth.make_weights(cfg, args.seed, device="cuda")
+    w = workload.build(wl, args.seed, weights=weights, log=log)
+    req, ctx = w.req, w.ctx
+    B, G, M = req.batch, w.drafts, w.drafts + req.batch
+    res = fv.DeviceResult.alloc(B)
+
+    def step():
+        ctx.verify(w.batch, res)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_read()
+    ctx.profile_enable(["gemm_gate_up"])      # event pairs around the dominant kernel only (32 launches / step)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    tau = res.accepted_len.cpu().numpy()
+    dom = prof["gemm_gate_up"]
+    dom_ms = dom["total_ms"] / dom["launches"]
+    dom_bytes = dom["bytes"] / dom["launches"]
+    roofline = {"bound": "hbm", "kernel": "k_gemm<.,SwiGLU> (gate|up projection, weight streaming)",
+                "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "launches": dom["launches"], "avg_us": dom_ms * 1e3, "bytes_per_launch": dom_bytes}
+    out = {"metric": "verified draft tokens/sec on 1 MI355X (8B shapes, batch 16)", "value": G / (ms * 1e-3),
+           "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+           "data": "synthetic",
+           "config": {"workload": wl.name, "model_shape": cfg.name, "batch": B, "drafts": G, "rows": M,
+                      "kv_tokens": int(req.seq_lens.sum()), "temperature": wl.temperature, "draft_noise_sigma": wl.sigma,
+                      "accepted_drafts": int(tau.sum()), "emitted_tokens": int(tau.sum()) + B},
+           "roofline": roofline}
+    # whole-step algorithmic bytes: weights once + KV of every cached position + logits
+    wbytes = sum(v.numel() * v.element_size() for k, v in weights.items() if k != "embed")
+    kvbytes = float((req.seq_lens + req.gammas + 1).sum()) * cfg.n_layers * cfg.n_kv_heads * cfg.head_dim * 2 * 2
+    out["step_bytes"] = {"weights": wbytes, "kv": kvbytes, "step_GBps": (wbytes + kvbytes) / (ms * 1e-3) / 1e9,
+                         "step_frac_of_hbm_peak": (wbytes + kvbytes) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    if args.breakdown:
+        ctx.profile_enable(True)
+        step()
+        torch.cuda.synchronize()
+        bd = ctx.profile_read()
+        ctx.profile_enable(False)
+        out["kernels"] = {k: {"launches": v["launches"], "ms": round(v["total_ms"], 4),
+                              "GBps": round(v["bytes"] / max(v["total_ms"], 1e-9) / 1e6, 1)} for k, v in bd.items()}
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, wl, req, weights, args.seed)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -39,7 +39,8 @@ typedef enum { FSV_F32 = 0, FSV_BF16 = 1 } fsv_dtype;
 
 typedef enum {
   FSV_OK = 0,
-  FSV_E_INVALID_ARG = -1, /* NULL pointer, negative size, inconsistent CSR, token id out of range ...   */
+  FSV_E_INVALID_ARG = -1, /* NULL pointer, negative size, inconsistent CSR ... (token and page ids
+                             live on the device and are clamped into range there, not reported)        */
   FSV_E_CAPACITY = -2,    /* batch, gamma, pages or rows beyond what the context was created for        */
   FSV_E_UNSUPPORTED = -3, /* shape the kernels do not cover (see fsv_create)                            */
   FSV_E_HIP = -4,         /* a HIP runtime call failed (allocation, launch)                             */
@@ -91,6 +92,8 @@ typedef struct {
  *   FSV_F32 : [position in page][head_dim] for both pools;
  *   FSV_BF16: the order in which the matrix cores consume it, see fsv_kv_import().
  * Use fsv_kv_import()/fsv_kv_export() to move sessions in and out; do not index tiles directly.
+ * Zero the pools once after allocating them: positions that were never written are masked out of
+ * the softmax but still pass through the matrix cores, so they must not hold NaN or Inf patterns.
  * The call appends the KV pairs of all M rows (positions seq_lens[b] .. seq_lens[b]+gamma_b).
  */
 typedef struct {
@@ -191,11 +194,13 @@ int fsv_linear(fsv_ctx *ctx, int32_t which, int32_t layer, const void *x, int32_
 int fsv_attention(fsv_ctx *ctx, int32_t layer, const void *q, const fsv_batch *batch, float *out, void *stream);
 
 /*
- * Per-kernel timing with HIP events on the call's stream.  fsv_profile_enable(ctx, 1) makes every
+ * Per-kernel timing with HIP events on the call's stream.  fsv_profile_enable(ctx, mask) makes every
  * later fsv_verify / fsv_sample / fsv_linear / fsv_attention record an event pair around each launch
- * of the kernel classes below (bounded ring, oldest dropped); fsv_profile_read() waits for the
- * recorded events and returns, per class, the number of launches and their summed duration, then
- * clears the ring.  Returns the number of classes written (<= cap).
+ * of the kernel classes whose bit (1u << FSV_K_*) is set in mask (0 = off, 0xffffffff = all; at most
+ * 8192 launches are kept, later ones are not recorded); fsv_profile_read() waits for the recorded
+ * events and returns, per class, the number of launches, their summed duration and the algorithmic
+ * bytes the host computed for them (weights for a GEMM, K and V for attention, logits and draft law
+ * for the sampling kernels), then clears the records.  Returns the number of classes written (<= cap).
  */
 enum { FSV_K_GEMM_QKV = 0, FSV_K_GEMM_O, FSV_K_GEMM_GATE_UP, FSV_K_GEMM_DOWN, FSV_K_GEMM_LM_HEAD,
        FSV_K_ATTENTION, FSV_K_ATTN_COMBINE, FSV_K_SAMPLE_STATS, FSV_K_SAMPLE_ACCEPT, FSV_K_SAMPLE_SELECT,
@@ -206,7 +211,7 @@ typedef struct {
   double total_ms;      /* sum of event-to-event times   */
   double bytes;         /* algorithmic bytes of those launches as the host computed them at launch  */
 } fsv_kernel_time;
-int fsv_profile_enable(fsv_ctx *ctx, int32_t on);
+int fsv_profile_enable(fsv_ctx *ctx, uint32_t class_mask);
 int fsv_profile_read(fsv_ctx *ctx, fsv_kernel_time *out, int32_t cap);
 const char *fsv_kernel_class_name(int32_t kernel_class);
 

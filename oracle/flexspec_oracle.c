@@ -59,8 +59,8 @@ static inline double widen(const void *w, int bf16, size_t idx) {
   return (double)((const float *)w)[idx];
 }
 
-/* y[m][o] = sum_k x[m][k] * W[o][k]   (x: [n][in], y: [n][out]) */
-static void linear(const void *W, int bf16, int out, int in, const double *x, int n, double *y) {
+/* Dense projection, the definition: y[m][o] = sum_k x[m][k] * W[o][k]   (x: [n][in], y: [n][out]) */
+void orc_linear(const void *W, int bf16, int out, int in, const double *x, int n, double *y) {
 #pragma omp parallel for schedule(static)
   for (int o = 0; o < out; ++o) {
     for (int m = 0; m < n; ++m) {
@@ -94,6 +94,45 @@ static void rope(double *vec, int hd, int pos, double theta) {
 }
 
 /*
+ * Attention of a block of n queries over one session's cache (one layer), the definition:
+ * query i (rotated, at position L+i) attends to keys 0 .. L+i, i.e. the restored context plus the
+ * block up to itself (causal only inside the block); query head hh reads KV head hh / (H/Hkv).
+ *   q   : [n][q_stride] with head hh at q[i*q_stride + hh*hd]
+ *   kl,vl: [>= L+n][Hkv*hd] keys / values of this layer
+ *   out : [n][H*hd]
+ */
+void orc_attention(const double *q, int q_stride, const double *kl, const double *vl, int L, int n, int H, int Hkv,
+                   int hd, double *out) {
+  const int kvdim = Hkv * hd, group = H / Hkv;
+  double *sc = malloc(sizeof(double) * (L + n));
+  for (int i = 0; i < n; ++i) {
+    int nkeys = L + i + 1;
+    for (int hh = 0; hh < H; ++hh) {
+      const double *qv = q + (size_t)i * q_stride + hh * hd;
+      int kvh = hh / group;
+      double mx = -INFINITY;
+      for (int j = 0; j < nkeys; ++j) {
+        const double *kv = kl + (size_t)j * kvdim + kvh * hd;
+        double s = 0.0;
+        for (int e = 0; e < hd; ++e) s += qv[e] * kv[e];
+        sc[j] = s / sqrt((double)hd);
+        if (sc[j] > mx) mx = sc[j];
+      }
+      double den = 0.0;
+      for (int j = 0; j < nkeys; ++j) { sc[j] = exp(sc[j] - mx); den += sc[j]; }
+      double *o = out + (size_t)i * H * hd + hh * hd;
+      for (int e = 0; e < hd; ++e) o[e] = 0.0;
+      for (int j = 0; j < nkeys; ++j) {
+        const double *vv = vl + (size_t)j * kvdim + kvh * hd;
+        double p = sc[j] / den;
+        for (int e = 0; e < hd; ++e) o[e] += p * vv[e];
+      }
+    }
+  }
+  free(sc);
+}
+
+/*
  * Score n new tokens that sit at positions L .. L+n-1 of one user's session.
  *   kc, vc : the session's KV cache, [n_layers][cap][n_kv_heads][head_dim] doubles;
  *            positions < L hold the restored context, positions L..L+n-1 are
@@ -110,12 +149,12 @@ int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *v
   if (n <= 0 || L < 0 || L + n > cap || H % Hkv != 0 || hd % 2 != 0) return -1;
   for (int i = 0; i < n; ++i)
     if (tokens[i] < 0 || tokens[i] >= V) return -1;
-  const int qdim = H * hd, kvdim = Hkv * hd, qkvdim = qdim + 2 * kvdim, group = H / Hkv;
+  const int qdim = H * hd, kvdim = Hkv * hd, qkvdim = qdim + 2 * kvdim;
   double *h = malloc(sizeof(double) * n * d), *a = malloc(sizeof(double) * n * d);
   double *qkv = malloc(sizeof(double) * n * qkvdim), *att = malloc(sizeof(double) * n * qdim);
   double *gu = malloc(sizeof(double) * n * 2 * F), *act = malloc(sizeof(double) * n * F);
-  double *upd = malloc(sizeof(double) * n * d), *sc = malloc(sizeof(double) * (L + n));
-  if (!h || !a || !qkv || !att || !gu || !act || !upd || !sc) return -1;
+  double *upd = malloc(sizeof(double) * n * d);
+  if (!h || !a || !qkv || !att || !gu || !act || !upd) return -1;
 
   for (int i = 0; i < n; ++i)
     for (int k = 0; k < d; ++k) h[(size_t)i * d + k] = widen(w->embed, bf, (size_t)tokens[i] * d + k);
@@ -123,7 +162,7 @@ int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *v
   for (int l = 0; l < mo->n_layers; ++l) {
     double *kl = kc + (size_t)l * cap * kvdim, *vl = vc + (size_t)l * cap * kvdim;
     rmsnorm(h, w->attn_norm[l], bf, d, mo->rms_eps, n, a);
-    linear(w->w_qkv[l], bf, qkvdim, d, a, n, qkv);
+    orc_linear(w->w_qkv[l], bf, qkvdim, d, a, n, qkv);
     for (int i = 0; i < n; ++i) {
       double *row = qkv + (size_t)i * qkvdim;
       int pos = L + i;
@@ -132,46 +171,23 @@ int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *v
       memcpy(kl + (size_t)pos * kvdim, row + qdim, sizeof(double) * kvdim);
       memcpy(vl + (size_t)pos * kvdim, row + qdim + kvdim, sizeof(double) * kvdim);
     }
-    for (int i = 0; i < n; ++i) {
-      int nkeys = L + i + 1; /* causal inside the block: keys 0 .. L+i */
-      for (int hh = 0; hh < H; ++hh) {
-        const double *qv = qkv + (size_t)i * qkvdim + hh * hd;
-        int kvh = hh / group;
-        double mx = -INFINITY;
-        for (int j = 0; j < nkeys; ++j) {
-          const double *kv = kl + (size_t)j * kvdim + kvh * hd;
-          double s = 0.0;
-          for (int e = 0; e < hd; ++e) s += qv[e] * kv[e];
-          sc[j] = s / sqrt((double)hd);
-          if (sc[j] > mx) mx = sc[j];
-        }
-        double den = 0.0;
-        for (int j = 0; j < nkeys; ++j) { sc[j] = exp(sc[j] - mx); den += sc[j]; }
-        double *o = att + (size_t)i * qdim + hh * hd;
-        for (int e = 0; e < hd; ++e) o[e] = 0.0;
-        for (int j = 0; j < nkeys; ++j) {
-          const double *vv = vl + (size_t)j * kvdim + kvh * hd;
-          double p = sc[j] / den;
-          for (int e = 0; e < hd; ++e) o[e] += p * vv[e];
-        }
-      }
-    }
-    linear(w->w_o[l], bf, d, qdim, att, n, upd);
+    orc_attention(qkv, qkvdim, kl, vl, L, n, H, Hkv, hd, att);
+    orc_linear(w->w_o[l], bf, d, qdim, att, n, upd);
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
     rmsnorm(h, w->mlp_norm[l], bf, d, mo->rms_eps, n, a);
-    linear(w->w_gate_up[l], bf, 2 * F, d, a, n, gu);
+    orc_linear(w->w_gate_up[l], bf, 2 * F, d, a, n, gu);
     for (int i = 0; i < n; ++i)
       for (int f = 0; f < F; ++f) {
         double g = gu[(size_t)i * 2 * F + f], u = gu[(size_t)i * 2 * F + F + f];
         act[(size_t)i * F + f] = g / (1.0 + exp(-g)) * u; /* silu(g) * u */
       }
-    linear(w->w_down[l], bf, d, F, act, n, upd);
+    orc_linear(w->w_down[l], bf, d, F, act, n, upd);
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
   }
   if (hidden) memcpy(hidden, h, sizeof(double) * n * d);
   rmsnorm(h, w->final_norm, bf, d, mo->rms_eps, n, a);
-  linear(w->lm_head, bf, V, d, a, n, logits);
-  free(h); free(a); free(qkv); free(att); free(gu); free(act); free(upd); free(sc);
+  orc_linear(w->lm_head, bf, V, d, a, n, logits);
+  free(h); free(a); free(qkv); free(att); free(gu); free(act); free(upd);
   return 0;
 }
 

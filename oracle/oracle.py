@@ -53,6 +53,8 @@ def lib():
         _lib.orc_forward.restype = C.c_int
         _lib.orc_sample.restype = C.c_int
         _lib.orc_rollback.restype = C.c_int
+        _lib.orc_linear.restype = None
+        _lib.orc_attention.restype = None
     return _lib
 
 
@@ -120,6 +122,32 @@ def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False):
     if rc != 0:
         raise ValueError("orc_forward rejected its arguments")
     return (logits, hidden) if want_hidden else logits
+
+
+def linear(W, x, bf16: bool):
+    """y = x W^T for W [out][in] (float32, or uint16 bf16 bits) and x [n][in] fp64: the dense step of the forward."""
+    W = np.ascontiguousarray(W)
+    x = np.ascontiguousarray(x, np.float64)
+    out, inn = W.shape
+    y = np.empty((x.shape[0], out), np.float64)
+    lib().orc_linear(C.c_void_p(W.ctypes.data), C.c_int(1 if bf16 else 0), C.c_int(out), C.c_int(inn),
+                     C.c_void_p(x.ctypes.data), C.c_int(x.shape[0]), C.c_void_p(y.ctypes.data))
+    return y
+
+
+def attention(q, kl, vl, L: int):
+    """Block attention over one layer of a session cache: q [n][H][hd] (rotated), kl/vl [>=L+n][Hkv][hd], fp64."""
+    q = np.ascontiguousarray(q, np.float64)
+    kl = np.ascontiguousarray(kl, np.float64)
+    vl = np.ascontiguousarray(vl, np.float64)
+    n, H, hd = q.shape
+    Hkv = kl.shape[1]
+    assert kl.shape[0] >= L + n and vl.shape == kl.shape
+    out = np.empty((n, H * hd), np.float64)
+    lib().orc_attention(C.c_void_p(q.ctypes.data), C.c_int(H * hd), C.c_void_p(kl.ctypes.data),
+                        C.c_void_p(vl.ctypes.data), C.c_int(L), C.c_int(n), C.c_int(H), C.c_int(Hkv), C.c_int(hd),
+                        C.c_void_p(out.ctypes.data))
+    return out
 
 
 def sample(logits, draft, q, u_acc, u_smp: float, T: float) -> SampleResult:

@@ -242,9 +242,9 @@ int fsv_attention(fsv_ctx *c, int32_t layer, const void *q, const fsv_batch *b, 
   return (c->d.dtype == FSV_F32) ? fsv_f32_attention(c, layer, q, b, M, out, s) : fsv_bf16_attention(c, layer, q, b, M, out, s);
 }
 
-int fsv_profile_enable(fsv_ctx *c, int32_t on) {
+int fsv_profile_enable(fsv_ctx *c, uint32_t class_mask) {
   if (!c) return FSV_E_INVALID_ARG;
-  c->prof_on = on != 0;
+  c->prof_mask = class_mask;
   return FSV_OK;
 }
 

@@ -71,7 +71,7 @@ struct fsv_ctx {
   int attn_max_splits = 0;
 
   // profiling
-  bool prof_on = false;
+  uint32_t prof_mask = 0;
   std::vector<fsv_prof_rec> prof;
 };
 
@@ -95,7 +95,8 @@ struct fsv_prof_scope {
   hipStream_t s;
   fsv_prof_rec r{};
   bool on;
-  fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes) : c(ctx), s(st), on(ctx->prof_on) {
+  fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes)
+      : c(ctx), s(st), on((ctx->prof_mask >> cls) & 1u) {
     if (!on) return;
     if (c->prof.size() >= 8192) { on = false; return; }
     r.cls = cls;

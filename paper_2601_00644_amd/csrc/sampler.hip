@@ -97,7 +97,7 @@ __global__ void k_build_rows(int B, int V, const int32_t *seq_lens, const int32_
     row_idx[rs + i] = i;
     row_pos[rs + i] = L + i;
     if (row_tok) {
-      int t = (i == 0) ? (last_token ? last_token[b] : 0) : draft[o + i - 1];
+      int t = (i == 0) ? (last_token ? last_token[b] : 0) : (draft ? draft[o + i - 1] : 0);
       row_tok[rs + i] = min(max(t, 0), V - 1);
     }
   }

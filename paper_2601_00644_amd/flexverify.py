@@ -243,8 +243,18 @@ class Context:
                                         C.c_void_p(out.data_ptr()), _stream()), "fsv_attention")
         return out
 
-    def profile_enable(self, on: bool):
-        self._check(lib().fsv_profile_enable(self._h, 1 if on else 0), "fsv_profile_enable")
+    def profile_enable(self, classes=True):
+        """classes: True = all kernel classes, False = off, or an iterable of class names."""
+        if classes is True:
+            mask = 0xFFFFFFFF
+        elif not classes:
+            mask = 0
+        else:
+            names = [lib().fsv_kernel_class_name(i).decode() for i in range(32)]
+            mask = 0
+            for n in classes:
+                mask |= 1 << names.index(n)
+        self._check(lib().fsv_profile_enable(self._h, C.c_uint32(mask)), "fsv_profile_enable")
 
     def profile_read(self) -> dict:
         buf = (KernelTime * 32)()

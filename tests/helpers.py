@@ -113,6 +113,20 @@ def logits_close(got: np.ndarray, ref: np.ndarray, tol: float):
     return bool((ratio <= tol).all()), float(ratio.max())
 
 
+def logits_close_bf16(got: np.ndarray, ref: np.ndarray, tol: float = 2e-2):
+    """The bf16 bar: every element within tol of the row's scale max|ref|, and every row within tol in L2.
+
+    Storing activations in bf16 between kernels (what the bf16 configuration means) by itself leaves an
+    rms logit error of 0.6 % (2 layers) to 1.3 % (24 layers) against an fp64 forward, whatever the
+    kernels do, so single elements cannot be held to tol of their own magnitude; the row scale can.
+    Returns (ok, worst element ratio, worst row L2 ratio).
+    """
+    scale = np.abs(ref).max(axis=-1, keepdims=True)
+    elem = float((np.abs(got - ref) / scale).max())
+    l2 = float((np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)).max())
+    return (elem <= tol and l2 <= tol), elem, l2
+
+
 def compare_decisions(exp_list, tau, nxt, accept_flag=ACCEPT_FLAG, cdf_flag=CDF_FLAG):
     """Exact match of (tau, next token) except draws the oracle itself places within the flag margins.
 
