@@ -10,12 +10,12 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
-LIB = os.path.join(HERE, "libflexverify.so")
+LIB = os.path.join(HERE, os.environ.get("FSV_LIB_NAME", "libflexverify.so"))
 OBJ = os.path.join(HERE, "_build")
 
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-         "-fno-gpu-rdc"]
+         "-fno-gpu-rdc"] + ([f"-DFSV_EXP={os.environ['FSV_EXP']}"] if os.environ.get("FSV_EXP") else [])
 
 
 def sources():

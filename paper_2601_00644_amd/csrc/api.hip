@@ -115,7 +115,7 @@ int fsv_create(const fsv_model_desc *desc, const fsv_weights *w, fsv_ctx **out) 
     if (d.n_heads / d.n_kv_heads * (d.max_gamma + 1) > 96) return FSV_E_UNSUPPORTED;
     if (d.dtype == FSV_BF16) {
       if (d.head_dim != 64 && d.head_dim != 128) return FSV_E_UNSUPPORTED;
-      if (d.d_model % 128 || d.d_ffn % 128 || (d.n_heads * d.head_dim) % 128) return FSV_E_UNSUPPORTED;
+      if (d.d_model % 256 || d.d_ffn % 256 || (d.n_heads * d.head_dim) % 256) return FSV_E_UNSUPPORTED;
     }
     if (!w->embed || !w->final_norm || !w->lm_head || !w->attn_norm || !w->w_qkv || !w->w_o || !w->mlp_norm ||
         !w->w_gate_up || !w->w_down)

@@ -15,20 +15,22 @@
 
 #include "fsv_internal.h"
 
+#ifndef FSV_EXP
+#define FSV_EXP 0  // timing experiments only (wrong results): 1 no activation staging, 2 no MFMA, 4 no LDS reads
+#endif
+
 namespace {
 
 typedef __hip_bfloat16 bf16;
 
-constexpr int KCB = 8;           // k-blocks (of 16) staged per LDS chunk: 128 contraction elements
-constexpr int KCHUNK = KCB * 16;
+constexpr int KCHUNK = 256;       // contraction elements per split / group granule (a multiple of every chunk size)
 constexpr int RTMAX = 3;         // query-row tiles of 32 per (request, kv head): group * (gamma+1) <= 96
 constexpr float kLog2eF = 1.4426950408889634f;
 
 __device__ inline float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ inline uint16_t f2bf(float f) {  // round to nearest even
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
-  return (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+__device__ inline uint16_t f2bf(float f) {  // round to nearest even (hardware conversion)
+  __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(uint16_t, b);
 }
 __device__ inline float wave_sum(float v) {
 #pragma unroll
@@ -114,17 +116,24 @@ __global__ void k_reduce_part(const float *__restrict__ part, int S, int Mpad, i
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };
 
 // One wave owns 32 output features (one weight tile row) for up to MT*32 batch rows and streams that
-// weight strip straight from HBM into MFMA operand registers; the four waves of a block share the
-// activation chunk, staged through LDS in operand order.  grid = (feature tiles / 4, K splits, row blocks).
-template <int MT, int EPI>
-__global__ __launch_bounds__(256) void k_gemm(const bf16x8_t *__restrict__ Wp, const uint4 *__restrict__ Ap,
-                                              void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                              int cps, int nchunks, int KBo) {
-  __shared__ uint4 lds[2][MT * KCB * 64];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, h = lane >> 5;
+// weight strip straight from HBM into MFMA operand registers, two 128-deep chunks ahead of its use.  A block
+// is WK groups of four waves: the four waves of a group share the activation chunk, staged through LDS in
+// operand order; the groups take disjoint halves of the block's K range (so twice the bytes are in flight
+// per compute unit) and are summed through LDS in group order before the epilogue.
+// grid = (feature tiles / 4, K splits, row blocks), dynamic LDS = WK * 2 * MT * 8 KiB.
+template <int MT, int EPI, int WK, int KC, int WS>
+__global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ Wp, const uint4 *__restrict__ Ap,
+                                                   void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
+                                                   int cps, int nchunks, int KBo) {
+  extern __shared__ uint4 lds_dyn[];
+  constexpr int CHU = MT * KC * 64;  // 16-byte units of one staged activation chunk
+  const int tid = threadIdx.x, grp = tid >> 8, gt = tid & 255, w = gt >> 6, lane = tid & 63, h = lane >> 5;
+  uint4 *lds = lds_dyn + grp * 2 * CHU;
   const int nt = blockIdx.x * 4 + w, split = blockIdx.y, mt0 = blockIdx.z * MT;
   const int mtc = min(MT, Mt_total - mt0);
-  const int c0 = split * cps, c1 = min(c0 + cps, nchunks);
+  const int cb0 = split * cps, cb1 = min(cb0 + cps, nchunks);
+  const int per = (max(cb1 - cb0, 0) + WK - 1) / WK;  // iterations every group runs (barriers stay uniform)
+  const int c0 = cb0 + grp * per, c1 = min(c0 + per, cb1);
   f32x16_t acc[MT];
 #pragma unroll
   for (int i = 0; i < MT; ++i)
@@ -132,56 +141,125 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16x8_t *__restrict__ Wp, c
     for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
 
   const bf16x8_t *wrow = Wp + (size_t)nt * KB * 64 + lane;
-  constexpr int APT = MT * KCB * 64 / 256;  // 16-byte units of the activation chunk each thread stages
-  uint4 areg[APT];
-  bf16x8_t wcur[KCB], wnext[KCB];
+  constexpr int APT = CHU / 256;  // units of the activation chunk each thread stages
+  uint4 areg[2][APT];  // activation chunks in flight: chunk j lives in slot j & 1, fetched two chunks ahead
+  bf16x8_t wbuf[WS][KC];  // weight chunks: in use and being fetched, WS - 1 chunks ahead (roles rotate by name)
 
-  auto load_a = [&](int c) {
+  // Loads are never put under a branch: a branch around a global load makes the compiler wait for ALL
+  // outstanding loads at the join, which would drain the weight prefetch every iteration.  Out-of-range
+  // chunks are clamped to a valid address and their activations masked to zero instead.
+  const int cmax = nchunks - 1, mlast = mtc - 1;
+  auto load_a = [&](int c, uint4(&dst)[APT]) {
 #pragma unroll
     for (int p = 0; p < APT; ++p) {
-      const int i = p * 256 + tid, mt = i / (KCB * 64), rem = i % (KCB * 64);
-      areg[p] = (mt < mtc) ? Ap[((size_t)(mt0 + mt) * KB + c * KCB) * 64 + rem] : make_uint4(0, 0, 0, 0);
+      const int i = p * 256 + gt, mt = min(i / (KC * 64), mlast), rem = i % (KC * 64);
+      dst[p] = Ap[((size_t)(mt0 + mt) * KB + c * KC) * 64 + rem];
     }
   };
-  auto store_a = [&](int buf) {
-#pragma unroll
-    for (int p = 0; p < APT; ++p) lds[buf][p * 256 + tid] = areg[p];
+  auto store_a = [&](int buf, uint32_t mask, uint4(&src)[APT]) {  // the mask is applied here, not at the load: touching
+#pragma unroll                                                    // the loaded value early would stall the wave on it
+    for (int p = 0; p < APT; ++p)
+      lds[buf * CHU + p * 256 + gt] = make_uint4(src[p].x & mask, src[p].y & mask, src[p].z & mask, src[p].w & mask);
   };
-  auto load_w = [&](int c, bf16x8_t(&dst)[KCB]) {
+  auto load_w = [&](int c, bf16x8_t(&dst)[KC]) {
+#if (FSV_EXP & 8)
 #pragma unroll
-    for (int kb = 0; kb < KCB; ++kb) dst[kb] = wrow[(size_t)(c * KCB + kb) * 64];
+    for (int kb = 0; kb < KC; ++kb) dst[kb] = wrow[(size_t)(kb) * 64 + 0 * c];
+#else
+#pragma unroll
+    for (int kb = 0; kb < KC; ++kb) dst[kb] = wrow[(size_t)(c * KC + kb) * 64];
+#endif
+  };
+  // Blocks walk their K range starting at different chunks (a fixed rotation per block): all blocks read the
+  // same small activation matrix, and in lockstep they would all hit the same few L2 channels at once.
+  const int rot = per > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u + grp) % (unsigned)per) : 0;
+  auto chunk_of = [&](int it) { return c0 + (per > 0 ? (it + rot) % per : 0); };
+  auto live = [&](int it, int c) -> uint32_t { return (it < per && c < c1) ? 0xffffffffu : 0u; };
+  auto lds_op = [&](int buf, int mt, int kb) {
+#if (FSV_EXP & 4)
+    uint4 raw = make_uint4(buf, mt, kb, lane);
+#else
+    uint4 raw = lds[buf * CHU + (mt * KC + kb) * 64 + lane];
+#endif
+    return *reinterpret_cast<bf16x8_t *>(&raw);
+  };
+  // One chunk: issue the prefetches (activations of the next chunk, weights two chunks ahead), then KC x MT MFMAs
+  // with the LDS operand reads running D k-blocks ahead of the MFMAs, then publish the next activation chunk.
+  constexpr int D = (MT >= 3) ? 1 : (MT == 2 ? 2 : 4);
+  auto chunk_step = [&](int it, bf16x8_t(&wuse)[KC], bf16x8_t(&wfetch)[KC], uint4(&afetch)[APT], uint4(&apub)[APT]) {
+    const int buf = it & 1, cn = chunk_of(it + 1), cnn = chunk_of(it + WS - 1);
+#if !(FSV_EXP & 1)
+    load_a(min(chunk_of(it + 2), cmax), afetch);
+#endif
+    load_w(min(cnn, cmax), wfetch);
+    __builtin_amdgcn_sched_barrier(0);  // the scheduler would sink the prefetch below the MFMA block otherwise
+    bf16x8_t aop[D + 1][MT];
+#pragma unroll
+    for (int kb = 0; kb < D; ++kb)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) aop[kb % (D + 1)][mt] = lds_op(buf, mt, kb);
+#pragma unroll
+    for (int kb = 0; kb < KC; ++kb) {
+      if (kb + D < KC) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) aop[(kb + D) % (D + 1)][mt] = lds_op(buf, mt, kb + D);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#if (FSV_EXP & 2)
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) acc[mt][0] += (float)wuse[kb][mt] + (float)aop[kb % (D + 1)][mt][0];
+#else
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], aop[kb % (D + 1)][mt], acc[mt], 0, 0, 0);
+#endif
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#if !(FSV_EXP & 1)
+    store_a(buf ^ 1, live(it + 1, cn), apub);
+#endif
+    __syncthreads();
   };
 
-  if (c0 < c1) {
-    load_a(c0);
-    load_w(c0, wcur);
-    store_a(0);
-    __syncthreads();
-    for (int c = c0; c < c1; ++c) {
-      const int buf = (c - c0) & 1;
-      const bool more = c + 1 < c1;
-      if (more) {
-        load_a(c + 1);
-        load_w(c + 1, wnext);
+  {
+    const int ca = chunk_of(0);
+    load_a(min(ca, cmax), areg[0]);
+#pragma unroll
+    for (int j = 0; j < WS - 1; ++j) load_w(min(chunk_of(j), cmax), wbuf[j]);
+    store_a(0, live(0, ca), areg[0]);
+    load_a(min(chunk_of(1), cmax), areg[1]);
+  }
+  __syncthreads();
+  // Unrolled so that the weight buffers (period WS) and the activation slots (period 2) rotate by name, not by
+  // copies.  The trip count is padded to the unroll factor instead of leaving the loop early (several exits make
+  // the compiler keep one copy of the accumulators per exit); padded steps run on zeroed activations.
+  constexpr int UNR = (WS == 2) ? 2 : 6;
+  const int per_pad = (per + UNR - 1) / UNR * UNR;
+#define FSV_STEP(S) chunk_step(it + (S), wbuf[(S) % WS], wbuf[((S) + WS - 1) % WS], areg[(S) & 1], areg[((S) + 1) & 1]);
+  for (int it = 0; it < per_pad; it += UNR) {
+    FSV_STEP(0) FSV_STEP(1)
+    if constexpr (WS > 2) { FSV_STEP(2) FSV_STEP(3) FSV_STEP(4) FSV_STEP(5) }
+  }
+#undef FSV_STEP
+  if constexpr (WK > 1) {  // sum the groups in order through LDS (each group reuses its own staging area)
+    float *red = reinterpret_cast<float *>(lds_dyn);
+    for (int gsrc = 1; gsrc < WK; ++gsrc) {
+      if (grp == gsrc) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) red[((w * MT + mt) * 16 + v) * 64 + lane] = acc[mt][v];
       }
+      __syncthreads();
+      if (grp == 0) {
 #pragma unroll
-      for (int kb = 0; kb < KCB; ++kb) {
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          if (mt < mtc) {
-            uint4 raw = lds[buf][(mt * KCB + kb) * 64 + lane];
-            bf16x8_t a = *reinterpret_cast<bf16x8_t *>(&raw);
-            acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wcur[kb], a, acc[mt], 0, 0, 0);
-          }
-        }
-      }
-      if (more) {
-        store_a(buf ^ 1);
-#pragma unroll
-        for (int kb = 0; kb < KCB; ++kb) wcur[kb] = wnext[kb];
+          for (int v = 0; v < 16; ++v) acc[mt][v] += red[((w * MT + mt) * 16 + v) * 64 + lane];
       }
       __syncthreads();
     }
+    if (grp != 0) return;
   }
 
   // epilogue: lane holds, for batch row m = tile*32 + lane%32, features nt*32 + 8*(v/4) + 4*h + v%4
@@ -243,18 +321,18 @@ __global__ __launch_bounds__(256) void k_gemm(const bf16x8_t *__restrict__ Wp, c
 // residual stream: x (+)= sum of split partials (or embedding), RMSNorm, emit the next GEMM's operand
 // ---------------------------------------------------------------------------------------------
 template <int EMBED>
-__global__ __launch_bounds__(256) void k_resid_norm(int M, int d, float eps, const int32_t *__restrict__ row_tok,
-                                                    const uint16_t *__restrict__ E, const float *__restrict__ part,
-                                                    int S, int Mpad, float *__restrict__ x,
-                                                    const uint16_t *__restrict__ gain, uint4 *__restrict__ a_out) {
-  const int r = blockIdx.x, tid = threadIdx.x, KB = d / 16;
+__global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, const int32_t *__restrict__ row_tok,
+                                                     const uint16_t *__restrict__ E, const float *__restrict__ part,
+                                                     int S, int Mpad, float *__restrict__ x,
+                                                     const uint16_t *__restrict__ gain, uint4 *__restrict__ a_out) {
+  const int r = blockIdx.x, tid = threadIdx.x, KB = d / 16, stride = blockDim.x * 8, nw = blockDim.x >> 6;
   if (r >= M) {
-    for (int k0 = tid * 8; k0 < d; k0 += 2048) a_out[tile_unit(r, k0, KB)] = make_uint4(0, 0, 0, 0);
+    for (int k0 = tid * 8; k0 < d; k0 += stride) a_out[tile_unit(r, k0, KB)] = make_uint4(0, 0, 0, 0);
     return;
   }
   float *xr = x + (size_t)r * d;
   float ss = 0.f;
-  for (int k0 = tid * 8; k0 < d; k0 += 2048) {
+  for (int k0 = tid * 8; k0 < d; k0 += stride) {
     float v[8];
     if (EMBED) {
       uint4 raw = *reinterpret_cast<const uint4 *>(E + (size_t)row_tok[r] * d + k0);
@@ -267,9 +345,24 @@ __global__ __launch_bounds__(256) void k_resid_norm(int M, int d, float eps, con
     } else {
       float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
       v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w; v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
-      for (int s = 0; s < S; ++s) {
-        const float *p = part + ((size_t)s * Mpad + r) * d + k0;
-        float4 pa = *reinterpret_cast<const float4 *>(p), pb = *reinterpret_cast<const float4 *>(p + 4);
+      const float *p = part + (size_t)r * d + k0;
+      const size_t sstr = (size_t)Mpad * d;
+      int s = 0;
+      for (; s + 4 <= S; s += 4) {  // four slices in flight; summed in slice order
+        float4 pa[4], pb[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          pa[u] = *reinterpret_cast<const float4 *>(p + (s + u) * sstr);
+          pb[u] = *reinterpret_cast<const float4 *>(p + (s + u) * sstr + 4);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          v[0] += pa[u].x; v[1] += pa[u].y; v[2] += pa[u].z; v[3] += pa[u].w;
+          v[4] += pb[u].x; v[5] += pb[u].y; v[6] += pb[u].z; v[7] += pb[u].w;
+        }
+      }
+      for (; s < S; ++s) {
+        float4 pa = *reinterpret_cast<const float4 *>(p + s * sstr), pb = *reinterpret_cast<const float4 *>(p + s * sstr + 4);
         v[0] += pa.x; v[1] += pa.y; v[2] += pa.z; v[3] += pa.w; v[4] += pb.x; v[5] += pb.y; v[6] += pb.z; v[7] += pb.w;
       }
     }
@@ -279,11 +372,13 @@ __global__ __launch_bounds__(256) void k_resid_norm(int M, int d, float eps, con
     for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
   }
   ss = wave_sum(ss);
-  __shared__ float s_ss[4];
+  __shared__ float s_ss[16];
   if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
   __syncthreads();
-  const float rinv = 1.0f / sqrtf(((s_ss[0] + s_ss[1]) + (s_ss[2] + s_ss[3])) / (float)d + eps);
-  for (int k0 = tid * 8; k0 < d; k0 += 2048) {  // each thread re-reads exactly what it wrote
+  float tot = 0.f;
+  for (int i = 0; i < nw; ++i) tot += s_ss[i];  // fixed order
+  const float rinv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int k0 = tid * 8; k0 < d; k0 += stride) {  // each thread re-reads exactly what it wrote
     float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
     float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
     uint4 graw = *reinterpret_cast<const uint4 *>(gain + k0);
@@ -346,8 +441,10 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
                                                      const int32_t *__restrict__ page_table, int max_pages,
                                                      int num_pages, size_t layer_off, uint16_t *__restrict__ qp,
                                                      uint16_t *__restrict__ kpool, uint16_t *__restrict__ vpool) {
+  // grid = (rows, groups of 8 heads of the q|k|v projection)
   __shared__ float s_cos[64], s_sin[64];
   const int r = blockIdx.x, half = hd / 2, heads = H + 2 * Hkv, qkvd = heads * hd, group = H / Hkv;
+  const int h0 = blockIdx.y * 8, h1 = min(h0 + 8, heads);
   const int b = row_req[r], i_row = row_idx[r], pos = row_pos[r];
   if (threadIdx.x < half) {
     double sn, cs;
@@ -357,14 +454,20 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
   }
   __syncthreads();
   const int page = min(max(page_table[(size_t)b * max_pages + (pos >> 4)], 0), num_pages - 1), t = pos & 15;
-  for (int idx = threadIdx.x; idx < heads * half; idx += blockDim.x) {
-    const int hh = idx / half, i = idx % half;
+  const size_t sstr = (size_t)Mpad * qkvd;
+  for (int idx = threadIdx.x; idx < (h1 - h0) * half; idx += blockDim.x) {
+    const int hh = h0 + idx / half, i = idx % half;
+    const float *p = part + (size_t)r * qkvd + hh * hd + i;
     float a = 0.f, c = 0.f;
-    for (int s = 0; s < S; ++s) {
-      const float *p = part + ((size_t)s * Mpad + r) * qkvd + hh * hd;
-      a += p[i];
-      c += p[i + half];
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {  // four slices in flight; summed in slice order
+      float pa[4], pc[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { pa[u] = p[(s + u) * sstr]; pc[u] = p[(s + u) * sstr + half]; }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) { a += pa[u]; c += pc[u]; }
     }
+    for (; s < S; ++s) { a += p[s * sstr]; c += p[s * sstr + half]; }
     if (hh < H + Hkv) {
       const float ra = a * s_cos[i] - c * s_sin[i], rb = a * s_sin[i] + c * s_cos[i];
       a = ra;
@@ -459,8 +562,13 @@ __global__ __launch_bounds__(256) void k_attention(
     const size_t t0 = layer_off + ((size_t)g0 * Hkv + kvh) * (16 * HD), t1 = layer_off + ((size_t)g1 * Hkv + kvh) * (16 * HD);
     k0 = kpool + t0; k1 = kpool + t1; v0 = vpool + t0; v1 = vpool + t1;
   };
-  bf16x8_t kreg[KS], vreg[VC][2];
-  auto load_tile = [&](int tl) {
+  // Tiles of this wave: w, w+4, ...  K and V of the next tile are fetched into a second register set while the
+  // current one is consumed (sets alternate by name); loads are never under a branch, so the tile index is clamped
+  // and a step past the wave's last tile is masked out completely instead of skipped.
+  const int myt = (ntiles > w) ? (ntiles - w + 3) >> 2 : 0;
+  bf16x8_t kA[KS], vA[VC][2], kB[KS], vB[VC][2];
+  auto load_tile = [&](int j, bf16x8_t(&kreg)[KS], bf16x8_t(&vreg)[VC][2]) {
+    const int tl = min(w + 4 * j, ntiles - 1);
     const uint16_t *k0, *k1, *v0, *v1;
     tile_ptrs(tl, k0, k1, v0, v1);
     const uint16_t *kp = (r < 16) ? k0 : k1;  // operand row = key r: rows 0-15 first page, 16-31 second page
@@ -473,10 +581,11 @@ __global__ __launch_bounds__(256) void k_attention(
       vreg[c][1] = *reinterpret_cast<const bf16x8_t *>(v1 + ((c * 2 + h) * 32 + r) * 8);
     }
   };
-
-  for (int tl = w; tl < ntiles; tl += 4) {
-    load_tile(tl);
-    const int kbase = key0 + tl * 32;
+  auto consume = [&](int j, bf16x8_t(&kreg)[KS], bf16x8_t(&vreg)[VC][2]) {
+    asm volatile("" ::: "memory");  // keep the query operand reads inside the loop (hoisted, they cost 32 VGPRs per row tile)
+    const bool dead = j >= myt;
+    const int kbase = key0 + (w + 4 * j) * 32;
+    const bool need_mask = dead || (kbase + 31 > L);  // every query row sees all keys <= L
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       if (rt >= rtc) continue;
@@ -490,16 +599,30 @@ __global__ __launch_bounds__(256) void k_attention(
       }
       // accumulator v of this lane: key kbase + 8*(v/4) + 4h + v%4, query row rt*32 + r
       float tmax = -INFINITY;
+      if (need_mask) {
+        const int limit = dead ? -1 : lim[rt];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int key = kbase + 8 * (v >> 2) + 4 * h + (v & 3);
-        s[v] = (key <= lim[rt]) ? s[v] * sc : -INFINITY;
-        tmax = fmaxf(tmax, s[v]);
+        for (int v = 0; v < 16; ++v) {
+          const int key = kbase + 8 * (v >> 2) + 4 * h + (v & 3);
+          s[v] = (key <= limit) ? s[v] * sc : -INFINITY;
+          tmax = fmaxf(tmax, s[v]);
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          s[v] *= sc;
+          tmax = fmaxf(tmax, s[v]);
+        }
       }
       tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      const float mnew = fmaxf(mrun[rt], tmax);
+      // Lazy reference: the running reference m only moves when the tile maximum exceeds it by more than 2^8
+      // (probabilities then stay below 256, exact enough in fp32 / bf16), so the accumulators are almost never
+      // rescaled; the first tile of a row needs no rescale either (its accumulators are still zero).
+      const float mold = mrun[rt];
+      const float mnew = (tmax > mold + 8.0f || mold == -INFINITY) ? fmaxf(mold, tmax) : mold;
       const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-      const float alpha = __builtin_amdgcn_exp2f(mrun[rt] - muse);
+      const float alpha = __builtin_amdgcn_exp2f(mold - muse);
+      const bool rescale = __any(mnew != mold && mold != -INFINITY);
       mrun[rt] = mnew;
       float psum = 0.f;
       bf16x8_t pb[2];
@@ -510,13 +633,29 @@ __global__ __launch_bounds__(256) void k_attention(
         pb[v >> 3][v & 7] = (__bf16)p;
       }
       lrun[rt] = lrun[rt] * alpha + psum;
+      if (rescale) {  // wave-uniform: once the running maxima have settled the accumulators are left alone
+#pragma unroll
+        for (int c = 0; c < VC; ++c)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[rt][c][v] *= alpha;
+      }
 #pragma unroll
       for (int c = 0; c < VC; ++c) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[rt][c][v] *= alpha;
         o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][0], pb[0], o[rt][c], 0, 0, 0);
         o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pb[1], o[rt][c], 0, 0, 0);
       }
+    }
+  };
+  if (myt > 0) {
+    load_tile(0, kA, vA);
+    const int myt_pad = (myt + 1) & ~1;
+    for (int j = 0; j < myt_pad; j += 2) {
+      load_tile(j + 1, kB, vB);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(j, kA, vA);
+      load_tile(j + 2, kA, vA);
+      __builtin_amdgcn_sched_barrier(0);
+      consume(j + 1, kB, vB);
     }
   }
 
@@ -678,19 +817,59 @@ int copy_dev(fsv_ctx *c, void **dst, const void *src, size_t bytes) {
   return FSV_OK;
 }
 
+int gemm_groups() {
+  static int v = 0;
+  if (!v) {
+    const char *e = getenv("FSV_GEMM_GROUPS");
+    v = e ? atoi(e) : 1;
+    if (v != 1 && v != 2) v = 1;
+  }
+  return v;
+}
+
+int gemm_variant() {  // chunk size / weight stages under test: 0 = 128-deep chunks, 3 stages; 1 = 256-deep, 2 stages
+  static int v = -1;
+  if (v < 0) {
+    const char *e = getenv("FSV_GEMM_VARIANT");
+    v = e ? atoi(e) : 0;
+  }
+  return v;
+}
+
+template <int MT, int EPI, int WK, int KC, int WS>
+int launch_gemm_t(fsv_ctx *c, dim3 grid, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int Mt, int M,
+                  int Mpad, int cps, int nchunks, int KBo, hipStream_t st) {
+  const size_t lds = (size_t)WK * 2 * MT * KC * 64 * 16;
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, WK, KC, WS>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  // cps / nchunks are counted in KCHUNK granules; the kernel counts in its own chunk size
+  const int f = KCHUNK / (KC * 16);
+  hipLaunchKernelGGL((k_gemm<MT, EPI, WK, KC, WS>), grid, dim3(256 * WK), lds, st, (const bf16x8_t *)Wp,
+                     (const uint4 *)Ap, out, s.N, s.K / 16, Mt, M, Mpad, cps * f, nchunks * f, KBo);
+  return FSV_OK;
+}
+
 template <int EPI>
 int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, int splits,
                 hipStream_t st) {
-  const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, KB = s.K / 16, nchunks = s.K / KCHUNK;
+  const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = s.K / KCHUNK;
   const int cps = fsv_ceil_div(nchunks, splits);
   const int mt_blk = Mt >= 4 ? 4 : Mt, mblocks = fsv_ceil_div(Mt, mt_blk);
   dim3 grid(s.NTpad / 4, splits, mblocks);
   const int KBo = (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0;
-  const double bytes = (double)s.N * s.K * 2;
-  fsv_prof_scope ps(c, st, cls, bytes);
-#define FSV_GEMM_CASE(MTV)                                                                                      \
-  hipLaunchKernelGGL((k_gemm<MTV, EPI>), grid, dim3(256), 0, st, (const bf16x8_t *)Wp, (const uint4 *)Ap, out, s.N, \
-                     KB, Mt, M, Mpad, cps, nchunks, KBo)
+  const int wk = (cps >= 2) ? gemm_groups() : 1, var = gemm_variant();
+  fsv_prof_scope ps(c, st, cls, (double)s.N * s.K * 2);
+  int rc;
+#define FSV_GEMM_ARGS c, grid, Wp, Ap, out, s, Mt, M, Mpad, cps, nchunks, KBo, st
+#define FSV_GEMM_CASE(MTV)                                                                   \
+  if (var == 1) rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 16, 2>(FSV_GEMM_ARGS)            \
+                               : launch_gemm_t<MTV, EPI, 1, 16, 2>(FSV_GEMM_ARGS);           \
+  else rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 8, 2>(FSV_GEMM_ARGS)                      \
+                      : launch_gemm_t<MTV, EPI, 1, 8, 2>(FSV_GEMM_ARGS)
   switch (mt_blk) {
     case 1: FSV_GEMM_CASE(1); break;
     case 2: FSV_GEMM_CASE(2); break;
@@ -698,6 +877,8 @@ int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, 
     default: FSV_GEMM_CASE(4); break;
   }
 #undef FSV_GEMM_CASE
+#undef FSV_GEMM_ARGS
+  if (rc) return rc;
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -828,10 +1009,11 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
                    sd = shape_of(c, FSV_W_DOWN), sl = shape_of(c, FSV_W_LM_HEAD);
   const int spq = pick_splits(sq, Mt, true), spo = pick_splits(so, Mt, true), spd = pick_splits(sd, Mt, true);
   float *part = (float *)c->buf_part;
+  const int nthr = min(1024, max(64, fsv_ceil_div(d.d_model / 8, 64) * 64));  // one 8-wide slice per thread
   int rc;
   {
     fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
-    hipLaunchKernelGGL(k_resid_norm<1>, dim3(Mpad), dim3(256), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
+    hipLaunchKernelGGL(k_resid_norm<1>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
                        (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
                        (uint4 *)c->buf_a);
   }
@@ -841,7 +1023,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
-      hipLaunchKernelGGL(k_rope_append, dim3(M), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim,
+      hipLaunchKernelGGL(k_rope_append, dim3(M, fsv_ceil_div(d.n_heads + 2 * d.n_kv_heads, 8)), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim,
                          (const double *)c->inv_freq, part, spq, Mpad, c->row_req, c->row_idx, c->row_pos, b->page_table,
                          d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, (uint16_t *)b->k_pool,
                          (uint16_t *)b->v_pool);
@@ -850,7 +1032,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
-      hipLaunchKernelGGL(k_resid_norm<0>, dim3(Mpad), dim3(256), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr, part,
+      hipLaunchKernelGGL(k_resid_norm<0>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr, part,
                          spo, Mpad, c->x, (const uint16_t *)L.mlp_norm, (uint4 *)c->buf_a);
     }
     if ((rc = launch_gemm<EPI_SWIGLU>(c, FSV_K_GEMM_GATE_UP, L.w_gate_up, c->buf_a, c->buf_act, sg, M, 1, s))) return rc;
@@ -858,7 +1040,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
       const void *gain = (l + 1 < d.n_layers) ? c->layers[l + 1].attn_norm : c->final_norm;
-      hipLaunchKernelGGL(k_resid_norm<0>, dim3(Mpad), dim3(256), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr, part,
+      hipLaunchKernelGGL(k_resid_norm<0>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr, part,
                          spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a);
     }
   }

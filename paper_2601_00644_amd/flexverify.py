@@ -14,7 +14,7 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libflexverify.so")
+LIB_PATH = os.path.join(_HERE, os.environ.get("FSV_LIB_NAME", "libflexverify.so"))
 
 F32, BF16 = 0, 1
 W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
