@@ -18,6 +18,10 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.j
          "-fno-gpu-rdc"] + ([f"-DFSV_EXP={os.environ['FSV_EXP']}"] if os.environ.get("FSV_EXP") else [])
 
 
+# per-file flags: the attention kernels keep their MFMA accumulators in architectural registers
+EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+
+
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
@@ -36,7 +40,7 @@ def build(verbose: bool = True) -> str:
 
     def one(src):
         obj = os.path.join(OBJ, os.path.basename(src) + ".o")
-        cmd = ["hipcc", *FLAGS, "-c", src, "-o", obj]
+        cmd = ["hipcc", *FLAGS, *EXTRA.get(os.path.basename(src), []), "-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.check_call(cmd)

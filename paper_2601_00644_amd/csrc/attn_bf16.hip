@@ -1,0 +1,438 @@
+// Multi-query paged attention of the FSV_BF16 path (the attention step of the target forward in Alg. 2
+// step 2, over the user's restored KV session plus the rows appended in this call, Sec. IV-C).
+// Built with -mllvm -amdgpu-mfma-vgpr-form: the MFMA accumulators stay in the architectural registers,
+// where the softmax arithmetic reaches them, and the accumulation registers hold the K/V tiles in flight.
+#include <math.h>
+#include <stdlib.h>
+
+#include "bf16_common.h"
+
+using namespace fsv_bf16;
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// Work decomposition.  The keys of request b are cut into tiles of 32 (two pages); a "part" is a run of
+// tp_b consecutive tiles, s_b parts per request, chosen so that every part of every request has about the
+// same length and parts x kv heads fills the machine once (one wave per part and kv head, four waves per
+// compute unit, every wave resident from the start).  A wave owns its part completely: it streams the K and
+// V page tiles of its key range straight from HBM into MFMA operand registers, NB - 1 tiles ahead of their
+// use (each byte of the KV stream is read by exactly one wave; all `group` query heads and all gamma+1
+// positions share it), forms S^T = K Q^T (rows = keys, so a query row's scores sit in two lanes), does the
+// online softmax in registers, and feeds the probabilities back as the B operand of O^T += V^T P^T without
+// any shuffle: the V tile is stored in the key order the score accumulators produce.  Waves never talk to
+// each other; a request with one part writes its result directly, the others leave (m, l, O) per part for
+// k_attn_combine.
+//
+// K/V loads go through a buffer descriptor over the layer's pool: a load of a tile beyond the wave's range
+// gets an offset outside the descriptor, for which the hardware returns zeros without touching memory, so
+// the software pipeline needs no branch around its loads and no over-read.
+
+// Pins a value to the accumulation half of the register file.  The K/V tiles in flight are only ever written
+// by loads and read by MFMAs, both of which reach that half directly; keeping them there leaves the
+// architectural half to the softmax arithmetic and the output accumulators.
+#define FSV_IN_AGPR(x) asm("" : "+a"(x))
+// Pins an MFMA accumulator to the architectural half: the softmax reads the score tile and rescales the output
+// tiles with ordinary vector instructions, which cannot address the accumulation half.
+#define FSV_IN_VGPR(x)
+
+// parts of a request with n key tiles when parts should hold about tpw tiles; *tp = tiles per part
+__device__ __host__ inline int attn_parts(int n, int tpw, int *tp) {
+  const int s0 = (n + tpw - 1) / tpw;
+  *tp = (n + s0 - 1) / s0;
+  return (n + *tp - 1) / *tp;
+}
+
+// part_prefix[b] = parts of requests before b, part_tiles[b] = tiles per part, part_map[global part] = request
+__global__ void k_attn_plan(int B, int tpw, const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ off,
+                            int32_t *__restrict__ part_prefix, int32_t *__restrict__ part_tiles,
+                            int32_t *__restrict__ part_map, int map_cap) {
+  if (blockIdx.x != 0 || threadIdx.x != 0) return;
+  int run = 0;
+  for (int b = 0; b < B; ++b) {
+    const int nk = seq_lens[b] + (off[b + 1] - off[b]) + 1;
+    int tp;
+    const int s = attn_parts((nk + 31) >> 5, tpw, &tp);
+    part_prefix[b] = run;
+    part_tiles[b] = tp;
+    for (int p = 0; p < s && run + p < map_cap; ++p) part_map[run + p] = b;
+    run += s;
+  }
+  part_prefix[B] = run;
+}
+
+template <int HD, int RT, int NB>
+__global__ __launch_bounds__(64) void k_attention(
+    int Hkv, int group, int rows_cap, const uint4 *__restrict__ qp, const int32_t *__restrict__ seq_lens,
+    const int32_t *__restrict__ off, const int32_t *__restrict__ part_map, const int32_t *__restrict__ part_prefix,
+    const int32_t *__restrict__ part_tiles, const int32_t *__restrict__ page_table, int max_pages, int num_pages,
+    const uint16_t *__restrict__ kpool, const uint16_t *__restrict__ vpool, uint32_t layer_bytes,
+    float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out, int KBq) {
+  constexpr int KS = HD / 16, VC = HD / 32, TILEB = 16 * HD * 2;  // TILEB: bytes of one (page, kv head) tile
+  constexpr uint32_t OOB = 0xFFFF0000u;                            // offset no descriptor here reaches
+  __shared__ uint4 s_q[RT * KS * 64];
+  const int lane = threadIdx.x, h = lane >> 5, r = lane & 31;
+  const int gw = blockIdx.x, pp = gw / Hkv, kvh = gw - pp * Hkv;
+  const int b = part_map[pp];
+  const int part = pp - part_prefix[b], nparts = part_prefix[b + 1] - part_prefix[b], tp = part_tiles[b];
+  const int L = seq_lens[b], gamma = off[b + 1] - off[b], rs = off[b] + b;
+  const int nk = L + gamma + 1, R = group * (gamma + 1);
+  const int t0 = part * tp, myt = min((nk + 31) >> 5, t0 + tp) - t0;  // >= 1 by construction of the parts
+  const int rtc = min(RT, (R + 31) >> 5);
+  const int32_t *pt = page_table + (size_t)b * max_pages;
+  const int npg = (nk + 15) >> 4;
+
+  const __amdgpu_buffer_rsrc_t krs = __builtin_amdgcn_make_buffer_rsrc((void *)kpool, 0, layer_bytes, 0x00020000);
+  const __amdgpu_buffer_rsrc_t vrs = __builtin_amdgcn_make_buffer_rsrc((void *)vpool, 0, layer_bytes, 0x00020000);
+  // lane part of the offsets inside a tile: K operand row = key r (rows 0-15 first page, 16-31 second page)
+  const uint32_t klane = (uint32_t)((h * 16 + (r & 15)) * 16), vlane = (uint32_t)((h * 32 + r) * 16);
+
+  bf16x8_t kb[NB][KS], vb[NB][VC][2];
+  auto pages_of = [&](int j, int &g0, int &g1) {  // physical pages of the wave's j-th tile (indices kept in range)
+    const int p0 = min(2 * (t0 + j), npg - 1), p1 = min(2 * (t0 + j) + 1, npg - 1);
+    g0 = min(max(pt[p0], 0), num_pages - 1);
+    g1 = min(max(pt[p1], 0), num_pages - 1);
+  };
+  auto issue = [&](int j, int g0, int g1, bf16x8_t(&kreg)[KS], bf16x8_t(&vreg)[VC][2]) {
+    const bool live = j < myt;
+    const uint32_t b0 = live ? (uint32_t)(g0 * Hkv + kvh) * TILEB : OOB, b1 = live ? (uint32_t)(g1 * Hkv + kvh) * TILEB : OOB;
+    const uint32_t ko = ((r < 16) ? b0 : b1) + klane, v0 = b0 + vlane, v1 = b1 + vlane;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+      kreg[s] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(krs, ko + s * 512, 0, 0));
+#pragma unroll
+    for (int c = 0; c < VC; ++c) {
+      vreg[c][0] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(vrs, v0 + c * 1024, 0, 0));
+      vreg[c][1] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(vrs, v1 + c * 1024, 0, 0));
+    }
+  };
+
+  // Queries go from global memory straight into LDS (no staging registers; lane i of a load fills 16-byte unit i
+  // of the addressed LDS block, which is the operand order already); rows beyond R hold whatever an earlier call
+  // left there: they only feed their own output rows, which are never stored.  Then the first NB - 1 tiles.
+#pragma unroll
+  for (int i = 0; i < RT * KS; ++i) {
+    if (i / KS >= rtc) continue;
+    const uint4 *src = qp + (((size_t)b * RTMAX + i / KS) * Hkv + kvh) * (KS * 64) + (i % KS) * 64 + lane;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                     (__attribute__((address_space(3))) void *)&s_q[i * 64], 16, 0, 0);
+  }
+  int g0n, g1n;
+#pragma unroll
+  for (int s = 0; s < NB - 1; ++s) {
+    pages_of(s, g0n, g1n);
+    issue(s, g0n, g1n, kb[s], vb[s]);
+  }
+  pages_of(NB - 1, g0n, g1n);
+  __builtin_amdgcn_sched_barrier(0);
+  __syncthreads();  // one wave per block: orders the LDS fill before the operand reads below
+
+  const float sc = kLog2eF / sqrtf((float)HD);
+  f32x16_t o[RT][VC];
+  float mrun[RT], lrun[RT];
+  int lim[RT];  // last key this lane's query row may see
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+#pragma unroll
+    for (int c = 0; c < VC; ++c)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) o[rt][c][v] = 0.f;
+    mrun[rt] = -INFINITY;
+    lrun[rt] = 0.f;
+    const int rr = rt * 32 + r;
+    lim[rt] = (rr < R) ? L + rr / group : -1;
+  }
+
+  auto consume = [&](int j, bf16x8_t(&kreg)[KS], bf16x8_t(&vreg)[VC][2]) {
+    asm volatile("" ::: "memory");  // keep the query operand reads inside the loop (hoisted, they cost 32 VGPRs per row tile)
+    // The pins sit at the point of use: placed after the loads they would count as a use and make the wave
+    // wait for every load at once.
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) FSV_IN_AGPR(kreg[ks]);
+#pragma unroll
+    for (int c = 0; c < VC; ++c) {
+      FSV_IN_AGPR(vreg[c][0]);
+      FSV_IN_AGPR(vreg[c][1]);
+    }
+    const int kbase = (t0 + j) * 32;
+    const bool need_mask = kbase + 31 > L;  // every query row sees all keys <= L
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+      if (rt >= rtc) continue;
+      f32x16_t s;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+        uint4 raw = s_q[(rt * KS + ks) * 64 + lane];
+        FSV_IN_VGPR(s);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[ks], *reinterpret_cast<bf16x8_t *>(&raw), s, 0, 0, 0);
+      }
+      FSV_IN_VGPR(s);
+      // accumulator v of this lane: key kbase + 8*(v/4) + 4h + v%4, query row rt*32 + r
+      float tmax = -INFINITY;
+      if (need_mask) {
+        const int limit = lim[rt];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int key = kbase + 8 * (v >> 2) + 4 * h + (v & 3);
+          s[v] = (key <= limit) ? s[v] * sc : -INFINITY;
+          tmax = fmaxf(tmax, s[v]);
+        }
+      } else {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          s[v] *= sc;
+          tmax = fmaxf(tmax, s[v]);
+        }
+      }
+      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+      // Lazy reference: the running reference m only moves when the tile maximum exceeds it by more than 2^8
+      // (probabilities then stay below 256, exact enough in fp32 / bf16), so the accumulators are almost never
+      // rescaled; the first tile of a row needs no rescale either (its accumulators are still zero).
+      const float mold = mrun[rt];
+      const float mnew = (tmax > mold + 8.0f || mold == -INFINITY) ? fmaxf(mold, tmax) : mold;
+      const float muse = (mnew == -INFINITY) ? 0.f : mnew;
+      const float alpha = __builtin_amdgcn_exp2f(mold - muse);
+      const bool rescale = __any(mnew != mold && mold != -INFINITY);
+      mrun[rt] = mnew;
+      float psum = 0.f;
+      bf16x8_t pb[2];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const float p = __builtin_amdgcn_exp2f(s[v] - muse);
+        psum += p;
+        pb[v >> 3][v & 7] = (__bf16)p;
+      }
+      lrun[rt] = lrun[rt] * alpha + psum;
+      if (rescale) {  // wave-uniform: once the running maxima have settled the accumulators are left alone
+#pragma unroll
+        for (int c = 0; c < VC; ++c)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o[rt][c][v] *= alpha;
+      }
+#pragma unroll
+      for (int c = 0; c < VC; ++c) {
+        FSV_IN_VGPR(o[rt][c]);
+        o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][0], pb[0], o[rt][c], 0, 0, 0);
+        FSV_IN_VGPR(o[rt][c]);
+        o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pb[1], o[rt][c], 0, 0, 0);
+        FSV_IN_VGPR(o[rt][c]);
+      }
+      __builtin_amdgcn_sched_barrier(0);  // row tiles one after the other: interleaved, their temporaries add up
+    }
+  };
+
+  // Step S of an unrolled round consumes buffer S and refills buffer S - 1 (the one consumed just before) with the
+  // tile NB - 1 ahead; buffers rotate by name.  Page ids are fetched one step before the loads that use them.
+  const int myt_pad = (myt + NB - 1) / NB * NB;
+  for (int j = 0; j < myt_pad; j += NB) {
+#pragma unroll
+    for (int S = 0; S < NB; ++S) {
+      issue(j + S + NB - 1, g0n, g1n, kb[(S + NB - 1) % NB], vb[(S + NB - 1) % NB]);
+      pages_of(j + S + NB, g0n, g1n);
+      __builtin_amdgcn_sched_barrier(0);
+      if (j + S < myt) consume(j + S, kb[S], vb[S]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // result of this wave: lane holds, for query row rt*32 + r, features 32c + 8g + 4h + (0..3)
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    if (rt >= rtc) continue;
+    const int rr = rt * 32 + r;
+    const float ll = lrun[rt] + __shfl_xor(lrun[rt], 32, 64);
+    if (rr >= R) continue;
+    if (nparts == 1) {
+      const float inv = 1.0f / ll;
+      const int m = rs + rr / group, col = (kvh * group + rr % group) * HD;
+#pragma unroll
+      for (int c = 0; c < VC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int e0 = 32 * c + 8 * g;
+          const uint32_t lo = (uint32_t)f2bf(o[rt][c][4 * g] * inv) | ((uint32_t)f2bf(o[rt][c][4 * g + 1] * inv) << 16);
+          const uint32_t hi = (uint32_t)f2bf(o[rt][c][4 * g + 2] * inv) | ((uint32_t)f2bf(o[rt][c][4 * g + 3] * inv) << 16);
+          *reinterpret_cast<uint2 *>(out + tile_unit(m, col + e0, KBq) * 8 + 4 * h) = make_uint2(lo, hi);
+        }
+    } else {
+      const size_t prow = (size_t)gw * rows_cap + rr;
+      if (h == 0) *reinterpret_cast<float2 *>(part_ml + prow * 2) = make_float2(mrun[rt], ll);
+      float *dst = part_o + prow * HD + 4 * h;
+#pragma unroll
+      for (int c = 0; c < VC; ++c)
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+          *reinterpret_cast<float4 *>(dst + 32 * c + 8 * g) =
+              make_float4(o[rt][c][4 * g], o[rt][c][4 * g + 1], o[rt][c][4 * g + 2], o[rt][c][4 * g + 3]);
+    }
+  }
+}
+
+// merge the parts of requests that have several, in part order.  grid = (kv heads, requests, row groups)
+template <int HD>
+__global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int rows_cap,
+                                                      const int32_t *__restrict__ off,
+                                                      const int32_t *__restrict__ part_prefix,
+                                                      const float *__restrict__ part_o,
+                                                      const float *__restrict__ part_ml, uint16_t *__restrict__ out,
+                                                      int KBq) {
+  constexpr int TPR = HD / 8, RPB = 256 / TPR;  // threads per row (eight features each), rows per block
+  const int b = blockIdx.y, kvh = blockIdx.x, tid = threadIdx.x;
+  const int p0 = part_prefix[b], nparts = part_prefix[b + 1] - p0;
+  if (nparts <= 1) return;
+  const int gamma = off[b + 1] - off[b], rs = off[b] + b, R = group * (gamma + 1);
+  const int rr = blockIdx.z * RPB + tid / TPR, e0 = (tid % TPR) * 8;
+  if (rr >= R) return;
+  const size_t base = ((size_t)p0 * Hkv + kvh) * rows_cap + rr, pstr = (size_t)Hkv * rows_cap;
+  float mm = -INFINITY;
+  for (int s = 0; s < nparts; ++s) mm = fmaxf(mm, part_ml[(base + s * pstr) * 2]);
+  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ll = 0.f;
+  for (int s = 0; s < nparts; ++s) {
+    const size_t prow = base + s * pstr;
+    const float2 ml = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
+    const float f = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - mm);
+    ll += ml.y * f;
+    const float *src = part_o + prow * HD + e0;
+    float4 a = *reinterpret_cast<const float4 *>(src), c = *reinterpret_cast<const float4 *>(src + 4);
+    acc[0] += a.x * f; acc[1] += a.y * f; acc[2] += a.z * f; acc[3] += a.w * f;
+    acc[4] += c.x * f; acc[5] += c.y * f; acc[6] += c.z * f; acc[7] += c.w * f;
+  }
+  const float inv = 1.0f / ll;
+  uint32_t pk[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) pk[j] = (uint32_t)f2bf(acc[2 * j] * inv) | ((uint32_t)f2bf(acc[2 * j + 1] * inv) << 16);
+  const int m = rs + rr / group, col = (kvh * group + rr % group) * HD + e0;
+  reinterpret_cast<uint4 *>(out)[tile_unit(m, col, KBq)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
+}
+
+int attn_waves_per_cu() {  // resident waves per compute unit the attention schedule is sized for
+  static int v = 0;
+  if (!v) {
+    const char *e = getenv("FSV_ATTN_WAVES_PER_CU");
+    v = e ? atoi(e) : 4;
+    if (v < 1 || v > 16) v = 4;
+  }
+  return v;
+}
+
+// Size the parts from the host copies of the lengths: the smallest part length for which parts x kv heads
+// still fits the machine once (or one part per request when even that does not fit).
+int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
+  const fsv_model_desc &d = c->d;
+  int max_n = 1, max_rows = 0;
+  long total_tiles = 0;
+  for (int i = 0; i < b->batch; ++i) {
+    const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
+    const int n = fsv_ceil_div(nk, 32);
+    max_n = max(max_n, n);
+    max_rows = max(max_rows, c->group * (g + 1));
+    total_tiles += n;
+    pl->kv_tokens += nk;
+  }
+  const int target = c->attn_wave_target;
+  int tpw = (int)max(2L, (total_tiles * d.n_kv_heads + target - 1) / target);
+  for (;; ++tpw) {
+    int parts = 0;
+    bool split = false;
+    for (int i = 0; i < b->batch; ++i) {
+      const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
+      int tp;
+      const int s = attn_parts(fsv_ceil_div(nk, 32), tpw, &tp);
+      parts += s;
+      split |= s > 1;
+    }
+    if (parts * d.n_kv_heads <= target || tpw >= max_n) {
+      pl->tpw = tpw;
+      pl->waves = parts * d.n_kv_heads;
+      pl->split = split;
+      break;
+    }
+  }
+  pl->rt = fsv_ceil_div(max_rows, 32);
+  if (pl->waves > c->attn_wave_cap) FSV_FAIL(c, FSV_E_CAPACITY, "%d attention parts > %d the workspace holds", pl->waves, c->attn_wave_cap);
+  if ((size_t)b->num_pages * d.n_kv_heads * 16 * d.head_dim * 2 > 0xFFFF0000ull)
+    FSV_FAIL(c, FSV_E_UNSUPPORTED, "one layer of a KV pool must stay below 4 GiB (%d pages given)", b->num_pages);
+  return FSV_OK;
+}
+
+int launch_attn_plan(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, hipStream_t st) {
+  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(64), 0, st, b->batch, pl.tpw, b->seq_lens, b->draft_offsets,
+                     c->attn_part_prefix, c->attn_part_tiles, c->attn_part_map, c->attn_wave_cap / c->d.n_kv_heads + 1);
+  FSV_HIP(c, hipGetLastError());
+  return FSV_OK;
+}
+
+int launch_attention(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, size_t layer_off, hipStream_t st) {
+  const fsv_model_desc &d = c->d;
+  const int group = c->group, KBq = d.n_heads * d.head_dim / 16;
+  const int rows_cap = group * (d.max_gamma + 1);
+  const uint32_t layer_bytes = (uint32_t)((size_t)b->num_pages * d.n_kv_heads * 16 * d.head_dim * 2);
+  float *po = (float *)c->attn_part;
+  float *pml = po + (size_t)c->attn_wave_cap * rows_cap * d.head_dim;
+  uint16_t *out = (uint16_t *)c->buf_att;
+  const uint16_t *kl = (const uint16_t *)b->k_pool + layer_off, *vl = (const uint16_t *)b->v_pool + layer_off;
+  {
+    fsv_prof_scope ps(c, st, FSV_K_ATTENTION, pl.kv_tokens * d.n_kv_heads * d.head_dim * 4.0);
+#define FSV_ATTN_LAUNCH(HDV, RTV, NBV)                                                                            \
+  hipLaunchKernelGGL((k_attention<HDV, RTV, NBV>), dim3(pl.waves), dim3(64), 0, st, d.n_kv_heads, group, rows_cap, \
+                     (const uint4 *)c->buf_q, b->seq_lens, b->draft_offsets, c->attn_part_map, c->attn_part_prefix, \
+                     c->attn_part_tiles, b->page_table, d.max_pages_per_req, b->num_pages, kl, vl, layer_bytes, po, \
+                     pml, out, KBq)
+    if (d.head_dim == 128) {
+      if (pl.rt <= 1) FSV_ATTN_LAUNCH(128, 1, 4); else if (pl.rt == 2) FSV_ATTN_LAUNCH(128, 2, 4); else FSV_ATTN_LAUNCH(128, 3, 2);
+    } else {
+      if (pl.rt <= 1) FSV_ATTN_LAUNCH(64, 1, 4); else if (pl.rt == 2) FSV_ATTN_LAUNCH(64, 2, 4); else FSV_ATTN_LAUNCH(64, 3, 4);
+    }
+#undef FSV_ATTN_LAUNCH
+    FSV_HIP(c, hipGetLastError());
+  }
+  if (pl.split) {
+    fsv_prof_scope pc(c, st, FSV_K_ATTN_COMBINE, 0.0);
+    const int rpb = 256 / (d.head_dim / 8);
+    dim3 cg(d.n_kv_heads, b->batch, fsv_ceil_div(pl.rt * 32, rpb));
+    if (d.head_dim == 128)
+      hipLaunchKernelGGL((k_attn_combine<128>), cg, dim3(256), 0, st, d.n_kv_heads, group, rows_cap, b->draft_offsets,
+                         c->attn_part_prefix, po, pml, out, KBq);
+    else
+      hipLaunchKernelGGL((k_attn_combine<64>), cg, dim3(256), 0, st, d.n_kv_heads, group, rows_cap, b->draft_offsets,
+                         c->attn_part_prefix, po, pml, out, KBq);
+    FSV_HIP(c, hipGetLastError());
+  }
+  return FSV_OK;
+}
+
+}  // namespace
+
+int fsv_bf16_attn_plan(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl, hipStream_t st) {
+  int rc = plan_attention(c, b, pl);
+  if (rc) return rc;
+  return launch_attn_plan(c, b, *pl, st);
+}
+
+int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, size_t layer_off, hipStream_t st) {
+  return launch_attention(c, b, *pl, layer_off, st);
+}
+
+int fsv_bf16_attn_create(fsv_ctx *c) {
+  const fsv_model_desc &d = c->d;
+  int dev = 0, cus = 0;
+  FSV_HIP(c, hipGetDevice(&dev));
+  FSV_HIP(c, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+  c->attn_wave_target = max(cus, 1) * attn_waves_per_cu();
+  c->attn_wave_cap = max(c->attn_wave_target, d.max_batch * d.n_kv_heads);
+  const int rows_cap = c->group * (d.max_gamma + 1);
+  c->attn_part_bytes = (size_t)c->attn_wave_cap * rows_cap * (d.head_dim + 2) * 4;
+  auto zalloc = [&](void **p, size_t bytes) -> int {
+    FSV_HIP(c, hipMalloc(p, bytes));
+    FSV_HIP(c, hipMemset(*p, 0, bytes));
+    return FSV_OK;
+  };
+  int rc;
+  if ((rc = zalloc(&c->attn_part, c->attn_part_bytes))) return rc;
+  if ((rc = zalloc((void **)&c->attn_part_prefix, sizeof(int32_t) * (d.max_batch + 1)))) return rc;
+  if ((rc = zalloc((void **)&c->attn_part_tiles, sizeof(int32_t) * d.max_batch))) return rc;
+  if ((rc = zalloc((void **)&c->attn_part_map, sizeof(int32_t) * (c->attn_wave_cap / d.n_kv_heads + 1)))) return rc;
+  return FSV_OK;
+}

@@ -66,9 +66,11 @@ struct fsv_ctx {
   void *buf_a = nullptr, *buf_qkv = nullptr, *buf_q = nullptr, *buf_att = nullptr, *buf_gu = nullptr,
        *buf_act = nullptr, *buf_part = nullptr;
   size_t part_bytes = 0;
-  void *attn_part = nullptr;    // split-KV partial results
+  void *attn_part = nullptr;    // per-part attention results (O, then (m, l)) of requests with several parts
   size_t attn_part_bytes = 0;
-  int attn_max_splits = 0;
+  int attn_wave_target = 0;     // waves the attention schedule aims at (resident waves of the device)
+  int attn_wave_cap = 0;        // waves the partial buffers hold
+  int32_t *attn_part_prefix = nullptr, *attn_part_tiles = nullptr, *attn_part_map = nullptr;
 
   // profiling
   uint32_t prof_mask = 0;
@@ -126,6 +128,17 @@ int fsv_f32_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float
 int fsv_f32_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s);
 int fsv_f32_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,
                     void *k_lin, void *v_lin, bool import, hipStream_t s);
+// attn_bf16.hip
+struct fsv_attn_plan {
+  int tpw = 0;          // target key tiles per part
+  int waves = 0;        // parts x kv heads
+  int rt = 1;           // query-row tiles of the widest request
+  bool split = false;   // some request has several parts
+  double kv_tokens = 0;
+};
+int fsv_bf16_attn_create(fsv_ctx *c);
+int fsv_bf16_attn_plan(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl, hipStream_t s);
+int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, size_t layer_off, hipStream_t s);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
 int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);

@@ -13,35 +13,15 @@
 #include <math.h>
 #include <stdlib.h>
 
-#include "fsv_internal.h"
+#include "bf16_common.h"
+
+using namespace fsv_bf16;
 
 #ifndef FSV_EXP
 #define FSV_EXP 0  // timing experiments only (wrong results): 1 no activation staging, 2 no MFMA, 4 no LDS reads
 #endif
 
 namespace {
-
-typedef __hip_bfloat16 bf16;
-
-constexpr int KCHUNK = 256;       // contraction elements per split / group granule (a multiple of every chunk size)
-constexpr int RTMAX = 3;         // query-row tiles of 32 per (request, kv head): group * (gamma+1) <= 96
-constexpr float kLog2eF = 1.4426950408889634f;
-
-__device__ inline float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ inline uint16_t f2bf(float f) {  // round to nearest even (hardware conversion)
-  __bf16 b = (__bf16)f;
-  return __builtin_bit_cast(uint16_t, b);
-}
-__device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-  return v;
-}
-
-// offset, in 16-byte units, of the operand unit holding (row r, k .. k+7), k a multiple of 8
-__device__ __host__ inline size_t tile_unit(int r, int k, int KB) {
-  return ((size_t)(r >> 5) * KB + (k >> 4)) * 64 + (r & 31) + 32 * ((k >> 3) & 1);
-}
 
 // ---------------------------------------------------------------------------------------------
 // one-time weight re-tiling
@@ -396,14 +376,6 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
 // ---------------------------------------------------------------------------------------------
 // KV page tiles (16 positions x head_dim per kv head)
 // ---------------------------------------------------------------------------------------------
-// K tile: element (t, e) at ((e/16*2 + (e%16)/8)*16 + t)*8 + e%8       (operand of the score MFMA, rows = keys)
-// V tile: element (t, e) at ((e/32*2 + (t%8)/4)*32 + e%32)*8 + 4*(t/8) + t%4   (operand of the P.V MFMA, rows = features,
-//         contraction index ordered the way the score accumulators leave the probabilities in registers)
-__device__ __host__ inline int k_tile_off(int t, int e) { return (((e >> 4) * 2 + ((e >> 3) & 1)) * 16 + t) * 8 + (e & 7); }
-__device__ __host__ inline int v_tile_off(int t, int e) {
-  return (((e >> 5) * 2 + ((t >> 2) & 1)) * 32 + (e & 31)) * 8 + 4 * (t >> 3) + (t & 3);
-}
-
 __global__ void k_kv_copy(int Hkv, int hd, int num_pages, const int32_t *__restrict__ pt, int pos0, int n,
                           uint16_t *__restrict__ kpool, uint16_t *__restrict__ vpool, uint16_t *__restrict__ klin,
                           uint16_t *__restrict__ vlin, int import) {
@@ -426,13 +398,6 @@ __global__ void k_kv_copy(int Hkv, int hd, int num_pages, const int32_t *__restr
 // ---------------------------------------------------------------------------------------------
 // rotary embedding + KV append; consumes the split partials of the QKV projection
 // ---------------------------------------------------------------------------------------------
-// query operand: row rr = i*group + g of (request, kv head), feature e:
-//   (((b*RTMAX + rr/32)*Hkv + kvh)*(hd/16) + e/16)*64 + rr%32 + 32*((e%16)/8) units of 8, element e%8
-__device__ inline size_t q_elem_off(int b, int kvh, int rr, int e, int Hkv, int hd) {
-  return (((((size_t)b * RTMAX + (rr >> 5)) * Hkv + kvh) * (hd >> 4) + (e >> 4)) * 64 + (rr & 31) + 32 * ((e >> 3) & 1)) * 8 +
-         (e & 7);
-}
-
 __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, const double *__restrict__ inv_freq,
                                                      const float *__restrict__ part, int S, int Mpad,
                                                      const int32_t *__restrict__ row_req,
@@ -497,265 +462,6 @@ __global__ void k_pack_q(int H, int Hkv, int hd, const uint16_t *__restrict__ q,
   for (int idx = threadIdx.x; idx < H * hd; idx += blockDim.x) {
     const int hh = idx / hd, e = idx % hd;
     qp[q_elem_off(b, hh / group, i_row * group + hh % group, e, Hkv, hd)] = q[(size_t)r * H * hd + idx];
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
-// multi-query paged attention
-// ---------------------------------------------------------------------------------------------
-// One block = (key range of CH tokens, kv head, request); its four waves take 32-key tiles round robin.
-// Per tile a wave loads K and V page tiles straight into MFMA operand registers (each byte of the KV
-// stream is used by exactly one wave, all `group` query heads and all gamma+1 positions share it),
-// forms S^T = K Q^T (rows = keys, so a query row's scores sit in two lanes), does the online softmax in
-// registers, and feeds the probabilities back as the B operand of O^T += V^T P^T without any shuffle:
-// the V tile is stored in the key order the score accumulators produce.
-template <int HD, int RT>
-__global__ __launch_bounds__(256) void k_attention(
-    int Hkv, int group, int CH, int rows_max, int max_splits, const uint4 *__restrict__ qp,
-    const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ off, const int32_t *__restrict__ page_table,
-    int max_pages, int num_pages, const uint16_t *__restrict__ kpool, const uint16_t *__restrict__ vpool,
-    size_t layer_off, float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out, int KBq) {
-  constexpr int KS = HD / 16, VC = HD / 32, OSTR = HD + 4;
-  // the query operand and the wave-merge buffer share LDS: the queries are dead once every wave has left its key loop
-  constexpr int QBYTES = RT * KS * 64 * 16, OBYTES = RT * 32 * OSTR * 4;
-  __shared__ __attribute__((aligned(16))) unsigned char s_raw[QBYTES > OBYTES ? QBYTES : OBYTES];
-  uint4 *s_q = reinterpret_cast<uint4 *>(s_raw);
-  float *s_o = reinterpret_cast<float *>(s_raw);
-  __shared__ float s_m[4][RT * 32], s_l[4][RT * 32];
-  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, h = lane >> 5, r = lane & 31;
-  const int b = blockIdx.z, kvh = blockIdx.y, split = blockIdx.x;
-  const int L = seq_lens[b], gamma = off[b + 1] - off[b], rs = off[b] + b;
-  const int nk = L + gamma + 1, R = group * (gamma + 1);
-  const int nsplit = (nk + CH - 1) / CH;
-  if (split >= nsplit) return;
-  const int rtc = min(RT, (R + 31) >> 5);
-  const int key0 = split * CH, key1 = min(nk, key0 + CH);
-  const int ntiles = (key1 - key0 + 31) >> 5;
-  // queries -> LDS (zero for rows beyond R)
-  for (int i = tid; i < RT * KS * 64; i += 256) {
-    const int rt = i / (KS * 64), rem = i % (KS * 64), rr = rt * 32 + (rem & 31);
-    s_q[i] = (rr < R) ? qp[(((size_t)b * RTMAX + rt) * Hkv + kvh) * (KS * 64) + rem] : make_uint4(0, 0, 0, 0);
-  }
-  __syncthreads();
-
-  const float sc = kLog2eF / sqrtf((float)HD);
-  f32x16_t o[RT][VC];
-  float mrun[RT], lrun[RT];
-  int lim[RT];  // last key this lane's query row may see
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-#pragma unroll
-    for (int c = 0; c < VC; ++c)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) o[rt][c][v] = 0.f;
-    mrun[rt] = -INFINITY;
-    lrun[rt] = 0.f;
-    const int rr = rt * 32 + r;
-    lim[rt] = (rr < R) ? L + rr / group : -1;
-  }
-  const int32_t *pt = page_table + (size_t)b * max_pages;
-  const int npg = (nk + 15) >> 4;
-
-  auto tile_ptrs = [&](int tl, const uint16_t *&k0, const uint16_t *&k1, const uint16_t *&v0, const uint16_t *&v1) {
-    const int p0 = (key0 >> 4) + tl * 2, p1 = min(p0 + 1, npg - 1);
-    const int g0 = min(max(pt[p0], 0), num_pages - 1), g1 = min(max(pt[p1], 0), num_pages - 1);
-    const size_t t0 = layer_off + ((size_t)g0 * Hkv + kvh) * (16 * HD), t1 = layer_off + ((size_t)g1 * Hkv + kvh) * (16 * HD);
-    k0 = kpool + t0; k1 = kpool + t1; v0 = vpool + t0; v1 = vpool + t1;
-  };
-  // Tiles of this wave: w, w+4, ...  K and V of the next tile are fetched into a second register set while the
-  // current one is consumed (sets alternate by name); loads are never under a branch, so the tile index is clamped
-  // and a step past the wave's last tile is masked out completely instead of skipped.
-  const int myt = (ntiles > w) ? (ntiles - w + 3) >> 2 : 0;
-  bf16x8_t kA[KS], vA[VC][2], kB[KS], vB[VC][2];
-  auto load_tile = [&](int j, bf16x8_t(&kreg)[KS], bf16x8_t(&vreg)[VC][2]) {
-    const int tl = min(w + 4 * j, ntiles - 1);
-    const uint16_t *k0, *k1, *v0, *v1;
-    tile_ptrs(tl, k0, k1, v0, v1);
-    const uint16_t *kp = (r < 16) ? k0 : k1;  // operand row = key r: rows 0-15 first page, 16-31 second page
-#pragma unroll
-    for (int s = 0; s < KS; ++s)
-      kreg[s] = *reinterpret_cast<const bf16x8_t *>(kp + (((s * 2 + h) * 16) + (r & 15)) * 8);
-#pragma unroll
-    for (int c = 0; c < VC; ++c) {
-      vreg[c][0] = *reinterpret_cast<const bf16x8_t *>(v0 + ((c * 2 + h) * 32 + r) * 8);
-      vreg[c][1] = *reinterpret_cast<const bf16x8_t *>(v1 + ((c * 2 + h) * 32 + r) * 8);
-    }
-  };
-  auto consume = [&](int j, bf16x8_t(&kreg)[KS], bf16x8_t(&vreg)[VC][2]) {
-    asm volatile("" ::: "memory");  // keep the query operand reads inside the loop (hoisted, they cost 32 VGPRs per row tile)
-    const bool dead = j >= myt;
-    const int kbase = key0 + (w + 4 * j) * 32;
-    const bool need_mask = dead || (kbase + 31 > L);  // every query row sees all keys <= L
-#pragma unroll
-    for (int rt = 0; rt < RT; ++rt) {
-      if (rt >= rtc) continue;
-      f32x16_t s;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) s[v] = 0.f;
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks) {
-        uint4 raw = s_q[(rt * KS + ks) * 64 + lane];
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[ks], *reinterpret_cast<bf16x8_t *>(&raw), s, 0, 0, 0);
-      }
-      // accumulator v of this lane: key kbase + 8*(v/4) + 4h + v%4, query row rt*32 + r
-      float tmax = -INFINITY;
-      if (need_mask) {
-        const int limit = dead ? -1 : lim[rt];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int key = kbase + 8 * (v >> 2) + 4 * h + (v & 3);
-          s[v] = (key <= limit) ? s[v] * sc : -INFINITY;
-          tmax = fmaxf(tmax, s[v]);
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          s[v] *= sc;
-          tmax = fmaxf(tmax, s[v]);
-        }
-      }
-      tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
-      // Lazy reference: the running reference m only moves when the tile maximum exceeds it by more than 2^8
-      // (probabilities then stay below 256, exact enough in fp32 / bf16), so the accumulators are almost never
-      // rescaled; the first tile of a row needs no rescale either (its accumulators are still zero).
-      const float mold = mrun[rt];
-      const float mnew = (tmax > mold + 8.0f || mold == -INFINITY) ? fmaxf(mold, tmax) : mold;
-      const float muse = (mnew == -INFINITY) ? 0.f : mnew;
-      const float alpha = __builtin_amdgcn_exp2f(mold - muse);
-      const bool rescale = __any(mnew != mold && mold != -INFINITY);
-      mrun[rt] = mnew;
-      float psum = 0.f;
-      bf16x8_t pb[2];
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(s[v] - muse);
-        psum += p;
-        pb[v >> 3][v & 7] = (__bf16)p;
-      }
-      lrun[rt] = lrun[rt] * alpha + psum;
-      if (rescale) {  // wave-uniform: once the running maxima have settled the accumulators are left alone
-#pragma unroll
-        for (int c = 0; c < VC; ++c)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o[rt][c][v] *= alpha;
-      }
-#pragma unroll
-      for (int c = 0; c < VC; ++c) {
-        o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][0], pb[0], o[rt][c], 0, 0, 0);
-        o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pb[1], o[rt][c], 0, 0, 0);
-      }
-    }
-  };
-  if (myt > 0) {
-    load_tile(0, kA, vA);
-    const int myt_pad = (myt + 1) & ~1;
-    for (int j = 0; j < myt_pad; j += 2) {
-      load_tile(j + 1, kB, vB);
-      __builtin_amdgcn_sched_barrier(0);
-      consume(j, kA, vA);
-      load_tile(j + 2, kA, vA);
-      __builtin_amdgcn_sched_barrier(0);
-      consume(j + 1, kB, vB);
-    }
-  }
-
-  // merge the four waves (fixed order), then write the block's result
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    lrun[rt] += __shfl_xor(lrun[rt], 32, 64);
-    if (h == 0) { s_m[w][rt * 32 + r] = mrun[rt]; s_l[w][rt * 32 + r] = lrun[rt]; }
-  }
-  __syncthreads();
-  float fscale[RT];
-#pragma unroll
-  for (int rt = 0; rt < RT; ++rt) {
-    const int rr = rt * 32 + r;
-    const float mm = fmaxf(fmaxf(s_m[0][rr], s_m[1][rr]), fmaxf(s_m[2][rr], s_m[3][rr]));
-    fscale[rt] = (mrun[rt] == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mrun[rt] - mm);
-  }
-  for (int ww = 0; ww < 4; ++ww) {
-    if (w == ww) {
-#pragma unroll
-      for (int rt = 0; rt < RT; ++rt) {
-        if (rt >= rtc) continue;
-#pragma unroll
-        for (int c = 0; c < VC; ++c)
-#pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            float *dst = s_o + (rt * 32 + r) * OSTR + 32 * c + 8 * g + 4 * h;
-            float4 val = make_float4(o[rt][c][4 * g] * fscale[rt], o[rt][c][4 * g + 1] * fscale[rt],
-                                     o[rt][c][4 * g + 2] * fscale[rt], o[rt][c][4 * g + 3] * fscale[rt]);
-            if (ww > 0) {
-              float4 old = *reinterpret_cast<float4 *>(dst);
-              val.x += old.x; val.y += old.y; val.z += old.z; val.w += old.w;
-            }
-            *reinterpret_cast<float4 *>(dst) = val;
-          }
-      }
-    }
-    __syncthreads();
-  }
-  // every thread: rows rr = tid / (HD/8) + k * (256 / (HD/8)), eight features each
-  constexpr int TPR = HD / 8;
-  for (int rr = tid / TPR; rr < R; rr += 256 / TPR) {
-    const int e0 = (tid % TPR) * 8;
-    const float m0 = s_m[0][rr], m1 = s_m[1][rr], m2 = s_m[2][rr], m3 = s_m[3][rr];
-    const float mm = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-    auto sf = [&](float mw) { return (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - mm); };
-    const float ll = ((s_l[0][rr] * sf(m0) + s_l[1][rr] * sf(m1)) + s_l[2][rr] * sf(m2)) + s_l[3][rr] * sf(m3);
-    const float *src = s_o + rr * OSTR + e0;
-    if (nsplit == 1) {
-      const float inv = 1.0f / ll;
-      uint32_t pk[4];
-#pragma unroll
-      for (int j = 0; j < 4; ++j) pk[j] = (uint32_t)f2bf(src[2 * j] * inv) | ((uint32_t)f2bf(src[2 * j + 1] * inv) << 16);
-      const int m = rs + rr / group, col = (kvh * group + rr % group) * HD + e0;
-      reinterpret_cast<uint4 *>(out)[tile_unit(m, col, KBq)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
-    } else {
-      const size_t prow = (((size_t)b * Hkv + kvh) * max_splits + split) * rows_max + rr;
-      float *dst = part_o + prow * HD + e0;
-      *reinterpret_cast<float4 *>(dst) = *reinterpret_cast<const float4 *>(src);
-      *reinterpret_cast<float4 *>(dst + 4) = *reinterpret_cast<const float4 *>(src + 4);
-      if (e0 == 0) { part_ml[prow * 2] = mm; part_ml[prow * 2 + 1] = ll; }
-    }
-  }
-}
-
-// merge the key-range partials of requests that were split, in split order
-template <int HD>
-__global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int CH, int rows_max, int max_splits,
-                                                      const int32_t *__restrict__ seq_lens,
-                                                      const int32_t *__restrict__ off,
-                                                      const float *__restrict__ part_o,
-                                                      const float *__restrict__ part_ml, uint16_t *__restrict__ out,
-                                                      int KBq) {
-  const int b = blockIdx.y, kvh = blockIdx.x, tid = threadIdx.x;
-  const int L = seq_lens[b], gamma = off[b + 1] - off[b], rs = off[b] + b;
-  const int nk = L + gamma + 1, R = group * (gamma + 1), nsplit = (nk + CH - 1) / CH;
-  if (nsplit <= 1) return;
-  constexpr int TPR = HD / 8;
-  for (int rr = tid / TPR; rr < R; rr += 256 / TPR) {
-    const int e0 = (tid % TPR) * 8;
-    const size_t base = (((size_t)b * Hkv + kvh) * max_splits) * rows_max + rr;
-    float mm = -INFINITY;
-    for (int s = 0; s < nsplit; ++s) mm = fmaxf(mm, part_ml[(base + (size_t)s * rows_max) * 2]);
-    float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ll = 0.f;
-    for (int s = 0; s < nsplit; ++s) {
-      const size_t prow = base + (size_t)s * rows_max;
-      const float ms = part_ml[prow * 2];
-      const float f = (ms == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ms - mm);
-      ll += part_ml[prow * 2 + 1] * f;
-      const float *src = part_o + prow * HD + e0;
-      float4 a = *reinterpret_cast<const float4 *>(src), c = *reinterpret_cast<const float4 *>(src + 4);
-      acc[0] += a.x * f; acc[1] += a.y * f; acc[2] += a.z * f; acc[3] += a.w * f;
-      acc[4] += c.x * f; acc[5] += c.y * f; acc[6] += c.z * f; acc[7] += c.w * f;
-    }
-    const float inv = 1.0f / ll;
-    uint32_t pk[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) pk[j] = (uint32_t)f2bf(acc[2 * j] * inv) | ((uint32_t)f2bf(acc[2 * j + 1] * inv) << 16);
-    const int m = rs + rr / group, col = (kvh * group + rr % group) * HD + e0;
-    reinterpret_cast<uint4 *>(out)[tile_unit(m, col, KBq)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
   }
 }
 
@@ -883,63 +589,6 @@ int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, 
   return FSV_OK;
 }
 
-int attn_chunk() {
-  static int v = 0;
-  if (!v) {
-    const char *e = getenv("FSV_ATTN_CHUNK");
-    v = e ? atoi(e) : 512;
-    if (v < 128 || v % 128) v = 512;
-  }
-  return v;
-}
-
-int launch_attention(fsv_ctx *c, const fsv_batch *b, size_t layer_off, hipStream_t st) {
-  const fsv_model_desc &d = c->d;
-  const int CH = attn_chunk(), group = c->group, KBq = d.n_heads * d.head_dim / 16;
-  const int rows_max = group * (d.max_gamma + 1);
-  int max_nk = 0, max_rows = 0;
-  double kv_tokens = 0;
-  for (int i = 0; i < b->batch; ++i) {
-    const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
-    max_nk = max(max_nk, nk);
-    max_rows = max(max_rows, group * (g + 1));
-    kv_tokens += nk;
-  }
-  const int nsplit = fsv_ceil_div(max_nk, CH), rt = fsv_ceil_div(max_rows, 32);
-  if (nsplit > c->attn_max_splits) FSV_FAIL(c, FSV_E_CAPACITY, "%d key ranges > %d the workspace holds", nsplit, c->attn_max_splits);
-  dim3 grid(nsplit, d.n_kv_heads, b->batch);
-  {
-    fsv_prof_scope ps(c, st, FSV_K_ATTENTION, kv_tokens * d.n_kv_heads * d.head_dim * 4.0);
-    float *po = (float *)c->attn_part;
-    float *pml = po + (size_t)d.max_batch * d.n_kv_heads * c->attn_max_splits * rows_max * d.head_dim;
-    uint16_t *out = (uint16_t *)c->buf_att;
-#define FSV_ATTN_LAUNCH(HDV, RTV)                                                                                  \
-  hipLaunchKernelGGL((k_attention<HDV, RTV>), grid, dim3(256), 0, st, d.n_kv_heads, group, CH, rows_max,           \
-                     c->attn_max_splits, (const uint4 *)c->buf_q, b->seq_lens, b->draft_offsets, b->page_table,    \
-                     d.max_pages_per_req, b->num_pages, (const uint16_t *)b->k_pool, (const uint16_t *)b->v_pool,  \
-                     layer_off, po, pml, out, KBq)
-    if (d.head_dim == 128) {
-      if (rt <= 1) FSV_ATTN_LAUNCH(128, 1); else if (rt == 2) FSV_ATTN_LAUNCH(128, 2); else FSV_ATTN_LAUNCH(128, 3);
-    } else {
-      if (rt <= 1) FSV_ATTN_LAUNCH(64, 1); else if (rt == 2) FSV_ATTN_LAUNCH(64, 2); else FSV_ATTN_LAUNCH(64, 3);
-    }
-#undef FSV_ATTN_LAUNCH
-    FSV_HIP(c, hipGetLastError());
-    if (nsplit > 1) {
-      fsv_prof_scope pc(c, st, FSV_K_ATTN_COMBINE, 0.0);
-      dim3 cg(d.n_kv_heads, b->batch);
-      if (d.head_dim == 128)
-        hipLaunchKernelGGL((k_attn_combine<128>), cg, dim3(256), 0, st, d.n_kv_heads, group, CH, rows_max,
-                           c->attn_max_splits, b->seq_lens, b->draft_offsets, po, pml, out, KBq);
-      else
-        hipLaunchKernelGGL((k_attn_combine<64>), cg, dim3(256), 0, st, d.n_kv_heads, group, CH, rows_max,
-                           c->attn_max_splits, b->seq_lens, b->draft_offsets, po, pml, out, KBq);
-      FSV_HIP(c, hipGetLastError());
-    }
-  }
-  return FSV_OK;
-}
-
 size_t layer_stride(const fsv_ctx *c, int num_pages) {
   return (size_t)num_pages * c->d.n_kv_heads * 16 * c->d.head_dim;
 }
@@ -992,12 +641,7 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
   }
   c->part_bytes = part;
   if ((rc = zalloc(&c->buf_part, part))) return rc;
-  // attention key-range partials
-  const int CH = attn_chunk(), rows_max = c->group * (d.max_gamma + 1);
-  c->attn_max_splits = fsv_ceil_div(d.max_pages_per_req * 16, CH);
-  const size_t prow = (size_t)d.max_batch * d.n_kv_heads * c->attn_max_splits * rows_max;
-  c->attn_part_bytes = prow * (d.head_dim + 2) * 4;
-  if ((rc = zalloc(&c->attn_part, c->attn_part_bytes))) return rc;
+  if ((rc = fsv_bf16_attn_create(c))) return rc;
   FSV_HIP(c, hipDeviceSynchronize());
   return FSV_OK;
 }
@@ -1011,6 +655,8 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
   float *part = (float *)c->buf_part;
   const int nthr = min(1024, max(64, fsv_ceil_div(d.d_model / 8, 64) * 64));  // one 8-wide slice per thread
   int rc;
+  fsv_attn_plan pl;
+  if ((rc = fsv_bf16_attn_plan(c, b, &pl, s))) return rc;
   {
     fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
     hipLaunchKernelGGL(k_resid_norm<1>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
@@ -1028,7 +674,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
                          d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, (uint16_t *)b->k_pool,
                          (uint16_t *)b->v_pool);
     }
-    if ((rc = launch_attention(c, b, lo, s))) return rc;
+    if ((rc = fsv_bf16_attn_launch(c, b, &pl, lo, s))) return rc;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
@@ -1079,8 +725,10 @@ int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b,
   const fsv_model_desc &d = c->d;
   hipLaunchKernelGGL(k_pack_q, dim3(M), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim, (const uint16_t *)q,
                      c->row_req, c->row_idx, (uint16_t *)c->buf_q);
-  int rc = launch_attention(c, b, (size_t)layer * layer_stride(c, b->num_pages), s);
-  if (rc) return rc;
+  fsv_attn_plan pl;
+  int rc;
+  if ((rc = fsv_bf16_attn_plan(c, b, &pl, s))) return rc;
+  if ((rc = fsv_bf16_attn_launch(c, b, &pl, (size_t)layer * layer_stride(c, b->num_pages), s))) return rc;
   const int qd = d.n_heads * d.head_dim;
   const size_t n = (size_t)M * (qd / 8);
   hipLaunchKernelGGL(k_unpack_act, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const uint4 *)c->buf_att, M, qd, out);
