@@ -286,18 +286,35 @@ __global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int ro
   const int rr = blockIdx.z * RPB + tid / TPR, e0 = (tid % TPR) * 8;
   if (rr >= R) return;
   const size_t base = ((size_t)p0 * Hkv + kvh) * rows_cap + rr, pstr = (size_t)Hkv * rows_cap;
+  // Parts are taken eight at a time with all loads issued before the first use: one part per iteration would put
+  // a full memory round trip into every step of this short loop.  The sums still run in part order.
+  constexpr int U = 8;
   float mm = -INFINITY;
-  for (int s = 0; s < nparts; ++s) mm = fmaxf(mm, part_ml[(base + s * pstr) * 2]);
+  for (int s0 = 0; s0 < nparts; s0 += U) {
+    float mv[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) mv[u] = part_ml[(base + min(s0 + u, nparts - 1) * pstr) * 2];
+#pragma unroll
+    for (int u = 0; u < U; ++u) mm = fmaxf(mm, mv[u]);
+  }
   float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ll = 0.f;
-  for (int s = 0; s < nparts; ++s) {
-    const size_t prow = base + s * pstr;
-    const float2 ml = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
-    const float f = (ml.x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml.x - mm);
-    ll += ml.y * f;
-    const float *src = part_o + prow * HD + e0;
-    float4 a = *reinterpret_cast<const float4 *>(src), c = *reinterpret_cast<const float4 *>(src + 4);
-    acc[0] += a.x * f; acc[1] += a.y * f; acc[2] += a.z * f; acc[3] += a.w * f;
-    acc[4] += c.x * f; acc[5] += c.y * f; acc[6] += c.z * f; acc[7] += c.w * f;
+  for (int s0 = 0; s0 < nparts; s0 += U) {
+    float2 ml[U];
+    float4 a[U], c[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const size_t prow = base + min(s0 + u, nparts - 1) * pstr;
+      ml[u] = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
+      a[u] = *reinterpret_cast<const float4 *>(part_o + prow * HD + e0);
+      c[u] = *reinterpret_cast<const float4 *>(part_o + prow * HD + e0 + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const float f = (s0 + u >= nparts || ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[u].x - mm);
+      ll += ml[u].y * f;
+      acc[0] += a[u].x * f; acc[1] += a[u].y * f; acc[2] += a[u].z * f; acc[3] += a[u].w * f;
+      acc[4] += c[u].x * f; acc[5] += c[u].y * f; acc[6] += c[u].z * f; acc[7] += c[u].w * f;
+    }
   }
   const float inv = 1.0f / ll;
   uint32_t pk[4];

@@ -213,12 +213,13 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
   // Unrolled so that the weight buffers (period WS) and the activation slots (period 2) rotate by name, not by
   // copies.  The trip count is padded to the unroll factor instead of leaving the loop early (several exits make
   // the compiler keep one copy of the accumulators per exit); padded steps run on zeroed activations.
-  constexpr int UNR = (WS == 2) ? 2 : 6;
+  constexpr int UNR = (WS % 2 == 0) ? WS : 2 * WS;
   const int per_pad = (per + UNR - 1) / UNR * UNR;
 #define FSV_STEP(S) chunk_step(it + (S), wbuf[(S) % WS], wbuf[((S) + WS - 1) % WS], areg[(S) & 1], areg[((S) + 1) & 1]);
   for (int it = 0; it < per_pad; it += UNR) {
     FSV_STEP(0) FSV_STEP(1)
-    if constexpr (WS > 2) { FSV_STEP(2) FSV_STEP(3) FSV_STEP(4) FSV_STEP(5) }
+    if constexpr (UNR > 2) { FSV_STEP(2) FSV_STEP(3) }
+    if constexpr (UNR > 4) { FSV_STEP(4) FSV_STEP(5) }
   }
 #undef FSV_STEP
   if constexpr (WK > 1) {  // sum the groups in order through LDS (each group reuses its own staging area)
@@ -248,6 +249,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
     if (mt >= mtc) continue;
     const int m = (mt0 + mt) * 32 + (lane & 31);
     if constexpr (EPI == EPI_PARTIAL) {
+      if (m >= M) continue;  // the consumers read rows below M only
       float *dst = (float *)out + ((size_t)split * Mpad + m) * N;
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
@@ -574,6 +576,8 @@ int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, 
 #define FSV_GEMM_CASE(MTV)                                                                   \
   if (var == 1) rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 16, 2>(FSV_GEMM_ARGS)            \
                                : launch_gemm_t<MTV, EPI, 1, 16, 2>(FSV_GEMM_ARGS);           \
+  else if (var == 2) rc = launch_gemm_t<MTV, EPI, 1, 8, 3>(FSV_GEMM_ARGS);                   \
+  else if (var == 3) rc = launch_gemm_t<MTV, EPI, 1, 8, 4>(FSV_GEMM_ARGS);                   \
   else rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 8, 2>(FSV_GEMM_ARGS)                      \
                       : launch_gemm_t<MTV, EPI, 1, 8, 2>(FSV_GEMM_ARGS)
   switch (mt_blk) {
