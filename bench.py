@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (one extra untimed pass)")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three plain 1 GiB device copies, the known-size reference the HBM counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent; see DESIGN.md for how the step "
@@ -145,6 +147,13 @@ def main():
         ctx.profile_enable(False)
         out["kernels"] = {k: {"launches": v["launches"], "ms": round(v["total_ms"], 4),
                               "GBps": round(v["bytes"] / max(v["total_ms"], 1e-9) / 1e6, 1)} for k, v in bd.items()}
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, wl, req, weights, args.seed)
     print(json.dumps(out), flush=True)

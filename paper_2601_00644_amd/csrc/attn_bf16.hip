@@ -70,6 +70,7 @@ __global__ __launch_bounds__(64) void k_attention(
     float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out, int KBq) {
   constexpr int KS = HD / 16, VC = HD / 32, TILEB = 16 * HD * 2;  // TILEB: bytes of one (page, kv head) tile
   constexpr uint32_t OOB = 0xFFFF0000u;                            // offset no descriptor here reaches
+  constexpr int kStream = 2;  // non-temporal: K/V bytes are used once and should not displace the queries and partials in L2
   __shared__ uint4 s_q[RT * KS * 64];
   const int lane = threadIdx.x, h = lane >> 5, r = lane & 31;
   const int gw = blockIdx.x, pp = gw / Hkv, kvh = gw - pp * Hkv;
@@ -99,11 +100,11 @@ __global__ __launch_bounds__(64) void k_attention(
     const uint32_t ko = ((r < 16) ? b0 : b1) + klane, v0 = b0 + vlane, v1 = b1 + vlane;
 #pragma unroll
     for (int s = 0; s < KS; ++s)
-      kreg[s] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(krs, ko + s * 512, 0, 0));
+      kreg[s] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(krs, ko + s * 512, 0, kStream));
 #pragma unroll
     for (int c = 0; c < VC; ++c) {
-      vreg[c][0] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(vrs, v0 + c * 1024, 0, 0));
-      vreg[c][1] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(vrs, v1 + c * 1024, 0, 0));
+      vreg[c][0] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(vrs, v0 + c * 1024, 0, kStream));
+      vreg[c][1] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(vrs, v1 + c * 1024, 0, kStream));
     }
   };
 

@@ -147,7 +147,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
     for (int kb = 0; kb < KC; ++kb) dst[kb] = wrow[(size_t)(kb) * 64 + 0 * c];
 #else
 #pragma unroll
-    for (int kb = 0; kb < KC; ++kb) dst[kb] = wrow[(size_t)(c * KC + kb) * 64];
+    for (int kb = 0; kb < KC; ++kb) dst[kb] = __builtin_nontemporal_load(&wrow[(size_t)(c * KC + kb) * 64]);
 #endif
   };
   // Blocks walk their K range starting at different chunks (a fixed rotation per block): all blocks read the
