@@ -21,6 +21,22 @@ using namespace fsv_bf16;
 #define FSV_EXP 0  // timing experiments only (wrong results): 1 no activation staging, 2 no MFMA, 4 no LDS reads
 #endif
 
+#ifdef FSV_TRACE
+__device__ long long g_trace[4 * 8192];
+extern "C" int fsv_debug_trace_read(long long *out, int n) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(long long) * n);
+}
+#define FSV_TR(slot) const long long _tr##slot = (slot) == 1 ? (long long)(__builtin_amdgcn_s_getreg(63492) | ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32)) : wall_clock64();
+#define FSV_TR_END                                                                    \
+  if (threadIdx.x == 0) {                                                             \
+    const int _b = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);    \
+    if (_b < 8192) { g_trace[_b * 4] = _tr0; g_trace[_b * 4 + 1] = _tr1; g_trace[_b * 4 + 2] = _tr2; g_trace[_b * 4 + 3] = wall_clock64(); } \
+  }
+#else
+#define FSV_TR(slot)
+#define FSV_TR_END
+#endif
+
 namespace {
 
 // ---------------------------------------------------------------------------------------------
@@ -106,6 +122,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
                                                    void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
                                                    int cps, int nchunks, int KBo) {
   extern __shared__ uint4 lds_dyn[];
+  FSV_TR(0)
   constexpr int CHU = MT * KC * 64;  // 16-byte units of one staged activation chunk
   const int tid = threadIdx.x, grp = tid >> 8, gt = tid & 255, w = gt >> 6, lane = tid & 63, h = lane >> 5;
   uint4 *lds = lds_dyn + grp * 2 * CHU;
@@ -210,6 +227,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
     load_a(min(chunk_of(1), cmax), areg[1]);
   }
   __syncthreads();
+  FSV_TR(1)
   // Unrolled so that the weight buffers (period WS) and the activation slots (period 2) rotate by name, not by
   // copies.  The trip count is padded to the unroll factor instead of leaving the loop early (several exits make
   // the compiler keep one copy of the accumulators per exit); padded steps run on zeroed activations.
@@ -222,6 +240,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
     if constexpr (UNR > 4) { FSV_STEP(4) FSV_STEP(5) }
   }
 #undef FSV_STEP
+  FSV_TR(2)
   if constexpr (WK > 1) {  // sum the groups in order through LDS (each group reuses its own staging area)
     float *red = reinterpret_cast<float *>(lds_dyn);
     for (int gsrc = 1; gsrc < WK; ++gsrc) {
@@ -297,6 +316,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
       }
     }
   }
+  FSV_TR_END
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -553,6 +573,14 @@ int launch_gemm_t(fsv_ctx *c, dim3 grid, const void *Wp, const void *Ap, void *o
     FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, WK, KC, WS>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
     attr_set = true;
+    if (getenv("FSV_DEBUG_OCC")) {
+    int nb = -1;
+    hipFuncAttributes fa;
+    (void)hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&k_gemm<MT, EPI, WK, KC, WS>));
+    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_gemm<MT, EPI, WK, KC, WS>, 256 * WK, lds);
+    fprintf(stderr, "k_gemm<%d,%d,%d,%d,%d>: numRegs %d static lds %zu dyn lds %zu -> blocks/CU %d\n", MT, EPI, WK, KC, WS, fa.numRegs,
+            fa.sharedSizeBytes, lds, nb);
+    }
   }
   // cps / nchunks are counted in KCHUNK granules; the kernel counts in its own chunk size
   const int f = KCHUNK / (KC * 16);
