@@ -127,6 +127,18 @@ def logits_close_bf16(got: np.ndarray, ref: np.ndarray, tol: float = 2e-2):
     return (elem <= tol and l2 <= tol), elem, l2
 
 
+def bf16_logit_tol(n_layers: int) -> float:
+    """The bf16 logit bar as a function of depth: 2e-2 up to 4 layers, then 9.6e-3 * sqrt(n_layers).
+
+    An exact (fp64) forward that merely STORES bf16 where the bf16 configuration does (GEMM inputs, q/k/v,
+    probabilities, attention output, SwiGLU output) differs from the fp64 forward by a worst-row L2 error of
+    0.64 % after 1 layer, 1.6 % after 8, 2.3 % after 16 and 3.3 % after 32 at the 8B shapes (measured with
+    plain torch fp64, independent of the library): about 6.4e-3 * sqrt(n_layers).  No kernel can do better
+    than that against the fp64 oracle, so beyond a few layers the bar is 1.5 times this inherent figure.
+    """
+    return max(2e-2, 9.6e-3 * float(np.sqrt(n_layers)))
+
+
 def compare_decisions(exp_list, tau, nxt, accept_flag=ACCEPT_FLAG, cdf_flag=CDF_FLAG):
     """Exact match of (tau, next token) except draws the oracle itself places within the flag margins.
 
