@@ -120,15 +120,31 @@ enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };
 template <int MT, int EPI, int WK, int KC, int WS>
 __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ Wp, const uint4 *__restrict__ Ap,
                                                    void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                                   int cps, int nchunks, int KBo) {
+                                                   int S, int nchunks, int gran, int KBo) {
   extern __shared__ uint4 lds_dyn[];
   FSV_TR(0)
   constexpr int CHU = MT * KC * 64;  // 16-byte units of one staged activation chunk
   const int tid = threadIdx.x, grp = tid >> 8, gt = tid & 255, w = gt >> 6, lane = tid & 63, h = lane >> 5;
   uint4 *lds = lds_dyn + grp * 2 * CHU;
-  const int nt = blockIdx.x * 4 + w, split = blockIdx.y, mt0 = blockIdx.z * MT;
+  // Blocks are dealt to the eight XCDs round robin by their linear index.  With a multiple of eight splits the
+  // index is decoded so that a split always lands on the same XCD: every XCD then stages only its own K slices of
+  // the activation matrix, which stay in its L2, instead of all of it.
+  int nblk, split;
+  {
+    const int L = blockIdx.x;
+    if ((S & 7) == 0) {
+      const int a = L >> 3, s8 = S >> 3;
+      split = (L & 7) + 8 * (a % s8);
+      nblk = a / s8;
+    } else {
+      split = L % S;
+      nblk = L / S;
+    }
+  }
+  const int nt = nblk * 4 + w, mt0 = blockIdx.z * MT;
   const int mtc = min(MT, Mt_total - mt0);
-  const int cb0 = split * cps, cb1 = min(cb0 + cps, nchunks);
+  // K range of the split: a balanced cut of the `nchunks` granules (of gran chunks each) into S parts
+  const int cb0 = (split * nchunks / S) * gran, cb1 = ((split + 1) * nchunks / S) * gran;
   const int per = (max(cb1 - cb0, 0) + WK - 1) / WK;  // iterations every group runs (barriers stay uniform)
   const int c0 = cb0 + grp * per, c1 = min(c0 + per, cb1);
   f32x16_t acc[MT];
@@ -145,7 +161,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
   // Loads are never put under a branch: a branch around a global load makes the compiler wait for ALL
   // outstanding loads at the join, which would drain the weight prefetch every iteration.  Out-of-range
   // chunks are clamped to a valid address and their activations masked to zero instead.
-  const int cmax = nchunks - 1, mlast = mtc - 1;
+  const int cmax = nchunks * gran - 1, mlast = mtc - 1;
   auto load_a = [&](int c, uint4(&dst)[APT]) {
 #pragma unroll
     for (int p = 0; p < APT; ++p) {
@@ -169,7 +185,7 @@ __global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ 
   };
   // Blocks walk their K range starting at different chunks (a fixed rotation per block): all blocks read the
   // same small activation matrix, and in lockstep they would all hit the same few L2 channels at once.
-  const int rot = per > 0 ? (int)((blockIdx.x * 5u + blockIdx.y * 3u + grp) % (unsigned)per) : 0;
+  const int rot = per > 0 ? (int)(((unsigned)nblk * 5u + (unsigned)split * 3u + grp) % (unsigned)per) : 0;
   auto chunk_of = [&](int it) { return c0 + (per > 0 ? (it + rot) % per : 0); };
   auto live = [&](int it, int c) -> uint32_t { return (it < per && c < c1) ? 0xffffffffu : 0u; };
   auto lds_op = [&](int buf, int mt, int kb) {
@@ -525,8 +541,8 @@ int pick_splits(const gemm_shape &s, int Mt, bool allow) {
   const int nchunks = s.K / KCHUNK, base = (s.NTpad / 4) * fsv_ceil_div(Mt, 4);
   int sp = target_blocks() / base;
   sp = max(1, min(sp, nchunks));
-  const int cps = fsv_ceil_div(nchunks, sp);
-  return fsv_ceil_div(nchunks, cps);  // no empty split
+  if (sp >= 8) sp &= ~7;  // a multiple of eight keeps each split on one XCD (see k_gemm); the K cut is balanced, not equal
+  return sp;
 }
 
 int pack_weight(fsv_ctx *c, const void *src, int which, void **dst) {
@@ -566,7 +582,7 @@ int gemm_variant() {  // chunk size / weight stages under test: 0 = 128-deep chu
 
 template <int MT, int EPI, int WK, int KC, int WS>
 int launch_gemm_t(fsv_ctx *c, dim3 grid, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int Mt, int M,
-                  int Mpad, int cps, int nchunks, int KBo, hipStream_t st) {
+                  int Mpad, int splits, int nchunks, int KBo, hipStream_t st) {
   const size_t lds = (size_t)WK * 2 * MT * KC * 64 * 16;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
@@ -582,10 +598,10 @@ int launch_gemm_t(fsv_ctx *c, dim3 grid, const void *Wp, const void *Ap, void *o
             fa.sharedSizeBytes, lds, nb);
     }
   }
-  // cps / nchunks are counted in KCHUNK granules; the kernel counts in its own chunk size
+  // nchunks is counted in KCHUNK granules; the kernel counts in its own chunk size, gran chunks to a granule
   const int f = KCHUNK / (KC * 16);
   hipLaunchKernelGGL((k_gemm<MT, EPI, WK, KC, WS>), grid, dim3(256 * WK), lds, st, (const bf16x8_t *)Wp,
-                     (const uint4 *)Ap, out, s.N, s.K / 16, Mt, M, Mpad, cps * f, nchunks * f, KBo);
+                     (const uint4 *)Ap, out, s.N, s.K / 16, Mt, M, Mpad, splits, nchunks, f, KBo);
   return FSV_OK;
 }
 
@@ -593,14 +609,13 @@ template <int EPI>
 int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, int splits,
                 hipStream_t st) {
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = s.K / KCHUNK;
-  const int cps = fsv_ceil_div(nchunks, splits);
   const int mt_blk = Mt >= 4 ? 4 : Mt, mblocks = fsv_ceil_div(Mt, mt_blk);
-  dim3 grid(s.NTpad / 4, splits, mblocks);
+  dim3 grid(s.NTpad / 4 * splits, 1, mblocks);
   const int KBo = (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0;
-  const int wk = (cps >= 2) ? gemm_groups() : 1, var = gemm_variant();
+  const int wk = (nchunks / splits >= 2) ? gemm_groups() : 1, var = gemm_variant();
   fsv_prof_scope ps(c, st, cls, (double)s.N * s.K * 2);
   int rc;
-#define FSV_GEMM_ARGS c, grid, Wp, Ap, out, s, Mt, M, Mpad, cps, nchunks, KBo, st
+#define FSV_GEMM_ARGS c, grid, Wp, Ap, out, s, Mt, M, Mpad, splits, nchunks, KBo, st
 #define FSV_GEMM_CASE(MTV)                                                                   \
   if (var == 1) rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 16, 2>(FSV_GEMM_ARGS)            \
                                : launch_gemm_t<MTV, EPI, 1, 16, 2>(FSV_GEMM_ARGS);           \
