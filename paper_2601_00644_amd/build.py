@@ -19,7 +19,7 @@ FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.j
 
 
 # per-file flags: the attention kernels keep their MFMA accumulators in architectural registers
-EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
+EXTRA = {"attn_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"], "gemm_bf16.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def sources():

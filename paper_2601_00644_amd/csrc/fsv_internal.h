@@ -139,6 +139,10 @@ struct fsv_attn_plan {
 int fsv_bf16_attn_create(fsv_ctx *c);
 int fsv_bf16_attn_plan(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl, hipStream_t s);
 int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, size_t layer_off, hipStream_t s);
+// gemm_bf16.hip: y = x W^T through the weight-streaming kernel; epi 0 = fp32 split partials [splits][Mpad][N],
+// 1 = SwiGLU to the bf16 operand order, 2 = fp32 rows [M][N]
+int fsv_bf16_gemm(fsv_ctx *c, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits,
+                  int KBo, hipStream_t st);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
 int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);

@@ -1,0 +1,246 @@
+// Weight-streaming bf16 GEMM of the FSV_BF16 path: the dense projections of the target forward (Alg. 2
+// step 2) for a few dozen to a few hundred rows, where streaming the weight matrix from HBM is the bound.
+// Built with -mllvm -amdgpu-mfma-vgpr-form (accumulators in architectural registers, the weight chunks in
+// flight in accumulation registers).
+//
+// A block is four compute waves and one loader wave.  Compute wave w owns 32 output features (one weight
+// tile row) for up to MT*32 batch rows over the block's K range and streams that strip of the re-tiled
+// matrix straight from HBM into MFMA operand registers, D chunks of 128 k ahead of its use.  The loader wave
+// copies the activation chunks of the same K range from global memory (L2) directly into a three-stage LDS
+// ring, two chunks ahead; the compute waves read their B operands from the ring.  Because the activation
+// loads are issued by a wave of their own, the compute waves' load counter tracks the weight stream only
+// and a wait for the oldest chunk never drains the younger ones.  One barrier per chunk hands a filled
+// stage to the compute waves and a consumed one back to the loader.
+#include <math.h>
+
+#include "bf16_common.h"
+
+using namespace fsv_bf16;
+
+namespace {
+
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+
+#define FSV_IN_AGPR(x) asm("" : "+a"(x))
+// The barrier as an opaque statement: memory operations do not move across it, and no counter wait is attached.
+#define FSV_BARRIER() asm volatile("s_barrier" ::: "memory")
+
+constexpr int KC = 8;     // 16-wide k blocks per chunk (128 contraction elements)
+constexpr int NST = 3;    // LDS stages of the activation ring
+constexpr int GRAN = 2;   // chunks per 256-element granule of the K cut
+
+template <int MT, int EPI, int D>
+__global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
+                                              void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
+                                              int S, int nchunks, int KBo) {
+  extern __shared__ uint4 lds[];
+  constexpr int CHU = MT * KC * 64;  // 16-byte units of one activation chunk
+  const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5;
+  // Blocks are dealt to the eight XCDs round robin by their linear index.  With a multiple of eight splits the
+  // index is decoded so that a split always lands on the same XCD: every XCD then stages only its own K slices of
+  // the activation matrix, which stay in its L2, instead of all of it.
+  int nblk, split;
+  {
+    const int L = blockIdx.x;
+    if ((S & 7) == 0) {
+      const int a = L >> 3, s8 = S >> 3;
+      split = (L & 7) + 8 * (a % s8);
+      nblk = a / s8;
+    } else {
+      split = L % S;
+      nblk = L / S;
+    }
+  }
+  const int mt0 = blockIdx.z * MT, mtc = min(MT, Mt_total - mt0), mlast = mtc - 1;
+  // K range of the split: a balanced cut of the `nchunks` granules into S parts, counted in chunks
+  const int cb0 = (split * nchunks / S) * GRAN, per = ((split + 1) * nchunks / S) * GRAN - cb0;
+
+  if (w == 4) {
+    // ---- loader wave: activation chunk `it` -> LDS stage it % NST, one 1 KiB row of units per instruction ----
+    auto fill = [&](int it) {
+      uint4 *dst = lds + (it % NST) * CHU;
+#pragma unroll
+      for (int i = 0; i < MT * KC; ++i) {
+        const int mt = min(i / KC, mlast);
+        const uint4 *src = Ap + ((size_t)(mt0 + mt) * KB + (size_t)(cb0 + it) * KC + i % KC) * 64 + lane;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                         (__attribute__((address_space(3))) void *)(dst + i * 64), 16, 0, 0);
+      }
+    };
+    fill(0);
+    if (per > 1) {
+      fill(1);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MT * KC) : "memory");  // chunk 0 has landed, chunk 1 may be in flight
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    FSV_BARRIER();
+    for (int it = 0; it < per; ++it) {
+      // stage (it + 2) % NST was read during step it - 1, which every compute wave left at the last barrier
+      if (it + 2 < per) {
+        fill(it + 2);
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MT * KC) : "memory");  // chunk it + 1 has landed
+      } else {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      }
+      FSV_BARRIER();
+    }
+    return;
+  }
+
+  // ---- compute waves ----
+  const int nt = nblk * 4 + w;
+  const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, wbytes, 0x00020000);
+  const uint32_t wbase = ((uint32_t)nt * (uint32_t)KB * 64u + (uint32_t)lane) * 16u;
+  constexpr uint32_t OOB = 0xFFFF0000u;  // a chunk beyond the K range: the descriptor returns zeros, no memory traffic
+  bf16x8_t wb[D + 1][KC];
+  auto issue = [&](int it, bf16x8_t(&dst)[KC]) {
+    const uint32_t off = (it < per) ? wbase + (uint32_t)(cb0 + it) * (KC * 1024u) : OOB;
+#pragma unroll
+    for (int kb = 0; kb < KC; ++kb)
+      dst[kb] = __builtin_bit_cast(bf16x8_t, __builtin_amdgcn_raw_buffer_load_b128(wrs, off + kb * 1024u, 0, 2));
+  };
+  f32x16_t acc[MT];
+#pragma unroll
+  for (int i = 0; i < MT; ++i)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
+#pragma unroll
+  for (int j = 0; j < D; ++j) issue(j, wb[j]);
+  FSV_BARRIER();
+
+  auto consume = [&](int it, bf16x8_t(&wuse)[KC]) {
+    const uint4 *stage = lds + (it % NST) * CHU + lane;
+#pragma unroll
+    for (int kb = 0; kb < KC; ++kb) {
+      FSV_IN_AGPR(wuse[kb]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        uint4 raw = stage[(mt * KC + kb) * 64];
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], *reinterpret_cast<bf16x8_t *>(&raw), acc[mt], 0, 0, 0);
+      }
+    }
+  };
+  // Step s of an unrolled round consumes buffer s and refills the buffer consumed just before it with the chunk D
+  // ahead; buffers rotate by name.  Steps past the K range are skipped whole, so that every wave of the block meets
+  // exactly 1 + per barriers.
+  for (int it = 0; it < per; it += D + 1) {
+#pragma unroll
+    for (int s = 0; s <= D; ++s) {
+      issue(it + s + D, wb[(s + D) % (D + 1)]);
+      __builtin_amdgcn_sched_barrier(0);
+      if (it + s < per) {
+        consume(it + s, wb[s]);
+        FSV_BARRIER();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+
+  // epilogue: lane holds, for batch row m = tile*32 + lane%32, features nt*32 + 8*(v/4) + 4*h + v%4
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt >= mtc) continue;
+    const int m = (mt0 + mt) * 32 + (lane & 31);
+    if constexpr (EPI == EPI_PARTIAL) {
+      if (m >= M) continue;  // the consumers read rows below M only
+      float *dst = (float *)out + ((size_t)split * Mpad + m) * N;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n0 = nt * 32 + 8 * g + 4 * h;
+        if (n0 + 3 < N) {
+          *reinterpret_cast<float4 *>(dst + n0) =
+              make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
+        }
+      }
+    } else if constexpr (EPI == EPI_F32) {
+      if (m < M) {
+        float *dst = (float *)out + (size_t)m * N;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n0 = nt * 32 + 8 * g + 4 * h;
+          if (n0 + 3 < N && (N & 3) == 0) {
+            *reinterpret_cast<float4 *>(dst + n0) =
+                make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
+          }
+        }
+      }
+    } else {  // SwiGLU: regs 0-3 gate / 4-7 up of features 16*nt + 4h + r, regs 8-11 / 12-15 of 16*nt + 8 + 4h + r
+      if (nt < KBo) {
+        uint16_t *base = (uint16_t *)out;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          uint16_t o4[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float gte = acc[mt][8 * j + r], up = acc[mt][8 * j + 4 + r];
+            o4[r] = f2bf(gte / (1.0f + __expf(-gte)) * up);
+          }
+          const size_t unit = ((size_t)(mt0 + mt) * KBo + nt) * 64 + (lane & 31) + 32 * j;
+          uint2 pk = make_uint2((uint32_t)o4[0] | ((uint32_t)o4[1] << 16), (uint32_t)o4[2] | ((uint32_t)o4[3] << 16));
+          *reinterpret_cast<uint2 *>(base + unit * 8 + 4 * h) = pk;
+        }
+      }
+    }
+  }
+}
+
+template <int MT, int EPI>
+int launch_t(fsv_ctx *c, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt, int M,
+             int Mpad, int splits, int nchunks, int KBo, hipStream_t st) {
+  constexpr int D = 3;
+  const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;
+  static bool attr_set = false;  // per instantiation
+  if (!attr_set) {
+    FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, D>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsb));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL((k_gemm<MT, EPI, D>), grid, dim3(320), ldsb, st, Wp, wbytes, (const uint4 *)Ap, out, N, KB, Mt, M, Mpad,
+                     splits, nchunks, KBo);
+  return FSV_OK;
+}
+
+template <int EPI>
+int launch_e(fsv_ctx *c, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits, int KBo,
+             hipStream_t st) {
+  const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = K / 256, KB = K / 16;
+  const int mt_blk = Mt >= 4 ? 4 : Mt, mblocks = fsv_ceil_div(Mt, mt_blk);
+  const size_t wbytes = (size_t)NTpad * KB * 1024;
+  if (wbytes > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
+  if (splits < 1 || splits > nchunks) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad split count %d for %d granules", splits, nchunks);
+  dim3 grid(NTpad / 4 * splits, 1, mblocks);
+#define FSV_ARGS c, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, st
+  switch (mt_blk) {
+    case 1: return launch_t<1, EPI>(FSV_ARGS);
+    case 2: return launch_t<2, EPI>(FSV_ARGS);
+    case 3: return launch_t<3, EPI>(FSV_ARGS);
+    default: return launch_t<4, EPI>(FSV_ARGS);
+  }
+#undef FSV_ARGS
+}
+
+}  // namespace
+
+int fsv_bf16_gemm(fsv_ctx *c, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits,
+                  int KBo, hipStream_t st) {
+  int rc;
+  switch (epi) {
+    case EPI_PARTIAL: rc = launch_e<EPI_PARTIAL>(c, Wp, Ap, out, N, K, NTpad, M, splits, KBo, st); break;
+    case EPI_SWIGLU: rc = launch_e<EPI_SWIGLU>(c, Wp, Ap, out, N, K, NTpad, M, splits, KBo, st); break;
+    default: rc = launch_e<EPI_F32>(c, Wp, Ap, out, N, K, NTpad, M, splits, KBo, st); break;
+  }
+  if (rc) return rc;
+  FSV_HIP(c, hipGetLastError());
+  return FSV_OK;
+}

@@ -615,6 +615,11 @@ int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, 
   const int wk = (nchunks / splits >= 2) ? gemm_groups() : 1, var = gemm_variant();
   fsv_prof_scope ps(c, st, cls, (double)s.N * s.K * 2);
   int rc;
+  {
+    static int use2 = -1;
+    if (use2 < 0) { const char *e = getenv("FSV_GEMM2"); use2 = e ? atoi(e) : 1; }
+    if (use2) return fsv_bf16_gemm(c, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, KBo, st);
+  }
 #define FSV_GEMM_ARGS c, grid, Wp, Ap, out, s, Mt, M, Mpad, splits, nchunks, KBo, st
 #define FSV_GEMM_CASE(MTV)                                                                   \
   if (var == 1) rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 16, 2>(FSV_GEMM_ARGS)            \
