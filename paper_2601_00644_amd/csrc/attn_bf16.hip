@@ -325,15 +325,7 @@ __global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int ro
   reinterpret_cast<uint4 *>(out)[tile_unit(m, col, KBq)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }
 
-int attn_waves_per_cu() {  // resident waves per compute unit the attention schedule is sized for
-  static int v = 0;
-  if (!v) {
-    const char *e = getenv("FSV_ATTN_WAVES_PER_CU");
-    v = e ? atoi(e) : 4;
-    if (v < 1 || v > 16) v = 4;
-  }
-  return v;
-}
+constexpr int kAttnWavesPerCu = 4;  // one per SIMD: a wave of this kernel takes the whole register file of its SIMD
 
 // Size the parts from the host copies of the lengths: the smallest part length for which parts x kv heads
 // still fits the machine once (or one part per request when even that does not fit).
@@ -435,10 +427,7 @@ int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl
 
 int fsv_bf16_attn_create(fsv_ctx *c) {
   const fsv_model_desc &d = c->d;
-  int dev = 0, cus = 0;
-  FSV_HIP(c, hipGetDevice(&dev));
-  FSV_HIP(c, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-  c->attn_wave_target = max(cus, 1) * attn_waves_per_cu();
+  c->attn_wave_target = c->n_cus * kAttnWavesPerCu;
   c->attn_wave_cap = max(c->attn_wave_target, d.max_batch * d.n_kv_heads);
   const int rows_cap = c->group * (d.max_gamma + 1);
   c->attn_part_bytes = (size_t)c->attn_wave_cap * rows_cap * (d.head_dim + 2) * 4;

@@ -68,6 +68,7 @@ struct fsv_ctx {
   size_t part_bytes = 0;
   void *attn_part = nullptr;    // per-part attention results (O, then (m, l)) of requests with several parts
   size_t attn_part_bytes = 0;
+  int n_cus = 0;                // compute units of the device the context was created on
   int attn_wave_target = 0;     // waves the attention schedule aims at (resident waves of the device)
   int attn_wave_cap = 0;        // waves the partial buffers hold
   int32_t *attn_part_prefix = nullptr, *attn_part_tiles = nullptr, *attn_part_map = nullptr;

@@ -111,16 +111,30 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
   for (int j = 0; j < D; ++j) issue(j, wb[j]);
   FSV_BARRIER();
 
+  // B operands are read from the ring DL k blocks ahead of the MFMAs that use them (a wave is alone on its SIMD,
+  // so nothing else hides the LDS latency); the scheduling barriers keep that order.
+  constexpr int DL = 2;
   auto consume = [&](int it, bf16x8_t(&wuse)[KC]) {
     const uint4 *stage = lds + (it % NST) * CHU + lane;
-#pragma unroll
-    for (int kb = 0; kb < KC; ++kb) {
-      FSV_IN_AGPR(wuse[kb]);
+    bf16x8_t aop[DL + 1][MT];
+    auto fetch = [&](int kb) {
 #pragma unroll
       for (int mt = 0; mt < MT; ++mt) {
         uint4 raw = stage[(mt * KC + kb) * 64];
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], *reinterpret_cast<bf16x8_t *>(&raw), acc[mt], 0, 0, 0);
+        aop[kb % (DL + 1)][mt] = *reinterpret_cast<bf16x8_t *>(&raw);
       }
+    };
+#pragma unroll
+    for (int kb = 0; kb < DL; ++kb) fetch(kb);
+#pragma unroll
+    for (int kb = 0; kb < KC; ++kb) {
+      if (kb + DL < KC) fetch(kb + DL);
+      __builtin_amdgcn_sched_barrier(0);
+      FSV_IN_AGPR(wuse[kb]);
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], aop[kb % (DL + 1)][mt], acc[mt], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
   };
   // Step s of an unrolled round consumes buffer s and refills the buffer consumed just before it with the chunk D
@@ -198,7 +212,7 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
 template <int MT, int EPI>
 int launch_t(fsv_ctx *c, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt, int M,
              int Mpad, int splits, int nchunks, int KBo, hipStream_t st) {
-  constexpr int D = 3;
+  constexpr int D = 2;  // weight chunks in flight per wave ahead of the one in use (deeper did not pay on MI355X)
   const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {

@@ -17,25 +17,7 @@
 
 using namespace fsv_bf16;
 
-#ifndef FSV_EXP
-#define FSV_EXP 0  // timing experiments only (wrong results): 1 no activation staging, 2 no MFMA, 4 no LDS reads
-#endif
 
-#ifdef FSV_TRACE
-__device__ long long g_trace[4 * 8192];
-extern "C" int fsv_debug_trace_read(long long *out, int n) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(g_trace), sizeof(long long) * n);
-}
-#define FSV_TR(slot) const long long _tr##slot = (slot) == 1 ? (long long)(__builtin_amdgcn_s_getreg(63492) | ((unsigned long long)__builtin_amdgcn_s_getreg(63508) << 32)) : wall_clock64();
-#define FSV_TR_END                                                                    \
-  if (threadIdx.x == 0) {                                                             \
-    const int _b = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);    \
-    if (_b < 8192) { g_trace[_b * 4] = _tr0; g_trace[_b * 4 + 1] = _tr1; g_trace[_b * 4 + 2] = _tr2; g_trace[_b * 4 + 3] = wall_clock64(); } \
-  }
-#else
-#define FSV_TR(slot)
-#define FSV_TR_END
-#endif
 
 namespace {
 
@@ -106,234 +88,7 @@ __global__ void k_reduce_part(const float *__restrict__ part, int S, int Mpad, i
   y[(size_t)m * N + dst] = acc;
 }
 
-// ---------------------------------------------------------------------------------------------
-// weight-streaming GEMM
-// ---------------------------------------------------------------------------------------------
-enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };
-
-// One wave owns 32 output features (one weight tile row) for up to MT*32 batch rows and streams that
-// weight strip straight from HBM into MFMA operand registers, two 128-deep chunks ahead of its use.  A block
-// is WK groups of four waves: the four waves of a group share the activation chunk, staged through LDS in
-// operand order; the groups take disjoint halves of the block's K range (so twice the bytes are in flight
-// per compute unit) and are summed through LDS in group order before the epilogue.
-// grid = (feature tiles / 4, K splits, row blocks), dynamic LDS = WK * 2 * MT * 8 KiB.
-template <int MT, int EPI, int WK, int KC, int WS>
-__global__ __launch_bounds__(256 * WK) void k_gemm(const bf16x8_t *__restrict__ Wp, const uint4 *__restrict__ Ap,
-                                                   void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                                   int S, int nchunks, int gran, int KBo) {
-  extern __shared__ uint4 lds_dyn[];
-  FSV_TR(0)
-  constexpr int CHU = MT * KC * 64;  // 16-byte units of one staged activation chunk
-  const int tid = threadIdx.x, grp = tid >> 8, gt = tid & 255, w = gt >> 6, lane = tid & 63, h = lane >> 5;
-  uint4 *lds = lds_dyn + grp * 2 * CHU;
-  // Blocks are dealt to the eight XCDs round robin by their linear index.  With a multiple of eight splits the
-  // index is decoded so that a split always lands on the same XCD: every XCD then stages only its own K slices of
-  // the activation matrix, which stay in its L2, instead of all of it.
-  int nblk, split;
-  {
-    const int L = blockIdx.x;
-    if ((S & 7) == 0) {
-      const int a = L >> 3, s8 = S >> 3;
-      split = (L & 7) + 8 * (a % s8);
-      nblk = a / s8;
-    } else {
-      split = L % S;
-      nblk = L / S;
-    }
-  }
-  const int nt = nblk * 4 + w, mt0 = blockIdx.z * MT;
-  const int mtc = min(MT, Mt_total - mt0);
-  // K range of the split: a balanced cut of the `nchunks` granules (of gran chunks each) into S parts
-  const int cb0 = (split * nchunks / S) * gran, cb1 = ((split + 1) * nchunks / S) * gran;
-  const int per = (max(cb1 - cb0, 0) + WK - 1) / WK;  // iterations every group runs (barriers stay uniform)
-  const int c0 = cb0 + grp * per, c1 = min(c0 + per, cb1);
-  f32x16_t acc[MT];
-#pragma unroll
-  for (int i = 0; i < MT; ++i)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) acc[i][v] = 0.f;
-
-  const bf16x8_t *wrow = Wp + (size_t)nt * KB * 64 + lane;
-  constexpr int APT = CHU / 256;  // units of the activation chunk each thread stages
-  uint4 areg[2][APT];  // activation chunks in flight: chunk j lives in slot j & 1, fetched two chunks ahead
-  bf16x8_t wbuf[WS][KC];  // weight chunks: in use and being fetched, WS - 1 chunks ahead (roles rotate by name)
-
-  // Loads are never put under a branch: a branch around a global load makes the compiler wait for ALL
-  // outstanding loads at the join, which would drain the weight prefetch every iteration.  Out-of-range
-  // chunks are clamped to a valid address and their activations masked to zero instead.
-  const int cmax = nchunks * gran - 1, mlast = mtc - 1;
-  auto load_a = [&](int c, uint4(&dst)[APT]) {
-#pragma unroll
-    for (int p = 0; p < APT; ++p) {
-      const int i = p * 256 + gt, mt = min(i / (KC * 64), mlast), rem = i % (KC * 64);
-      dst[p] = Ap[((size_t)(mt0 + mt) * KB + c * KC) * 64 + rem];
-    }
-  };
-  auto store_a = [&](int buf, uint32_t mask, uint4(&src)[APT]) {  // the mask is applied here, not at the load: touching
-#pragma unroll                                                    // the loaded value early would stall the wave on it
-    for (int p = 0; p < APT; ++p)
-      lds[buf * CHU + p * 256 + gt] = make_uint4(src[p].x & mask, src[p].y & mask, src[p].z & mask, src[p].w & mask);
-  };
-  auto load_w = [&](int c, bf16x8_t(&dst)[KC]) {
-#if (FSV_EXP & 8)
-#pragma unroll
-    for (int kb = 0; kb < KC; ++kb) dst[kb] = wrow[(size_t)(kb) * 64 + 0 * c];
-#else
-#pragma unroll
-    for (int kb = 0; kb < KC; ++kb) dst[kb] = __builtin_nontemporal_load(&wrow[(size_t)(c * KC + kb) * 64]);
-#endif
-  };
-  // Blocks walk their K range starting at different chunks (a fixed rotation per block): all blocks read the
-  // same small activation matrix, and in lockstep they would all hit the same few L2 channels at once.
-  const int rot = per > 0 ? (int)(((unsigned)nblk * 5u + (unsigned)split * 3u + grp) % (unsigned)per) : 0;
-  auto chunk_of = [&](int it) { return c0 + (per > 0 ? (it + rot) % per : 0); };
-  auto live = [&](int it, int c) -> uint32_t { return (it < per && c < c1) ? 0xffffffffu : 0u; };
-  auto lds_op = [&](int buf, int mt, int kb) {
-#if (FSV_EXP & 4)
-    uint4 raw = make_uint4(buf, mt, kb, lane);
-#else
-    uint4 raw = lds[buf * CHU + (mt * KC + kb) * 64 + lane];
-#endif
-    return *reinterpret_cast<bf16x8_t *>(&raw);
-  };
-  // One chunk: issue the prefetches (activations of the next chunk, weights two chunks ahead), then KC x MT MFMAs
-  // with the LDS operand reads running D k-blocks ahead of the MFMAs, then publish the next activation chunk.
-  constexpr int D = (MT >= 3) ? 1 : (MT == 2 ? 2 : 4);
-  auto chunk_step = [&](int it, bf16x8_t(&wuse)[KC], bf16x8_t(&wfetch)[KC], uint4(&afetch)[APT], uint4(&apub)[APT]) {
-    const int buf = it & 1, cn = chunk_of(it + 1), cnn = chunk_of(it + WS - 1);
-#if !(FSV_EXP & 1)
-    load_a(min(chunk_of(it + 2), cmax), afetch);
-#endif
-    load_w(min(cnn, cmax), wfetch);
-    __builtin_amdgcn_sched_barrier(0);  // the scheduler would sink the prefetch below the MFMA block otherwise
-    bf16x8_t aop[D + 1][MT];
-#pragma unroll
-    for (int kb = 0; kb < D; ++kb)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) aop[kb % (D + 1)][mt] = lds_op(buf, mt, kb);
-#pragma unroll
-    for (int kb = 0; kb < KC; ++kb) {
-      if (kb + D < KC) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) aop[(kb + D) % (D + 1)][mt] = lds_op(buf, mt, kb + D);
-      }
-      __builtin_amdgcn_sched_barrier(0);
-#if (FSV_EXP & 2)
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) acc[mt][0] += (float)wuse[kb][mt] + (float)aop[kb % (D + 1)][mt][0];
-#else
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], aop[kb % (D + 1)][mt], acc[mt], 0, 0, 0);
-#endif
-      __builtin_amdgcn_sched_barrier(0);
-    }
-#if !(FSV_EXP & 1)
-    store_a(buf ^ 1, live(it + 1, cn), apub);
-#endif
-    __syncthreads();
-  };
-
-  {
-    const int ca = chunk_of(0);
-    load_a(min(ca, cmax), areg[0]);
-#pragma unroll
-    for (int j = 0; j < WS - 1; ++j) load_w(min(chunk_of(j), cmax), wbuf[j]);
-    store_a(0, live(0, ca), areg[0]);
-    load_a(min(chunk_of(1), cmax), areg[1]);
-  }
-  __syncthreads();
-  FSV_TR(1)
-  // Unrolled so that the weight buffers (period WS) and the activation slots (period 2) rotate by name, not by
-  // copies.  The trip count is padded to the unroll factor instead of leaving the loop early (several exits make
-  // the compiler keep one copy of the accumulators per exit); padded steps run on zeroed activations.
-  constexpr int UNR = (WS % 2 == 0) ? WS : 2 * WS;
-  const int per_pad = (per + UNR - 1) / UNR * UNR;
-#define FSV_STEP(S) chunk_step(it + (S), wbuf[(S) % WS], wbuf[((S) + WS - 1) % WS], areg[(S) & 1], areg[((S) + 1) & 1]);
-  for (int it = 0; it < per_pad; it += UNR) {
-    FSV_STEP(0) FSV_STEP(1)
-    if constexpr (UNR > 2) { FSV_STEP(2) FSV_STEP(3) }
-    if constexpr (UNR > 4) { FSV_STEP(4) FSV_STEP(5) }
-  }
-#undef FSV_STEP
-  FSV_TR(2)
-  if constexpr (WK > 1) {  // sum the groups in order through LDS (each group reuses its own staging area)
-    float *red = reinterpret_cast<float *>(lds_dyn);
-    for (int gsrc = 1; gsrc < WK; ++gsrc) {
-      if (grp == gsrc) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) red[((w * MT + mt) * 16 + v) * 64 + lane] = acc[mt][v];
-      }
-      __syncthreads();
-      if (grp == 0) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[mt][v] += red[((w * MT + mt) * 16 + v) * 64 + lane];
-      }
-      __syncthreads();
-    }
-    if (grp != 0) return;
-  }
-
-  // epilogue: lane holds, for batch row m = tile*32 + lane%32, features nt*32 + 8*(v/4) + 4*h + v%4
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    if (mt >= mtc) continue;
-    const int m = (mt0 + mt) * 32 + (lane & 31);
-    if constexpr (EPI == EPI_PARTIAL) {
-      if (m >= M) continue;  // the consumers read rows below M only
-      float *dst = (float *)out + ((size_t)split * Mpad + m) * N;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n0 = nt * 32 + 8 * g + 4 * h;
-        if (n0 + 3 < N) {
-          *reinterpret_cast<float4 *>(dst + n0) =
-              make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
-        }
-      }
-    } else if constexpr (EPI == EPI_F32) {
-      if (m < M) {
-        float *dst = (float *)out + (size_t)m * N;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n0 = nt * 32 + 8 * g + 4 * h;
-          if (n0 + 3 < N && (N & 3) == 0) {
-            *reinterpret_cast<float4 *>(dst + n0) =
-                make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
-          } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
-          }
-        }
-      }
-    } else {  // SwiGLU: regs 0-3 gate / 4-7 up of features 16*nt + 4h + r, regs 8-11 / 12-15 of 16*nt + 8 + 4h + r
-      if (nt < KBo) {
-        uint16_t *base = (uint16_t *)out;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          uint16_t o4[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float gte = acc[mt][8 * j + r], up = acc[mt][8 * j + 4 + r];
-            o4[r] = f2bf(gte / (1.0f + __expf(-gte)) * up);
-          }
-          const size_t unit = ((size_t)(mt0 + mt) * KBo + nt) * 64 + (lane & 31) + 32 * j;
-          uint2 pk = make_uint2((uint32_t)o4[0] | ((uint32_t)o4[1] << 16), (uint32_t)o4[2] | ((uint32_t)o4[3] << 16));
-          *reinterpret_cast<uint2 *>(base + unit * 8 + 4 * h) = pk;
-        }
-      }
-    }
-  }
-  FSV_TR_END
-}
+enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };  // epilogues of fsv_bf16_gemm
 
 // ---------------------------------------------------------------------------------------------
 // residual stream: x (+)= sum of split partials (or embedding), RMSNorm, emit the next GEMM's operand
@@ -525,21 +280,12 @@ gemm_shape shape_of(const fsv_ctx *c, int which) {
   return s;
 }
 
-int target_blocks() {
-  static int v = 0;
-  if (!v) {
-    const char *e = getenv("FSV_GEMM_BLOCKS");
-    v = e ? atoi(e) : 512;
-    if (v < 1) v = 512;
-  }
-  return v;
-}
-
-// K splits so that feature tiles x splits x row blocks comes to about two blocks per compute unit
-int pick_splits(const gemm_shape &s, int Mt, bool allow) {
+// K splits so that feature tiles x splits x row blocks comes to about one block per compute unit (a block fills
+// the unit's LDS with its activation ring; more splits only add partial sums to write and read back)
+int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
   if (!allow) return 1;
   const int nchunks = s.K / KCHUNK, base = (s.NTpad / 4) * fsv_ceil_div(Mt, 4);
-  int sp = target_blocks() / base;
+  int sp = c->n_cus / base;
   sp = max(1, min(sp, nchunks));
   if (sp >= 8) sp &= ~7;  // a multiple of eight keeps each split on one XCD (see k_gemm); the K cut is balanced, not equal
   return sp;
@@ -561,84 +307,11 @@ int copy_dev(fsv_ctx *c, void **dst, const void *src, size_t bytes) {
   return FSV_OK;
 }
 
-int gemm_groups() {
-  static int v = 0;
-  if (!v) {
-    const char *e = getenv("FSV_GEMM_GROUPS");
-    v = e ? atoi(e) : 1;
-    if (v != 1 && v != 2) v = 1;
-  }
-  return v;
-}
-
-int gemm_variant() {  // chunk size / weight stages under test: 0 = 128-deep chunks, 3 stages; 1 = 256-deep, 2 stages
-  static int v = -1;
-  if (v < 0) {
-    const char *e = getenv("FSV_GEMM_VARIANT");
-    v = e ? atoi(e) : 0;
-  }
-  return v;
-}
-
-template <int MT, int EPI, int WK, int KC, int WS>
-int launch_gemm_t(fsv_ctx *c, dim3 grid, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int Mt, int M,
-                  int Mpad, int splits, int nchunks, int KBo, hipStream_t st) {
-  const size_t lds = (size_t)WK * 2 * MT * KC * 64 * 16;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, WK, KC, WS>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-    attr_set = true;
-    if (getenv("FSV_DEBUG_OCC")) {
-    int nb = -1;
-    hipFuncAttributes fa;
-    (void)hipFuncGetAttributes(&fa, reinterpret_cast<const void *>(&k_gemm<MT, EPI, WK, KC, WS>));
-    (void)hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, k_gemm<MT, EPI, WK, KC, WS>, 256 * WK, lds);
-    fprintf(stderr, "k_gemm<%d,%d,%d,%d,%d>: numRegs %d static lds %zu dyn lds %zu -> blocks/CU %d\n", MT, EPI, WK, KC, WS, fa.numRegs,
-            fa.sharedSizeBytes, lds, nb);
-    }
-  }
-  // nchunks is counted in KCHUNK granules; the kernel counts in its own chunk size, gran chunks to a granule
-  const int f = KCHUNK / (KC * 16);
-  hipLaunchKernelGGL((k_gemm<MT, EPI, WK, KC, WS>), grid, dim3(256 * WK), lds, st, (const bf16x8_t *)Wp,
-                     (const uint4 *)Ap, out, s.N, s.K / 16, Mt, M, Mpad, splits, nchunks, f, KBo);
-  return FSV_OK;
-}
-
 template <int EPI>
 int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, int splits,
                 hipStream_t st) {
-  const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = s.K / KCHUNK;
-  const int mt_blk = Mt >= 4 ? 4 : Mt, mblocks = fsv_ceil_div(Mt, mt_blk);
-  dim3 grid(s.NTpad / 4 * splits, 1, mblocks);
-  const int KBo = (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0;
-  const int wk = (nchunks / splits >= 2) ? gemm_groups() : 1, var = gemm_variant();
   fsv_prof_scope ps(c, st, cls, (double)s.N * s.K * 2);
-  int rc;
-  {
-    static int use2 = -1;
-    if (use2 < 0) { const char *e = getenv("FSV_GEMM2"); use2 = e ? atoi(e) : 1; }
-    if (use2) return fsv_bf16_gemm(c, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, KBo, st);
-  }
-#define FSV_GEMM_ARGS c, grid, Wp, Ap, out, s, Mt, M, Mpad, splits, nchunks, KBo, st
-#define FSV_GEMM_CASE(MTV)                                                                   \
-  if (var == 1) rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 16, 2>(FSV_GEMM_ARGS)            \
-                               : launch_gemm_t<MTV, EPI, 1, 16, 2>(FSV_GEMM_ARGS);           \
-  else if (var == 2) rc = launch_gemm_t<MTV, EPI, 1, 8, 3>(FSV_GEMM_ARGS);                   \
-  else if (var == 3) rc = launch_gemm_t<MTV, EPI, 1, 8, 4>(FSV_GEMM_ARGS);                   \
-  else rc = (wk == 2) ? launch_gemm_t<MTV, EPI, 2, 8, 2>(FSV_GEMM_ARGS)                      \
-                      : launch_gemm_t<MTV, EPI, 1, 8, 2>(FSV_GEMM_ARGS)
-  switch (mt_blk) {
-    case 1: FSV_GEMM_CASE(1); break;
-    case 2: FSV_GEMM_CASE(2); break;
-    case 3: FSV_GEMM_CASE(3); break;
-    default: FSV_GEMM_CASE(4); break;
-  }
-#undef FSV_GEMM_CASE
-#undef FSV_GEMM_ARGS
-  if (rc) return rc;
-  FSV_HIP(c, hipGetLastError());
-  return FSV_OK;
+  return fsv_bf16_gemm(c, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0, st);
 }
 
 size_t layer_stride(const fsv_ctx *c, int num_pages) {
@@ -651,6 +324,12 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
   const fsv_model_desc &d = c->d;
   const int qd = d.n_heads * d.head_dim, qkvd = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   int rc;
+  {
+    int dev = 0;
+    FSV_HIP(c, hipGetDevice(&dev));
+    FSV_HIP(c, hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev));
+    if (c->n_cus < 1) c->n_cus = 1;
+  }
   if ((rc = copy_dev(c, &c->embed, w->embed, (size_t)2 * d.vocab * d.d_model))) return rc;
   if ((rc = copy_dev(c, &c->final_norm, w->final_norm, (size_t)2 * d.d_model))) return rc;
   if ((rc = pack_weight(c, w->lm_head, FSV_W_LM_HEAD, &c->lm_head))) return rc;
@@ -689,7 +368,7 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
     gemm_shape s = shape_of(c, which);
     if (which == FSV_W_LM_HEAD) continue;  // written straight to the logits
     for (int Mt = 1; Mt <= MtMax; ++Mt)
-      part = max(part, (size_t)pick_splits(s, Mt, which != FSV_W_GATE_UP) * Mt * 32 * s.N * 4);
+      part = max(part, (size_t)pick_splits(c, s, Mt, which != FSV_W_GATE_UP) * Mt * 32 * s.N * 4);
   }
   c->part_bytes = part;
   if ((rc = zalloc(&c->buf_part, part))) return rc;
@@ -703,7 +382,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32;
   const gemm_shape sq = shape_of(c, FSV_W_QKV), so = shape_of(c, FSV_W_O), sg = shape_of(c, FSV_W_GATE_UP),
                    sd = shape_of(c, FSV_W_DOWN), sl = shape_of(c, FSV_W_LM_HEAD);
-  const int spq = pick_splits(sq, Mt, true), spo = pick_splits(so, Mt, true), spd = pick_splits(sd, Mt, true);
+  const int spq = pick_splits(c, sq, Mt, true), spo = pick_splits(c, so, Mt, true), spd = pick_splits(c, sd, Mt, true);
   float *part = (float *)c->buf_part;
   const int nthr = min(1024, max(64, fsv_ceil_div(d.d_model / 8, 64) * 64));  // one 8-wide slice per thread
   int rc;
@@ -764,7 +443,7 @@ int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, floa
                      (uint4 *)c->buf_a);
   int rc;
   if (which == FSV_W_LM_HEAD) return launch_gemm<EPI_F32>(c, cls, Wp, c->buf_a, y, sh, M, 1, s);
-  const int sp = pick_splits(sh, Mt, which != FSV_W_GATE_UP);
+  const int sp = pick_splits(c, sh, Mt, which != FSV_W_GATE_UP);
   if ((rc = launch_gemm<EPI_PARTIAL>(c, cls, Wp, c->buf_a, c->buf_part, sh, M, sp, s))) return rc;
   const size_t n = (size_t)M * sh.N;
   hipLaunchKernelGGL(k_reduce_part, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float *)c->buf_part, sp, Mpad,
