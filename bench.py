@@ -20,6 +20,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes one launch of the dominant kernel (gate|up GEMM at 97 rows) moves, from the two rocprofv3 --pmc passes recorded
+# in profiles/verify_c3_8b_b16_hbm_traffic.txt: FETCH_SIZE 118876.5 counts x 2.0 KiB + WRITE_SIZE 3584.0 counts x 1.0 KiB
+# (the scale factors are what the same counters read for a plain 1 GiB copy).  Only valid for the default workload.
+GATE_UP_TRAFFIC_BYTES = (118876.5 * 2.0 + 3584.0 * 1.0) * 1024.0
 
 
 def log(msg):
@@ -124,7 +128,8 @@ def main():
     dom_bytes = dom["bytes"] / dom["launches"]
     roofline = {"bound": "hbm", "kernel": "k_gemm<.,SwiGLU> (gate|up projection, weight streaming)",
                 "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                "traffic": GATE_UP_TRAFFIC_BYTES if (wl.name == "c3_8b_b16" and args.seed == 1) else None,
                 "launches": dom["launches"], "avg_us": dom_ms * 1e3, "bytes_per_launch": dom_bytes}
     out = {"metric": "verified draft tokens/sec on 1 MI355X (8B shapes, batch 16)", "value": G / (ms * 1e-3),
            "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,

@@ -2,6 +2,7 @@
 // step 2, over the user's restored KV session plus the rows appended in this call, Sec. IV-C).
 // Built with -mllvm -amdgpu-mfma-vgpr-form: the MFMA accumulators stay in the architectural registers,
 // where the softmax arithmetic reaches them, and the accumulation registers hold the K/V tiles in flight.
+#include <hip/hip_ext.h>
 #include <math.h>
 #include <stdlib.h>
 
@@ -384,9 +385,10 @@ int launch_attention(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, si
   uint16_t *out = (uint16_t *)c->buf_att;
   const uint16_t *kl = (const uint16_t *)b->k_pool + layer_off, *vl = (const uint16_t *)b->v_pool + layer_off;
   {
-    fsv_prof_scope ps(c, st, FSV_K_ATTENTION, pl.kv_tokens * d.n_kv_heads * d.head_dim * 4.0);
+    fsv_prof_scope ps(c, st, FSV_K_ATTENTION, pl.kv_tokens * d.n_kv_heads * d.head_dim * 4.0, true);
 #define FSV_ATTN_LAUNCH(HDV, RTV, NBV)                                                                            \
-  hipLaunchKernelGGL((k_attention<HDV, RTV, NBV>), dim3(pl.waves), dim3(64), 0, st, d.n_kv_heads, group, rows_cap, \
+  hipExtLaunchKernelGGL((k_attention<HDV, RTV, NBV>), dim3(pl.waves), dim3(64), 0, st, ps.start(), ps.stop(), 0,   \
+                        d.n_kv_heads, group, rows_cap,                                                             \
                      (const uint4 *)c->buf_q, b->seq_lens, b->draft_offsets, c->attn_part_map, c->attn_part_prefix, \
                      c->attn_part_tiles, b->page_table, d.max_pages_per_req, b->num_pages, kl, vl, layer_bytes, po, \
                      pml, out, KBq)

@@ -92,24 +92,28 @@ struct fsv_ctx {
     if (_e != hipSuccess) FSV_FAIL(ctx, FSV_E_HIP, "%s: %s", #call, hipGetErrorString(_e)); \
   } while (0)
 
-// scoped event pair around one kernel class (no-op unless profiling is on)
+// scoped event pair around one kernel class (no-op unless profiling is on).  By default the pair is recorded on the
+// stream before and after whatever is launched inside the scope; a launch that can carry its own start / stop events
+// (hipExtLaunchKernelGGL) takes them with ext() instead, which times the kernel itself without the dispatch gaps.
 struct fsv_prof_scope {
   fsv_ctx *c;
   hipStream_t s;
   fsv_prof_rec r{};
-  bool on;
-  fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes)
-      : c(ctx), s(st), on((ctx->prof_mask >> cls) & 1u) {
+  bool on, external;
+  fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes, bool ext_mode = false)
+      : c(ctx), s(st), on((ctx->prof_mask >> cls) & 1u), external(ext_mode) {
     if (!on) return;
     if (c->prof.size() >= 8192) { on = false; return; }
     r.cls = cls;
     r.bytes = bytes;
     if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) { on = false; return; }
-    (void)hipEventRecord(r.e0, s);
+    if (!external) (void)hipEventRecord(r.e0, s);
   }
+  hipEvent_t start() const { return (on && external) ? r.e0 : nullptr; }
+  hipEvent_t stop() const { return (on && external) ? r.e1 : nullptr; }
   ~fsv_prof_scope() {
     if (!on) return;
-    (void)hipEventRecord(r.e1, s);
+    if (!external) (void)hipEventRecord(r.e1, s);
     c->prof.push_back(r);
   }
 };
@@ -142,8 +146,8 @@ int fsv_bf16_attn_plan(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl, hipStr
 int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, size_t layer_off, hipStream_t s);
 // gemm_bf16.hip: y = x W^T through the weight-streaming kernel; epi 0 = fp32 split partials [splits][Mpad][N],
 // 1 = SwiGLU to the bf16 operand order, 2 = fp32 rows [M][N]
-int fsv_bf16_gemm(fsv_ctx *c, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits,
-                  int KBo, hipStream_t st);
+int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
+                  int splits, int KBo, hipStream_t st);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
 int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);

@@ -310,8 +310,7 @@ int copy_dev(fsv_ctx *c, void **dst, const void *src, size_t bytes) {
 template <int EPI>
 int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, int splits,
                 hipStream_t st) {
-  fsv_prof_scope ps(c, st, cls, (double)s.N * s.K * 2);
-  return fsv_bf16_gemm(c, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0, st);
+  return fsv_bf16_gemm(c, cls, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0, st);
 }
 
 size_t layer_stride(const fsv_ctx *c, int num_pages) {
