@@ -73,6 +73,52 @@ def cpu_baseline(cfg, wl, req, weights, seed, budget_rows=9):
             "sample": f"request {b} of the batch alone (context {L}, gamma {g}, {g + 1} rows): {dt:.2f} s"}
 
 
+def sampler_bench(args, torch, fv, synth):
+    """The accept / resample step alone (fsv_sample) at the sampling configuration: batch 64, ragged gamma 1..16,
+    vocabulary 152064, bf16 logits ~ N(0,3), draft laws from logits noised with sigma 0.7, temperature 0.7."""
+    V, B, sigma, T = 152064, 64, 0.7, 0.7
+    log("workload c4_sampler: generating logits and draft laws on the device")
+    case = synth.make_sampler_case(B, 1, 16, V, sigma, T, args.seed, logits_dtype="bf16", device="cuda")
+    G, M = int(case.draft_offsets[-1]), int(case.draft_offsets[-1]) + B
+    cfg = synth.ModelCfg("sampler", 0, 0, 0, 0, 0, 0, V, "bf16")
+    ctx = fv.Context(cfg, None, B, 16, sampler_only=True)
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device="cuda")
+    batch = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs, t(case.u_accept),
+                           t(case.u_sample), t(case.temperature), None, None, None, 0, None,
+                           np.ascontiguousarray(case.draft_offsets), np.ascontiguousarray(case.temperature))
+    res = fv.DeviceResult.alloc(B)
+    for _ in range(args.warmup):
+        ctx.sample(case.logits, batch, res)
+    torch.cuda.synchronize()
+    ctx.profile_read()
+    ctx.profile_enable(["sample_stats", "sample_accept", "sample_select"])
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(args.steps):
+        ctx.sample(case.logits, batch, res)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / args.steps
+    prof = ctx.profile_read()
+    ctx.profile_enable(False)
+    dom = prof["sample_stats"]
+    dom_ms, dom_bytes = dom["total_ms"] / dom["launches"], dom["bytes"] / dom["launches"]
+    tau = res.accepted_len.cpu().numpy()
+    out = {"metric": "verified draft tokens/sec on 1 MI355X (rejection sampling alone, vocabulary 152064, batch 64)",
+           "value": G / (ms * 1e-3), "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+           "data": "synthetic",
+           "config": {"workload": "c4_sampler", "batch": B, "drafts": G, "rows": M, "vocab": V, "temperature": T,
+                      "draft_noise_sigma": sigma, "accepted_drafts": int(tau.sum())},
+           "roofline": {"bound": "hbm", "kernel": "k_row_stats (one pass over every logits row)",
+                        "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                        "launches": dom["launches"], "avg_us": dom_ms * 1e3, "bytes_per_launch": dom_bytes},
+           "kernels": {k: {"launches": v["launches"], "avg_us": round(v["total_ms"] / v["launches"] * 1e3, 2),
+                           "GBps": round(v["bytes"] / max(v["total_ms"], 1e-9) / 1e6, 1)} for k, v in prof.items()}}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -95,6 +141,8 @@ def main():
     from paper_2601_00644_amd import synth, workload
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    if args.workload == "c4_sampler":
+        return sampler_bench(args, torch, fv, synth)
     wl = synth.WORKLOADS[args.workload]
     cfg = synth.MODELS[wl.model]
     log(f"workload {wl.name}: model {cfg.name}, generating weights on the device")
