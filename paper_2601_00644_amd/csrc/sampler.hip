@@ -3,11 +3,11 @@
 // temperature > 0 the speculative-sampling rule that keeps the output law equal to the target's,
 // Sec. II and Regime B of Sec. V) and the rollback of Sec. IV-C.
 //
-// Three launches, all bound by streaming logits from HBM:
-//   k_row_stats   grid (chunks, rows)      one pass over every logits row: per chunk (max, sum e^{(l-max)/T}, argmax)
-//   k_accept_mass grid (slices, requests)  acceptance tests from gathered scalars, then one pass over the
-//                                          single row the emitted token is drawn from (and its draft-law row)
-//                                          producing the mass of every 2048-id sub-block
+// Four launches; the two that stream logits from HBM (k_row_stats, k_mass) carry the time:
+//   k_row_stats   grid (chunks / 4, rows)  one pass over every logits row: per chunk (max, sum e^{(l-max)/T}, argmax)
+//   k_accept      grid (requests)          row statistics combined, acceptance tests from gathered scalars
+//   k_mass        grid (slices, requests)  one pass over the single row the emitted token is drawn from (and its
+//                                          draft-law row) producing the mass of every 2048-id sub-block
 //   k_select      grid (requests)          locate the sub-block and the id by inverse CDF, emit flags, roll back
 // Every floating-point sum is taken in a fixed order (no atomics), so results are reproducible.
 #include <limits.h>
@@ -19,13 +19,22 @@ namespace {
 
 constexpr double kLog2e = 1.4426950408889634074;
 
-// e^{d * k / log2e} for d <= 0 (k = log2(e) / T), product formed in fp64, 2^frac on the transcendental unit.
-__device__ inline float exp_scaled(float d, double k) {
-  double z = (double)d * k;
-  if (!(z > -1000.0)) return 0.f;  // also catches -inf and NaN (all -inf chunk)
-  double n = rint(z);
-  float f = (float)(z - n);
-  return ldexpf(__builtin_amdgcn_exp2f(f), (int)n);
+// e^{d / T} for d <= 0 as 2^{d * k}, k = log2(e) / T carried as a float pair (k_hi + k_lo) so that its rounding does not
+// tilt large against small terms; the product is formed in fp32 (the error it leaves is relative to a term's own size,
+// 1e-7 for the terms that carry the mass) and 2^z comes from the transcendental unit.  Vocabulary-wide sums are bound by
+// this arithmetic, not by HBM, if it is done in fp64.
+struct exp_scale {
+  float hi, lo;
+};
+__device__ inline exp_scale make_exp_scale(double k) {
+  exp_scale s;
+  s.hi = (float)k;
+  s.lo = (float)(k - (double)s.hi);
+  return s;
+}
+__device__ inline float exp_scaled(float d, exp_scale k) {
+  const float z = fmaf(d, k.lo, d * k.hi);
+  return (z > -150.f) ? __builtin_amdgcn_exp2f(z) : 0.f;  // also catches -inf and NaN (a chunk that is all -inf)
 }
 
 template <typename LT>
@@ -33,6 +42,17 @@ struct loader;
 
 template <>
 struct loader<uint16_t> {  // bf16 bit patterns
+  // eight ids from a 16-byte aligned, fully in-range address: no bounds logic, so that a run of these loads is
+  // issued back to back (a branch per load makes the wave wait for each load before the next)
+  static __device__ inline void load8_fast(const uint16_t *row, int i0, float (&v)[8]) {
+    uint4 raw = *reinterpret_cast<const uint4 *>(row + i0);
+    uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      v[2 * j] = __uint_as_float(w[j] << 16);
+      v[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    }
+  }
   static __device__ inline void load8(const uint16_t *row, int i0, int V, bool vec, float fill, float (&v)[8]) {
     if (vec && i0 + 8 <= V) {
       uint4 raw = *reinterpret_cast<const uint4 *>(row + i0);
@@ -51,6 +71,12 @@ struct loader<uint16_t> {  // bf16 bit patterns
 
 template <>
 struct loader<float> {
+  static __device__ inline void load8_fast(const float *row, int i0, float (&v)[8]) {
+    float4 a = *reinterpret_cast<const float4 *>(row + i0);
+    float4 b = *reinterpret_cast<const float4 *>(row + i0 + 4);
+    v[0] = a.x; v[1] = a.y; v[2] = a.z; v[3] = a.w;
+    v[4] = b.x; v[5] = b.y; v[6] = b.z; v[7] = b.w;
+  }
   static __device__ inline void load8(const float *row, int i0, int V, bool vec, float fill, float (&v)[8]) {
     if (vec && i0 + 8 <= V) {
       float4 a = *reinterpret_cast<const float4 *>(row + i0);
@@ -103,87 +129,88 @@ __global__ void k_build_rows(int B, int V, const int32_t *seq_lens, const int32_
   }
 }
 
+// One wave per 8192-id chunk of a row: all of the chunk's loads are issued before the first use (sixteen 16-byte loads
+// per lane for bf16), the maximum and the sum are reduced over the wave with shuffles, and no LDS or barrier is
+// involved; waves are independent, so a compute unit keeps a dozen of them streaming.  grid = (chunks / 4, rows).
 template <typename LT>
 __global__ __launch_bounds__(256) void k_row_stats(const LT *__restrict__ logits, int V, int nc,
                                                    const int32_t *__restrict__ row_req,
                                                    const float *__restrict__ temperature, float *__restrict__ pmax,
                                                    double *__restrict__ psum, int32_t *__restrict__ parg, int vec) {
-  const int c = blockIdx.x, r = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  constexpr int P = FSV_CHUNK / 512;  // passes of 64 lanes x 8 ids
+  const int tid = threadIdx.x, lane = tid & 63, c = blockIdx.x * 4 + (tid >> 6), r = blockIdx.y;
+  if (c >= nc) return;
   const LT *row = logits + (size_t)r * V;
   const float T = temperature[row_req[r]];
-  float v[FSV_SPC][8];
-  const int base = c * FSV_CHUNK + tid * 8;
+  float v[P][8];
+  const int base = c * FSV_CHUNK + lane * 8;
+  if (vec && (c + 1) * FSV_CHUNK <= V) {  // wave-uniform: every chunk but a ragged last one
 #pragma unroll
-  for (int s = 0; s < FSV_SPC; ++s) loader<LT>::load8(row, base + s * FSV_SBK, V, vec != 0, -INFINITY, v[s]);
+    for (int p = 0; p < P; ++p) loader<LT>::load8_fast(row, base + p * 512, v[p]);
+  } else {
+#pragma unroll
+    for (int p = 0; p < P; ++p) loader<LT>::load8(row, base + p * 512, V, vec != 0, -INFINITY, v[p]);
+  }
+  // A row needs either the argmax (greedy, T = 0) or the sum of exponentials (T > 0), never both; the vocabulary-wide
+  // pass is bound by its arithmetic as soon as it carries more than a handful of operations per id.
   float mx = -INFINITY;
   int ai = INT_MAX;
-#pragma unroll
-  for (int s = 0; s < FSV_SPC; ++s)
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      if (v[s][j] > mx) { mx = v[s][j]; ai = base + s * FSV_SBK + j; }
-  // block (max, lowest id attaining it)
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    float om = __shfl_xor(mx, off, 64);
-    int oi = __shfl_xor(ai, off, 64);
-    if (om > mx || (om == mx && oi < ai)) { mx = om; ai = oi; }
-  }
-  __shared__ float s_m[4];
-  __shared__ int s_i[4];
-  __shared__ double s_d[4];
-  if (lane == 0) { s_m[w] = mx; s_i[w] = ai; }
-  __syncthreads();
-  mx = s_m[0]; ai = s_i[0];
-#pragma unroll
-  for (int i = 1; i < 4; ++i)
-    if (s_m[i] > mx || (s_m[i] == mx && s_i[i] < ai)) { mx = s_m[i]; ai = s_i[i]; }
   double sum = 0.0;
   if (T > 0.f) {
-    const double k = kLog2e / (double)T;
 #pragma unroll
-    for (int s = 0; s < FSV_SPC; ++s)
+    for (int p = 0; p < P; ++p)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) sum += (double)exp_scaled(v[s][j] - mx, k);
+      for (int j = 0; j < 8; ++j) mx = fmaxf(mx, v[p][j]);
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
-    if (lane == 0) s_d[w] = sum;
-    __syncthreads();
-    sum = (s_d[0] + s_d[1]) + (s_d[2] + s_d[3]);
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    if (mx > -INFINITY) {  // wave-uniform; an all -inf chunk carries no mass
+      // 2^{(l - max) k} with k in fp32: its rounding moves a term by 6e-8 of its own exponent, nothing for the terms
+      // that carry the sum; ids beyond the vocabulary were loaded as -inf and come out as 0
+      const float k = (float)(kLog2e / (double)T);
+#pragma unroll
+      for (int p = 0; p < P; ++p) {  // eight terms at a time in fp32, the groups in fp64
+        float part = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) part += __builtin_amdgcn_exp2f((v[p][j] - mx) * k);
+        sum += (double)part;
+      }
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, 64);
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+        if (v[p][j] > mx) { mx = v[p][j]; ai = base + p * 512 + j; }   // ids ascend with (p, j): the first maximum stays
+    // wave (max, lowest id attaining it)
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      float om = __shfl_xor(mx, off, 64);
+      int oi = __shfl_xor(ai, off, 64);
+      if (om > mx || (om == mx && oi < ai)) { mx = om; ai = oi; }
+    }
   }
-  if (tid == 0) {
+  if (lane == 0) {
     pmax[(size_t)r * nc + c] = mx;
     psum[(size_t)r * nc + c] = sum;
     parg[(size_t)r * nc + c] = ai;
   }
 }
 
-// Combine the per-chunk statistics of one row in chunk order: row max, sum of e^{(l-max)/T}, argmax id.
-__device__ inline void combine_row(const float *pmax, const double *psum, const int32_t *parg, int nc, double invT,
-                                   double *m_out, double *S_out, int *arg_out) {
-  float m = pmax[0];
-  int a = parg[0];
-  for (int c = 1; c < nc; ++c)
-    if (pmax[c] > m) { m = pmax[c]; a = parg[c]; }   // strict: the earliest chunk wins ties
-  double S = 0.0;
-  if (invT > 0.0)
-    for (int c = 0; c < nc; ++c) {
-      double sc = (pmax[c] == m) ? 1.0 : exp(((double)pmax[c] - (double)m) * invT);
-      S += psum[c] * sc;
-    }
-  *m_out = (double)m;
-  *S_out = S;
-  *arg_out = a;
-}
-
 #define FSV_MAX_GAMMA 16
 
 template <typename LT>
 __device__ inline double thread_masses(const LT *lrow, const float *qrow, int i0, int V, bool lvec, bool qvec,
-                                       float m, double k, double invS, bool residual, double (&mass)[8]) {
+                                       float m, exp_scale k, double invS, bool residual, bool fast, double (&mass)[8]) {
   float lv[8], qv[8];
-  loader<LT>::load8(lrow, i0, V, lvec, -INFINITY, lv);
-  if (residual) loader<float>::load8(qrow, i0, V, qvec, 0.f, qv);
+  if (fast) {  // the caller has checked alignment and range for the whole sub-block
+    loader<LT>::load8_fast(lrow, i0, lv);
+    if (residual) loader<float>::load8_fast(qrow, i0, qv);
+  } else {
+    loader<LT>::load8(lrow, i0, V, lvec, -INFINITY, lv);
+    if (residual) loader<float>::load8(qrow, i0, V, qvec, 0.f, qv);
+  }
   double t = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -198,86 +225,109 @@ __device__ inline double thread_masses(const LT *lrow, const float *qrow, int i0
   return t;
 }
 
+// Acceptance tests of one request.  Wave w combines the per-chunk statistics of rows w, w+4, ... (one chunk per lane:
+// row max with the lowest id attaining it, then the sum of the rescaled chunk sums over a fixed shuffle tree); then
+// thread i tests draft i+1 from two gathered scalars, and thread 0 takes the accepted prefix.  grid = requests.
 template <typename LT>
-__global__ __launch_bounds__(256) void k_accept_mass(
-    const LT *__restrict__ logits, int V, int nc, int nsb, const int32_t *__restrict__ off,
-    const int32_t *__restrict__ draft, const float *__restrict__ q, const float *__restrict__ u_acc,
-    const float *__restrict__ temperature, const float *__restrict__ pmax, const double *__restrict__ psum,
-    const int32_t *__restrict__ parg, double *__restrict__ bsum, int32_t *__restrict__ tau_ws,
-    double *__restrict__ rowstat, int32_t *__restrict__ accepted_len, int32_t *__restrict__ next_token,
-    uint32_t *__restrict__ flags, int lvec, int qvec) {
-  const int b = blockIdx.y, tid = threadIdx.x;
+__global__ __launch_bounds__(256) void k_accept(
+    const LT *__restrict__ logits, int V, int nc, const int32_t *__restrict__ off, const int32_t *__restrict__ draft,
+    const float *__restrict__ q, const float *__restrict__ u_acc, const float *__restrict__ temperature,
+    const float *__restrict__ pmax, const double *__restrict__ psum, const int32_t *__restrict__ parg,
+    int32_t *__restrict__ tau_ws, double *__restrict__ rowstat, int32_t *__restrict__ accepted_len,
+    int32_t *__restrict__ next_token, uint32_t *__restrict__ flags) {
+  const int b = blockIdx.x, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int o = off[b], gamma = min(off[b + 1] - o, FSV_MAX_GAMMA), rs = o + b;
   const float T = temperature[b];
+  const double invT = (T > 0.f) ? 1.0 / (double)T : 0.0;
+  __shared__ double s_m[FSV_MAX_GAMMA + 1], s_S[FSV_MAX_GAMMA + 1];
+  __shared__ int s_arg[FSV_MAX_GAMMA + 1], s_acc[FSV_MAX_GAMMA], s_near[FSV_MAX_GAMMA];
+  for (int i = w; i <= gamma; i += 4) {
+    const size_t base = (size_t)(rs + i) * nc;
+    const float pm = (lane < nc) ? pmax[base + lane] : -INFINITY;
+    const double ps = (lane < nc) ? psum[base + lane] : 0.0;
+    float mx = pm;
+    int ai = (lane < nc) ? parg[base + lane] : INT_MAX;
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) {
+      const float om = __shfl_xor(mx, sh, 64);
+      const int oi = __shfl_xor(ai, sh, 64);
+      if (om > mx || (om == mx && oi < ai)) { mx = om; ai = oi; }
+    }
+    double term = 0.0;
+    if (T > 0.f && lane < nc) term = ps * ((pm == mx) ? 1.0 : exp(((double)pm - (double)mx) * invT));
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) term += __shfl_xor(term, sh, 64);
+    if (lane == 0) { s_m[i] = (double)mx; s_S[i] = term; s_arg[i] = ai; }
+  }
+  __syncthreads();
   if (T <= 0.f) {  // greedy (Alg. 2): accept while the draft equals the argmax, emit the argmax
-    if (blockIdx.x == 0 && tid == 0) {
-      int tau = 0, am = 0;
-      for (;;) {
-        double m_, S_;
-        combine_row(pmax + (size_t)(rs + tau) * nc, psum, parg + (size_t)(rs + tau) * nc, nc, 0.0, &m_, &S_, &am);
-        if (tau < gamma && draft[o + tau] == am) ++tau; else break;
-      }
+    if (tid == 0) {
+      int tau = 0;
+      while (tau < gamma && draft[o + tau] == s_arg[tau]) ++tau;
       tau_ws[b] = tau;
       accepted_len[b] = tau;
-      next_token[b] = am;
+      next_token[b] = s_arg[tau];
       flags[b] = 0u;
     }
     return;
   }
-  const double invT = 1.0 / (double)T, k = kLog2e * invT;
-  __shared__ double s_m[FSV_MAX_GAMMA + 1], s_S[FSV_MAX_GAMMA + 1];
-  __shared__ int s_acc[FSV_MAX_GAMMA], s_near[FSV_MAX_GAMMA];
-  __shared__ int s_tau;
-  __shared__ double s_w[4];
-  if (tid <= gamma) {
-    const int r = rs + tid;
-    double m, S;
-    int am;
-    combine_row(pmax + (size_t)r * nc, psum + (size_t)r * nc, parg + (size_t)r * nc, nc, invT, &m, &S, &am);
-    s_m[tid] = m;
-    s_S[tid] = S;
-    if (tid < gamma) {  // row r scores draft tid+1
-      int d = min(max(draft[o + tid], 0), V - 1);
-      float lv;
-      if constexpr (sizeof(LT) == 2) lv = __uint_as_float((uint32_t)logits[(size_t)r * V + d] << 16);
-      else lv = logits[(size_t)r * V + d];
-      double p = exp(((double)lv - m) * invT) / S;
-      double qd = (double)q[(size_t)(o + tid) * V + d];
-      double ratio = p / qd;
-      double a = (ratio >= 1.0) ? 1.0 : ratio;
-      if (!(a == a)) a = 0.0;
-      double u = (double)u_acc[o + tid];
-      s_acc[tid] = (u < a) ? 1 : 0;
-      s_near[tid] = (fabs(u - a) < 1e-4) ? 1 : 0;
-    }
+  if (tid < gamma) {  // row rs + tid scores draft tid + 1
+    const int r = rs + tid, d = min(max(draft[o + tid], 0), V - 1);
+    float lv;
+    if constexpr (sizeof(LT) == 2) lv = __uint_as_float((uint32_t)logits[(size_t)r * V + d] << 16);
+    else lv = logits[(size_t)r * V + d];
+    const double p = exp(((double)lv - s_m[tid]) * invT) / s_S[tid];
+    const double qd = (double)q[(size_t)(o + tid) * V + d];
+    const double ratio = p / qd;
+    double a = (ratio >= 1.0) ? 1.0 : ratio;
+    if (!(a == a)) a = 0.0;
+    const double u = (double)u_acc[o + tid];
+    s_acc[tid] = (u < a) ? 1 : 0;
+    s_near[tid] = (fabs(u - a) < 1e-4) ? 1 : 0;
   }
   __syncthreads();
   if (tid == 0) {
     int tau = 0;
     while (tau < gamma && s_acc[tau]) ++tau;
-    s_tau = tau;
-  }
-  __syncthreads();
-  const int tau = s_tau;
-  const bool residual = tau < gamma;
-  const double m = s_m[tau], invS = 1.0 / s_S[tau];
-  if (blockIdx.x == 0 && tid == 0) {
-    uint32_t f = residual ? 4u : 0u;
+    uint32_t f = (tau < gamma) ? 4u : 0u;
     for (int i = 0; i < gamma && i <= tau; ++i) f |= s_near[i] ? 1u : 0u;
     tau_ws[b] = tau;
     accepted_len[b] = tau;
     flags[b] = f;
-    rowstat[2 * b] = m;
-    rowstat[2 * b + 1] = invS;
+    rowstat[2 * b] = s_m[tau];
+    rowstat[2 * b + 1] = 1.0 / s_S[tau];
   }
+}
+
+// Mass of every 2048-id sub-block of the row the emitted token is drawn from (the residual max(0, p - q) after a
+// rejection, p itself when every draft passed): one wave per sub-block, four passes of 512 ids, so the loop needs no
+// block-wide synchronisation.  grid = (sub-blocks / 4, requests).
+template <typename LT>
+__global__ __launch_bounds__(256) void k_mass(const LT *__restrict__ logits, int V, int nsb, const int32_t *__restrict__ off,
+                                              const float *__restrict__ q, const float *__restrict__ temperature,
+                                              const int32_t *__restrict__ tau_ws, const double *__restrict__ rowstat,
+                                              double *__restrict__ bsum, int lvec, int qvec) {
+  const int b = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const float T = temperature[b];
+  if (T <= 0.f) return;
+  const int o = off[b], gamma = min(off[b + 1] - o, FSV_MAX_GAMMA), rs = o + b, tau = tau_ws[b];
+  const bool residual = tau < gamma;
+  const double m = rowstat[2 * b], invS = rowstat[2 * b + 1];
+  const exp_scale k = make_exp_scale(kLog2e / (double)T);
   const LT *lrow = logits + (size_t)(rs + tau) * V;
   const float *qrow = residual ? q + (size_t)(o + tau) * V : nullptr;
-  for (int sb = blockIdx.x; sb < nsb; sb += gridDim.x) {
-    double mass[8], tot;
-    double t = thread_masses<LT>(lrow, qrow, sb * FSV_SBK + tid * 8, V, lvec != 0, qvec != 0, (float)m, k, invS,
-                                 residual, mass);
-    block_incl_scan(t, s_w, &tot);
-    if (tid == 0) bsum[(size_t)b * nsb + sb] = tot;
+  for (int sb = blockIdx.x * 4 + w; sb < nsb; sb += gridDim.x * 4) {
+    double tot = 0.0;
+    const bool fast = lvec && qvec && (sb + 1) * FSV_SBK <= V;  // wave-uniform
+#pragma unroll
+    for (int part = 0; part < FSV_SBK / 512; ++part) {
+      double mass[8];
+      tot += thread_masses<LT>(lrow, qrow, sb * FSV_SBK + part * 512 + lane * 8, V, lvec != 0, qvec != 0, (float)m, k, invS,
+                               residual, fast, mass);
+    }
+#pragma unroll
+    for (int sh = 32; sh > 0; sh >>= 1) tot += __shfl_xor(tot, sh, 64);
+    if (lane == 0) bsum[(size_t)b * nsb + sb] = tot;
   }
 }
 
@@ -307,7 +357,7 @@ __global__ __launch_bounds__(256) void k_select(
   __shared__ int s_pick, s_first, s_lastpos;
   bool residual = tau < gamma;
   const double m = rowstat[2 * b], invS = rowstat[2 * b + 1];
-  const double k = kLog2e / (double)T;
+  const exp_scale k = make_exp_scale(kLog2e / (double)T);
   const LT *lrow = logits + (size_t)(rs + tau) * V;
   const float *qrow = residual ? q + (size_t)(o + tau) * V : nullptr;
   for (int sb = tid; sb < nsb; sb += 256) s_sb[sb] = bsum[(size_t)b * nsb + sb];
@@ -326,7 +376,7 @@ __global__ __launch_bounds__(256) void k_select(
     for (int sb = 0; sb < nsb; ++sb) {
       double mass[8], tot;
       double t = thread_masses<LT>(lrow, qrow, sb * FSV_SBK + tid * 8, V, lvec != 0, qvec != 0, (float)m, k, invS,
-                                   false, mass);
+                                   false, false, mass);
       block_incl_scan(t, s_w, &tot);
       if (tid == 0) s_sb[sb] = tot;
     }
@@ -359,7 +409,7 @@ __global__ __launch_bounds__(256) void k_select(
   const double lo = s_lo;
   double mass[8];
   const int i0 = sb * FSV_SBK + tid * 8;
-  double t = thread_masses<LT>(lrow, qrow, i0, V, lvec != 0, qvec != 0, (float)m, k, invS, residual, mass);
+  double t = thread_masses<LT>(lrow, qrow, i0, V, lvec != 0, qvec != 0, (float)m, k, invS, residual, false, mass);
   double incl = block_incl_scan(t, s_w, nullptr);
   const bool crosses = (lo + incl) > target;  // false for every thread when lo == inf
   if (crosses) atomicMin(&s_first, tid);
@@ -417,15 +467,16 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
   int32_t *acc = r->accepted_len ? r->accepted_len : c->acc_scratch;
   {
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_STATS, (double)M * V * sizeof(LT));
-    hipLaunchKernelGGL(k_row_stats<LT>, dim3(nc, M), dim3(256), 0, s, logits, V, nc, c->row_req, b->temperature,
+    hipLaunchKernelGGL(k_row_stats<LT>, dim3(fsv_ceil_div(nc, 4), M), dim3(256), 0, s, logits, V, nc, c->row_req, b->temperature,
                        c->pmax, c->psum, c->parg, lvec);
   }
   {
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_ACCEPT, (double)B * V * (sizeof(LT) + 4));
-    int slices = nsb < 8 ? nsb : 8;
-    hipLaunchKernelGGL(k_accept_mass<LT>, dim3(slices, B), dim3(256), 0, s, logits, V, nc, nsb, b->draft_offsets,
-                       b->draft_tokens, b->draft_probs, b->u_accept, b->temperature, c->pmax, c->psum, c->parg,
-                       c->bsum, c->tau_ws, c->rowstat, acc, r->next_token, r->flags, lvec, qvec);
+    hipLaunchKernelGGL(k_accept<LT>, dim3(B), dim3(256), 0, s, logits, V, nc, b->draft_offsets, b->draft_tokens,
+                       b->draft_probs, b->u_accept, b->temperature, c->pmax, c->psum, c->parg, c->tau_ws, c->rowstat, acc,
+                       r->next_token, r->flags);
+    hipLaunchKernelGGL(k_mass<LT>, dim3(fsv_ceil_div(nsb, 4), B), dim3(256), 0, s, logits, V, nsb, b->draft_offsets,
+                       b->draft_probs, b->temperature, c->tau_ws, c->rowstat, c->bsum, lvec, qvec);
   }
   {
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_SELECT, (double)B * FSV_SBK * (sizeof(LT) + 4));
