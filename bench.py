@@ -127,6 +127,8 @@ def main():
     ap.add_argument("--workload", default="c3_8b_b16")
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pages", default=None, choices=["interleaved", "permuted", "contiguous"],
+                    help="page-table layout of the KV sessions (default: the workload's own, interleaved)")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (one extra untimed pass)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, the known-size reference the HBM counters are scaled by")
@@ -144,6 +146,9 @@ def main():
     if args.workload == "c4_sampler":
         return sampler_bench(args, torch, fv, synth)
     wl = synth.WORKLOADS[args.workload]
+    if args.pages:
+        from dataclasses import replace
+        wl = replace(wl, pages=args.pages)
     cfg = synth.MODELS[wl.model]
     log(f"workload {wl.name}: model {cfg.name}, generating weights on the device")
     weights = synth.make_weights(cfg, args.seed, device="cuda")

@@ -88,7 +88,7 @@ void fsv_destroy(fsv_ctx *c) {
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->x, c->logits,
-                  c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_tiles, c->attn_part_map};
+                  c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   for (auto &L : c->layers) {

@@ -44,19 +44,23 @@ __device__ __host__ inline int attn_parts(int n, int tpw, int *tp) {
   return (n + *tp - 1) / *tp;
 }
 
-// part_prefix[b] = parts of requests before b, part_tiles[b] = tiles per part, part_map[global part] = request
+// part_prefix[b] = parts of requests before b (the merge kernel's index); part_desc[global part] = everything a wave of
+// the attention kernel needs to start, in one 32-byte record: request, first tile, tiles, parts of the request, cached
+// length, drafts, first row, (pad) -- a wave fetches it with a single scalar load instead of a chain of dependent ones
 __global__ void k_attn_plan(int B, int tpw, const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ off,
-                            int32_t *__restrict__ part_prefix, int32_t *__restrict__ part_tiles,
-                            int32_t *__restrict__ part_map, int map_cap) {
+                            int32_t *__restrict__ part_prefix, int32_t *__restrict__ part_desc, int map_cap) {
   if (blockIdx.x != 0 || threadIdx.x != 0) return;
   int run = 0;
   for (int b = 0; b < B; ++b) {
-    const int nk = seq_lens[b] + (off[b + 1] - off[b]) + 1;
+    const int L = seq_lens[b], gamma = off[b + 1] - off[b], nk = L + gamma + 1, n = (nk + 31) >> 5;
     int tp;
-    const int s = attn_parts((nk + 31) >> 5, tpw, &tp);
+    const int s = attn_parts(n, tpw, &tp);
     part_prefix[b] = run;
-    part_tiles[b] = tp;
-    for (int p = 0; p < s && run + p < map_cap; ++p) part_map[run + p] = b;
+    for (int p = 0; p < s && run + p < map_cap; ++p) {
+      int32_t *d = part_desc + (size_t)(run + p) * 8;
+      d[0] = b; d[1] = p * tp; d[2] = min(n, (p + 1) * tp) - p * tp; d[3] = s;
+      d[4] = L; d[5] = gamma; d[6] = off[b] + b; d[7] = 0;
+    }
     run += s;
   }
   part_prefix[B] = run;
@@ -64,22 +68,20 @@ __global__ void k_attn_plan(int B, int tpw, const int32_t *__restrict__ seq_lens
 
 template <int HD, int RT, int NB>
 __global__ __launch_bounds__(64) void k_attention(
-    int Hkv, int group, int rows_cap, const uint4 *__restrict__ qp, const int32_t *__restrict__ seq_lens,
-    const int32_t *__restrict__ off, const int32_t *__restrict__ part_map, const int32_t *__restrict__ part_prefix,
-    const int32_t *__restrict__ part_tiles, const int32_t *__restrict__ page_table, int max_pages, int num_pages,
-    const uint16_t *__restrict__ kpool, const uint16_t *__restrict__ vpool, uint32_t layer_bytes,
-    float *__restrict__ part_o, float *__restrict__ part_ml, uint16_t *__restrict__ out, int KBq) {
+    int Hkv, int group, int rows_cap, const uint4 *__restrict__ qp, const int32_t *__restrict__ part_desc,
+    const int32_t *__restrict__ page_table, int max_pages, int num_pages, const uint16_t *__restrict__ kpool,
+    const uint16_t *__restrict__ vpool, uint32_t layer_bytes, float *__restrict__ part_o, float *__restrict__ part_ml,
+    uint16_t *__restrict__ out, int KBq) {
   constexpr int KS = HD / 16, VC = HD / 32, TILEB = 16 * HD * 2;  // TILEB: bytes of one (page, kv head) tile
   constexpr uint32_t OOB = 0xFFFF0000u;                            // offset no descriptor here reaches
   constexpr int kStream = 2;  // non-temporal: K/V bytes are used once and should not displace the queries and partials in L2
   __shared__ uint4 s_q[RT * KS * 64];
   const int lane = threadIdx.x, h = lane >> 5, r = lane & 31;
   const int gw = blockIdx.x, pp = gw / Hkv, kvh = gw - pp * Hkv;
-  const int b = part_map[pp];
-  const int part = pp - part_prefix[b], nparts = part_prefix[b + 1] - part_prefix[b], tp = part_tiles[b];
-  const int L = seq_lens[b], gamma = off[b + 1] - off[b], rs = off[b] + b;
+  const int4 d0 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * 8);
+  const int4 d1 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * 8 + 4);
+  const int b = d0.x, t0 = d0.y, myt = d0.z, nparts = d0.w, L = d1.x, gamma = d1.y, rs = d1.z;
   const int nk = L + gamma + 1, R = group * (gamma + 1);
-  const int t0 = part * tp, myt = min((nk + 31) >> 5, t0 + tp) - t0;  // >= 1 by construction of the parts
   const int rtc = min(RT, (R + 31) >> 5);
   const int32_t *pt = page_table + (size_t)b * max_pages;
   const int npg = (nk + 15) >> 4;
@@ -111,7 +113,10 @@ __global__ __launch_bounds__(64) void k_attention(
 
   // Queries go from global memory straight into LDS (no staging registers; lane i of a load fills 16-byte unit i
   // of the addressed LDS block, which is the operand order already); rows beyond R hold whatever an earlier call
-  // left there: they only feed their own output rows, which are never stored.  Then the first NB - 1 tiles.
+  // left there: they only feed their own output rows, which are never stored.  The wave waits for them here, before
+  // the K/V stream starts: a wait placed after the first tiles were issued would have to drain those as well
+  // (loads complete in order), and the pipeline would start empty.  The page ids of the first tiles are fetched by
+  // scalar loads meanwhile.
 #pragma unroll
   for (int i = 0; i < RT * KS; ++i) {
     if (i / KS >= rtc) continue;
@@ -119,15 +124,15 @@ __global__ __launch_bounds__(64) void k_attention(
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
                                      (__attribute__((address_space(3))) void *)&s_q[i * 64], 16, 0, 0);
   }
-  int g0n, g1n;
+  int gp0[NB], gp1[NB];
 #pragma unroll
-  for (int s = 0; s < NB - 1; ++s) {
-    pages_of(s, g0n, g1n);
-    issue(s, g0n, g1n, kb[s], vb[s]);
-  }
-  pages_of(NB - 1, g0n, g1n);
+  for (int s = 0; s < NB; ++s) pages_of(s, gp0[s], gp1[s]);
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the queries are in LDS
   __builtin_amdgcn_sched_barrier(0);
-  __syncthreads();  // one wave per block: orders the LDS fill before the operand reads below
+#pragma unroll
+  for (int s = 0; s < NB - 1; ++s) issue(s, gp0[s], gp1[s], kb[s], vb[s]);
+  int g0n = gp0[NB - 1], g1n = gp1[NB - 1];
+  __builtin_amdgcn_sched_barrier(0);
 
   const float sc = kLog2eF / sqrtf((float)HD);
   f32x16_t o[RT][VC];
@@ -370,7 +375,7 @@ int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
 
 int launch_attn_plan(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, hipStream_t st) {
   hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(64), 0, st, b->batch, pl.tpw, b->seq_lens, b->draft_offsets,
-                     c->attn_part_prefix, c->attn_part_tiles, c->attn_part_map, c->attn_wave_cap / c->d.n_kv_heads + 1);
+                     c->attn_part_prefix, c->attn_part_map, c->attn_wave_cap / c->d.n_kv_heads + 1);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -389,13 +394,12 @@ int launch_attention(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, si
 #define FSV_ATTN_LAUNCH(HDV, RTV, NBV)                                                                            \
   hipExtLaunchKernelGGL((k_attention<HDV, RTV, NBV>), dim3(pl.waves), dim3(64), 0, st, ps.start(), ps.stop(), 0,   \
                         d.n_kv_heads, group, rows_cap,                                                             \
-                     (const uint4 *)c->buf_q, b->seq_lens, b->draft_offsets, c->attn_part_map, c->attn_part_prefix, \
-                     c->attn_part_tiles, b->page_table, d.max_pages_per_req, b->num_pages, kl, vl, layer_bytes, po, \
-                     pml, out, KBq)
+                     (const uint4 *)c->buf_q, c->attn_part_map, b->page_table, d.max_pages_per_req, b->num_pages,  \
+                     kl, vl, layer_bytes, po, pml, out, KBq)
     if (d.head_dim == 128) {
-      if (pl.rt <= 1) FSV_ATTN_LAUNCH(128, 1, 4); else if (pl.rt == 2) FSV_ATTN_LAUNCH(128, 2, 4); else FSV_ATTN_LAUNCH(128, 3, 2);
+      if (pl.rt <= 1) FSV_ATTN_LAUNCH(128, 1, 2); else if (pl.rt == 2) FSV_ATTN_LAUNCH(128, 2, 2); else FSV_ATTN_LAUNCH(128, 3, 2);
     } else {
-      if (pl.rt <= 1) FSV_ATTN_LAUNCH(64, 1, 4); else if (pl.rt == 2) FSV_ATTN_LAUNCH(64, 2, 4); else FSV_ATTN_LAUNCH(64, 3, 4);
+      if (pl.rt <= 1) FSV_ATTN_LAUNCH(64, 1, 2); else if (pl.rt == 2) FSV_ATTN_LAUNCH(64, 2, 2); else FSV_ATTN_LAUNCH(64, 3, 2);
     }
 #undef FSV_ATTN_LAUNCH
     FSV_HIP(c, hipGetLastError());
@@ -441,7 +445,6 @@ int fsv_bf16_attn_create(fsv_ctx *c) {
   int rc;
   if ((rc = zalloc(&c->attn_part, c->attn_part_bytes))) return rc;
   if ((rc = zalloc((void **)&c->attn_part_prefix, sizeof(int32_t) * (d.max_batch + 1)))) return rc;
-  if ((rc = zalloc((void **)&c->attn_part_tiles, sizeof(int32_t) * d.max_batch))) return rc;
-  if ((rc = zalloc((void **)&c->attn_part_map, sizeof(int32_t) * (c->attn_wave_cap / d.n_kv_heads + 1)))) return rc;
+  if ((rc = zalloc((void **)&c->attn_part_map, sizeof(int32_t) * 8 * (c->attn_wave_cap / d.n_kv_heads + 1)))) return rc;
   return FSV_OK;
 }

@@ -71,7 +71,7 @@ struct fsv_ctx {
   int n_cus = 0;                // compute units of the device the context was created on
   int attn_wave_target = 0;     // waves the attention schedule aims at (resident waves of the device)
   int attn_wave_cap = 0;        // waves the partial buffers hold
-  int32_t *attn_part_prefix = nullptr, *attn_part_tiles = nullptr, *attn_part_map = nullptr;
+  int32_t *attn_part_prefix = nullptr, *attn_part_map = nullptr;   // parts before each request; 8-int record per part
 
   // profiling
   uint32_t prof_mask = 0;

@@ -177,7 +177,8 @@ def make_page_table(seq_lens, gammas, page_size: int, kind: str, seed: int):
     """Physical page ids for every request's logical pages.
 
     "interleaved": logical page j of request b is physical page j*B + b (round-robin over requests);
-    "permuted": a seeded random permutation of the same set of pages.
+    "permuted": a seeded random permutation of the same set of pages;
+    "contiguous": request b owns physical pages b*max_pages .. (b+1)*max_pages - 1 in order.
     """
     B = len(seq_lens)
     need = [(int(seq_lens[b]) + int(gammas[b]) + 1 + page_size - 1) // page_size for b in range(B)]
@@ -189,6 +190,8 @@ def make_page_table(seq_lens, gammas, page_size: int, kind: str, seed: int):
     if kind == "permuted":
         perm = torch.randperm(num_pages, generator=_gen(seed, 4)).numpy().astype(np.int32)
         pt = perm[pt]
+    elif kind == "contiguous":
+        pt = (np.arange(B, dtype=np.int32)[:, None] * max_pages + np.arange(max_pages, dtype=np.int32)[None, :]).astype(np.int32)
     elif kind != "interleaved":
         raise ValueError(kind)
     return pt, num_pages
