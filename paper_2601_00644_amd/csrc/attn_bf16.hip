@@ -331,7 +331,7 @@ __global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int ro
   reinterpret_cast<uint4 *>(out)[tile_unit(m, col, KBq)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }
 
-constexpr int kAttnWavesPerCu = 4;  // one per SIMD: a wave of this kernel takes the whole register file of its SIMD
+constexpr int kAttnWavesPerCu = 3;  // a wave takes most of a SIMD's registers, so at most four fit; three measured best on MI355X
 
 // Size the parts from the host copies of the lengths: the smallest part length for which parts x kv heads
 // still fits the machine once (or one part per request when even that does not fit).

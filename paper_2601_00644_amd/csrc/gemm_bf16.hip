@@ -5,7 +5,7 @@
 //
 // A block is four compute waves and one loader wave.  Compute wave w owns 32 output features (one weight
 // tile row) for up to MT*32 batch rows over the block's K range and streams that strip of the re-tiled
-// matrix straight from HBM into MFMA operand registers, D chunks of 128 k ahead of its use.  The loader wave
+// matrix straight from HBM into MFMA operand registers, D chunks of 128 k (D = 1) ahead of its use.  The loader wave
 // copies the activation chunks of the same K range from global memory (L2) directly into a three-stage LDS
 // ring, two chunks ahead; the compute waves read their B operands from the ring.  Because the activation
 // loads are issued by a wave of their own, the compute waves' load counter tracks the weight stream only
@@ -213,7 +213,9 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
 template <int MT, int EPI>
 int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt,
              int M, int Mpad, int splits, int nchunks, int KBo, hipStream_t st) {
-  constexpr int D = 2;  // weight chunks in flight per wave ahead of the one in use (deeper did not pay on MI355X)
+  // Weight chunks in flight per wave ahead of the one in use.  Measured on MI355X, one is best: with two to four the
+  // bytes in flight across the chip approach the size of the L2s they pass through and the achieved bandwidth drops.
+  constexpr int D = 1;
   const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;
   static bool attr_set = false;  // per instantiation
   if (!attr_set) {
