@@ -15,7 +15,7 @@ namespace {
 // ---------------------------------------------------------------------------------------------
 // Work decomposition.  The keys of request b are cut into tiles of 32 (two pages); a "part" is a run of
 // tp_b consecutive tiles, s_b parts per request, chosen so that every part of every request has about the
-// same length and parts x kv heads fills the machine once (one wave per part and kv head, four waves per
+// same length and parts x kv heads fills the machine once (one wave per part and kv head, about three waves per
 // compute unit, every wave resident from the start).  A wave owns its part completely: it streams the K and
 // V page tiles of its key range straight from HBM into MFMA operand registers, NB - 1 tiles ahead of their
 // use (each byte of the KV stream is read by exactly one wave; all `group` query heads and all gamma+1
