@@ -35,26 +35,31 @@ constexpr int GRAN = 2;   // chunks per 256-element granule of the K cut
 template <int MT, int EPI, int D>
 __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
                                               void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                              int S, int nchunks, int KBo) {
+                                              int S, int nchunks, int KBo, int NBv, int MB) {
   extern __shared__ uint4 lds[];
   constexpr int CHU = MT * KC * 64;  // 16-byte units of one activation chunk
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5;
-  // Blocks are dealt to the eight XCDs round robin by their linear index.  With a multiple of eight splits the
-  // index is decoded so that a split always lands on the same XCD: every XCD then stages only its own K slices of
-  // the activation matrix, which stay in its L2, instead of all of it.
-  int nblk, split;
+  // Blocks are dealt to the eight XCDs round robin by their linear index, which is decoded as
+  // (XCD, row block, split group, feature block) with the row block fastest: the row blocks that need the same
+  // weight strip are then neighbours in time on ONE XCD and all but the first find the strip in that XCD's L2
+  // (many rows: the weights come from HBM once, not once per row block), and with a multiple of eight splits a
+  // split always lands on the same XCD, so every XCD stages only its own K slices of the activation matrix.
+  int nblk, split, zb;
   {
-    const int L = blockIdx.x;
+    const int L = blockIdx.x, x = L & 7, a = L >> 3;
+    zb = a % MB;
+    const int a2 = a / MB;
     if ((S & 7) == 0) {
-      const int a = L >> 3, s8 = S >> 3;
-      split = (L & 7) + 8 * (a % s8);
-      nblk = a / s8;
-    } else {
-      split = L % S;
-      nblk = L / S;
+      const int s8 = S >> 3;
+      split = x + 8 * (a2 % s8);
+      nblk = a2 / s8;
+    } else {  // the host pads the feature blocks to a multiple of eight in this case
+      split = a2 % S;
+      nblk = (a2 / S) * 8 + x;
     }
   }
-  const int mt0 = blockIdx.z * MT, mtc = min(MT, Mt_total - mt0), mlast = mtc - 1;
+  if (nblk >= NBv) return;  // padding block (whole block, before any barrier)
+  const int mt0 = zb * MT, mtc = min(MT, Mt_total - mt0), mlast = mtc - 1;
   // K range of the split: a balanced cut of the `nchunks` granules into S parts, counted in chunks
   const int cb0 = (split * nchunks / S) * GRAN, per = ((split + 1) * nchunks / S) * GRAN - cb0;
 
@@ -212,7 +217,7 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
 
 template <int MT, int EPI>
 int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt,
-             int M, int Mpad, int splits, int nchunks, int KBo, hipStream_t st) {
+             int M, int Mpad, int splits, int nchunks, int KBo, int NB, int mblocks, hipStream_t st) {
   // Weight chunks in flight per wave ahead of the one in use.  Measured on MI355X, one is best: with two to four the
   // bytes in flight across the chip approach the size of the L2s they pass through and the achieved bandwidth drops.
   constexpr int D = 1;
@@ -226,7 +231,7 @@ int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, co
   // the profiling events ride on the dispatch itself: they time the kernel, not the gaps around it
   fsv_prof_scope ps(c, st, cls, (double)N * KB * 32.0, true);
   hipExtLaunchKernelGGL((k_gemm<MT, EPI, D>), grid, dim3(320), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
-                        (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo);
+                        (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks);
   return FSV_OK;
 }
 
@@ -238,8 +243,10 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
   const size_t wbytes = (size_t)NTpad * KB * 1024;
   if (wbytes > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
   if (splits < 1 || splits > nchunks) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad split count %d for %d granules", splits, nchunks);
-  dim3 grid(NTpad / 4 * splits, 1, mblocks);
-#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, st
+  // one-dimensional grid, decoded in the kernel; feature blocks padded to a multiple of eight when the splits are not
+  const int NB = NTpad / 4, NBg = (splits % 8 == 0) ? NB : (NB + 7) / 8 * 8;
+  dim3 grid((unsigned)NBg * splits * mblocks, 1, 1);
+#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, st
   switch (mt_blk) {
     case 1: return launch_t<1, EPI>(FSV_ARGS);
     case 2: return launch_t<2, EPI>(FSV_ARGS);
