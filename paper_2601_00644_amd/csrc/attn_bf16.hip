@@ -33,6 +33,9 @@ namespace {
 // by loads and read by MFMAs, both of which reach that half directly; keeping them there leaves the
 // architectural half to the softmax arithmetic and the output accumulators.
 #define FSV_IN_AGPR(x) asm("" : "+a"(x))
+#ifndef FSV_RT_FENCE
+#define FSV_RT_FENCE __builtin_amdgcn_sched_barrier(0);
+#endif
 // Pins an MFMA accumulator to the architectural half: the softmax reads the score tile and rescales the output
 // tiles with ordinary vector instructions, which cannot address the accumulation half.
 #define FSV_IN_VGPR(x)
@@ -226,7 +229,7 @@ __global__ __launch_bounds__(64) void k_attention(
         o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pb[1], o[rt][c], 0, 0, 0);
         FSV_IN_VGPR(o[rt][c]);
       }
-      __builtin_amdgcn_sched_barrier(0);  // row tiles one after the other: interleaved, their temporaries add up
+      FSV_RT_FENCE
     }
   };
 
@@ -337,35 +340,41 @@ constexpr int kAttnWavesPerCu = 3;  // a wave takes most of a SIMD's registers, 
 // still fits the machine once (or one part per request when even that does not fit).
 int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
   const fsv_model_desc &d = c->d;
-  int max_n = 1, max_rows = 0;
+  int max_rows = 0;
   long total_tiles = 0;
   for (int i = 0; i < b->batch; ++i) {
     const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
     const int n = fsv_ceil_div(nk, 32);
-    max_n = max(max_n, n);
     max_rows = max(max_rows, c->group * (g + 1));
     total_tiles += n;
     pl->kv_tokens += nk;
   }
+  // One round if it can be had: the smallest part length, up to twice the even share, for which parts x kv heads fit the
+  // resident waves.  Otherwise (many requests, or a few very long ones among many short ones) parts of a quarter of the
+  // even share, run in several rounds: waves are independent, so the hardware keeps every slot busy and the last round
+  // is short.  Keeping whole requests as single parts instead would let the longest request set the kernel's time.
   const int target = c->attn_wave_target;
-  int tpw = (int)max(2L, (total_tiles * d.n_kv_heads + target - 1) / target);
-  for (;; ++tpw) {
+  auto count = [&](int tpw, bool *split) {
     int parts = 0;
-    bool split = false;
+    *split = false;
     for (int i = 0; i < b->batch; ++i) {
       const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
       int tp;
       const int s = attn_parts(fsv_ceil_div(nk, 32), tpw, &tp);
       parts += s;
-      split |= s > 1;
+      *split |= s > 1;
     }
-    if (parts * d.n_kv_heads <= target || tpw >= max_n) {
-      pl->tpw = tpw;
-      pl->waves = parts * d.n_kv_heads;
-      pl->split = split;
-      break;
-    }
+    return parts * d.n_kv_heads;
+  };
+  const int even = (int)max(2L, (total_tiles * d.n_kv_heads + target - 1) / target);
+  int tpw = 0;
+  for (int t = even; t <= 2 * even; ++t) {
+    bool sp;
+    if (count(t, &sp) <= target) { tpw = t; break; }
   }
+  if (!tpw) tpw = max(8, (even + 3) / 4);
+  pl->tpw = tpw;
+  pl->waves = count(tpw, &pl->split);
   pl->rt = fsv_ceil_div(max_rows, 32);
   if (pl->waves > c->attn_wave_cap) FSV_FAIL(c, FSV_E_CAPACITY, "%d attention parts > %d the workspace holds", pl->waves, c->attn_wave_cap);
   if ((size_t)b->num_pages * d.n_kv_heads * 16 * d.head_dim * 2 > 0xFFFF0000ull)
@@ -434,7 +443,7 @@ int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl
 int fsv_bf16_attn_create(fsv_ctx *c) {
   const fsv_model_desc &d = c->d;
   c->attn_wave_target = c->n_cus * kAttnWavesPerCu;
-  c->attn_wave_cap = max(c->attn_wave_target, d.max_batch * d.n_kv_heads);
+  c->attn_wave_cap = 4 * c->attn_wave_target + 2 * d.max_batch * d.n_kv_heads;  // multi-round schedules: see plan_attention
   const int rows_cap = c->group * (d.max_gamma + 1);
   c->attn_part_bytes = (size_t)c->attn_wave_cap * rows_cap * (d.head_dim + 2) * 4;
   auto zalloc = [&](void **p, size_t bytes) -> int {
