@@ -132,7 +132,9 @@ typedef struct {
  * Create a context: validate the description, copy / re-tile the weights, allocate the workspace.
  * Supported shapes: page_size 16; head_dim 64 or 128 for FSV_BF16 (any even head_dim for FSV_F32);
  * n_heads a multiple of n_kv_heads with n_heads / n_kv_heads * (max_gamma + 1) <= 96;
- * d_model, d_ffn and n_heads*head_dim multiples of 256 for FSV_BF16.
+ * d_model, d_ffn and n_heads*head_dim multiples of 256 for FSV_BF16; every weight matrix below 4 GiB.
+ * For FSV_BF16 one layer of a KV pool (num_pages * n_kv_heads * 16 * head_dim * 2 bytes) must stay below
+ * 4 GiB: fsv_verify / fsv_attention return FSV_E_UNSUPPORTED otherwise.
  * weights may be NULL only when n_layers == 0.
  */
 int fsv_create(const fsv_model_desc *desc, const fsv_weights *weights, fsv_ctx **out);

@@ -15,7 +15,7 @@ OBJ = os.path.join(HERE, "_build")
 
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-         "-fno-gpu-rdc"] + os.environ.get("FSV_DEFS", "").split()
+         "-fno-gpu-rdc"]
 
 
 # per-file flags: the attention kernels keep their MFMA accumulators in architectural registers

@@ -33,9 +33,6 @@ namespace {
 // by loads and read by MFMAs, both of which reach that half directly; keeping them there leaves the
 // architectural half to the softmax arithmetic and the output accumulators.
 #define FSV_IN_AGPR(x) asm("" : "+a"(x))
-#ifndef FSV_RT_FENCE
-#define FSV_RT_FENCE __builtin_amdgcn_sched_barrier(0);
-#endif
 // Pins an MFMA accumulator to the architectural half: the softmax reads the score tile and rescales the output
 // tiles with ordinary vector instructions, which cannot address the accumulation half.
 #define FSV_IN_VGPR(x)
@@ -229,7 +226,7 @@ __global__ __launch_bounds__(64) void k_attention(
         o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pb[1], o[rt][c], 0, 0, 0);
         FSV_IN_VGPR(o[rt][c]);
       }
-      FSV_RT_FENCE
+      __builtin_amdgcn_sched_barrier(0);  // row tiles one after the other: interleaved, their temporaries add up
     }
   };
 
