@@ -119,6 +119,42 @@ def sampler_bench(args, torch, fv, synth):
     print(json.dumps(out), flush=True)
 
 
+def gemm_sweep(args, torch, fv, synth):
+    """The GEMM kernel alone (fsv_linear on the 8B gate|up matrix, 4096 -> 28672) over a sweep of row counts:
+    achieved weight-stream GB/s and bf16 MFMA TFLOP/s per launch, from events carried by the dispatch."""
+    import dataclasses
+    cfg = dataclasses.replace(synth.MODELS["llama8b"], n_layers=4, vocab=32000, name="llama8b_4layers")
+    log("workload gemm_sweep: 4 layers of 8B-shape weights")
+    weights = synth.make_weights(cfg, args.seed, device="cuda")
+    rows = [8, 16, 32, 64, 97, 128, 256, 512, 1024, 2048]
+    ctx = fv.Context(cfg, weights, max_batch=128, max_gamma=15, max_pages_per_req=1, max_rows=max(rows))
+    del weights
+    torch.cuda.empty_cache()
+    K, N = cfg.d_model, 2 * cfg.d_ffn
+    table = []
+    for M in rows:
+        x = torch.randn((M, K), device="cuda").to(torch.bfloat16)
+        for l in range(cfg.n_layers):
+            ctx.linear(fv.W_GATE_UP, l, x, N)
+        torch.cuda.synchronize()
+        ctx.profile_read()
+        ctx.profile_enable(["gemm_gate_up"])
+        for _ in range(args.steps):
+            for l in range(cfg.n_layers):          # a different matrix every launch: nothing stays in the caches
+                ctx.linear(fv.W_GATE_UP, l, x, N)
+        torch.cuda.synchronize()
+        p = ctx.profile_read()["gemm_gate_up"]
+        ctx.profile_enable(False)
+        us = p["total_ms"] / p["launches"] * 1e3
+        table.append({"rows": M, "avg_us": round(us, 2), "weight_GBps": round(N * K * 2 / us / 1e3, 1),
+                      "mfma_TFLOPs": round(2.0 * M * N * K / us / 1e6, 1),
+                      "frac_hbm_peak": round(N * K * 2 / us / 1e3 / HBM_PEAK_GBS, 3),
+                      "frac_mfma_peak": round(2.0 * M * N * K / us / 1e6 / 2500.0, 3)})
+        log(str(table[-1]))
+    print(json.dumps({"metric": "weight-streaming GEMM alone, 8B gate|up matrix (28672 x 4096 bf16), per launch",
+                      "config": {"workload": "gemm_sweep"}, "dtype": "bf16", "data": "synthetic", "sweep": table}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,6 +181,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     if args.workload == "c4_sampler":
         return sampler_bench(args, torch, fv, synth)
+    if args.workload == "gemm_sweep":
+        return gemm_sweep(args, torch, fv, synth)
     wl = synth.WORKLOADS[args.workload]
     if args.pages:
         from dataclasses import replace

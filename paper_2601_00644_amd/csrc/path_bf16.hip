@@ -10,14 +10,16 @@
 // Weights use it with r = output feature (re-tiled once at create), activations with r = batch row.
 // The product is formed transposed, D[n][m] = sum_k W[n][k] X[m][k], so each lane ends up with four
 // consecutive output features of one row.
+//
+// This file: weight re-tiling, the residual / RMSNorm kernel (fused with the split-K reduction), RoPE + KV append,
+// session import / export, and the launch order of one forward.  The GEMM kernel is in gemm_bf16.hip, the attention
+// kernels in attn_bf16.hip (both are built with their own compiler flags).
 #include <math.h>
 #include <stdlib.h>
 
 #include "bf16_common.h"
 
 using namespace fsv_bf16;
-
-
 
 namespace {
 
