@@ -31,9 +31,10 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 constexpr int KC = 8;     // 16-wide k blocks per chunk (128 contraction elements)
 constexpr int NST = 3;    // LDS stages of the activation ring
 constexpr int GRAN = 2;   // chunks per 256-element granule of the K cut
+constexpr int NLD = 1;    // loader waves per block (a second one did not help: the issue rate is not what limits the fill)
 
 template <int MT, int EPI, int D>
-__global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
+__global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
                                               void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
                                               int S, int nchunks, int KBo, int NBv, int MB) {
   extern __shared__ uint4 lds[];
@@ -63,12 +64,16 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
   // K range of the split: a balanced cut of the `nchunks` granules into S parts, counted in chunks
   const int cb0 = (split * nchunks / S) * GRAN, per = ((split + 1) * nchunks / S) * GRAN - cb0;
 
-  if (w == 4) {
-    // ---- loader wave: activation chunk `it` -> LDS stage it % NST, one 1 KiB row of units per instruction ----
+  if (w >= 4) {
+    // ---- loader waves: activation chunk `it` -> LDS stage it % NST, one 1 KiB row of units per instruction; loader
+    // wave l takes the rows i with i % NLD == l ----
+    constexpr int PERW = (MT * KC + NLD - 1) / NLD;  // instructions per loader wave and chunk
+    const int lw = w - 4;
     auto fill = [&](int it) {
       uint4 *dst = lds + (it % NST) * CHU;
 #pragma unroll
-      for (int i = 0; i < MT * KC; ++i) {
+      for (int j = 0; j < PERW; ++j) {
+        const int i = min(j * NLD + lw, MT * KC - 1);  // (a repeated last row when the split is uneven)
         const int mt = min(i / KC, mlast);
         const uint4 *src = Ap + ((size_t)(mt0 + mt) * KB + (size_t)(cb0 + it) * KC + i % KC) * 64 + lane;
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
     fill(0);
     if (per > 1) {
       fill(1);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MT * KC) : "memory");  // chunk 0 has landed, chunk 1 may be in flight
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PERW) : "memory");  // chunk 0 has landed, chunk 1 may be in flight
     } else {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     }
@@ -87,7 +92,7 @@ __global__ __launch_bounds__(320) void k_gemm(const void *__restrict__ Wp, uint3
       // stage (it + 2) % NST was read during step it - 1, which every compute wave left at the last barrier
       if (it + 2 < per) {
         fill(it + 2);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MT * KC) : "memory");  // chunk it + 1 has landed
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PERW) : "memory");  // chunk it + 1 has landed
       } else {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
       }
@@ -230,7 +235,7 @@ int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, co
   }
   // the profiling events ride on the dispatch itself: they time the kernel, not the gaps around it
   fsv_prof_scope ps(c, st, cls, (double)N * KB * 32.0, true);
-  hipExtLaunchKernelGGL((k_gemm<MT, EPI, D>), grid, dim3(320), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
+  hipExtLaunchKernelGGL((k_gemm<MT, EPI, D>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
                         (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks);
   return FSV_OK;
 }
