@@ -31,7 +31,7 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 constexpr int KC = 8;     // 16-wide k blocks per chunk (128 contraction elements)
 constexpr int NST = 3;    // LDS stages of the activation ring
 constexpr int GRAN = 2;   // chunks per 256-element granule of the K cut
-constexpr int NLD = 1;    // loader waves per block (a second one did not help: the issue rate is not what limits the fill)
+constexpr int NLD = 2;    // loader waves per block: two halve the time of the first fills, which matters for the short split-K blocks
 
 template <int MT, int EPI, int D>
 __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
