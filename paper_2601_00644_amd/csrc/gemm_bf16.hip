@@ -3,10 +3,10 @@
 // Built with -mllvm -amdgpu-mfma-vgpr-form (accumulators in architectural registers, the weight chunks in
 // flight in accumulation registers).
 //
-// A block is four compute waves and one loader wave.  Compute wave w owns 32 output features (one weight
+// A block is four compute waves and NLD loader waves.  Compute wave w owns 32 output features (one weight
 // tile row) for up to MT*32 batch rows over the block's K range and streams that strip of the re-tiled
-// matrix straight from HBM into MFMA operand registers, D chunks of 128 k (D = 1) ahead of its use.  The loader wave
-// copies the activation chunks of the same K range from global memory (L2) directly into a three-stage LDS
+// matrix straight from HBM into MFMA operand registers, D chunks of 128 k (D = 1) ahead of its use.  The loader waves
+// copy the activation chunks of the same K range from global memory (L2) directly into a three-stage LDS
 // ring, two chunks ahead; the compute waves read their B operands from the ring.  Because the activation
 // loads are issued by a wave of their own, the compute waves' load counter tracks the weight stream only
 // and a wait for the oldest chunk never drains the younger ones.  One barrier per chunk hands a filled
