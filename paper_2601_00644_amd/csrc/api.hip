@@ -86,7 +86,7 @@ const char *fsv_kernel_class_name(int32_t k) { return (k >= 0 && k < FSV_K_COUNT
 void fsv_destroy(fsv_ctx *c) {
   if (!c) return;
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
-  void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->row_req, c->row_idx, c->row_pos, c->row_tok,
+  void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->x, c->logits,
                   c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map};
   for (void *p : ptrs)

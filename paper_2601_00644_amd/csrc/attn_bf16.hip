@@ -293,34 +293,54 @@ __global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int ro
   const int rr = blockIdx.z * RPB + tid / TPR, e0 = (tid % TPR) * 8;
   if (rr >= R) return;
   const size_t base = ((size_t)p0 * Hkv + kvh) * rows_cap + rr, pstr = (size_t)Hkv * rows_cap;
-  // Parts are taken eight at a time with all loads issued before the first use: one part per iteration would put
-  // a full memory round trip into every step of this short loop.  The sums still run in part order.
-  constexpr int U = 8;
-  float mm = -INFINITY;
-  for (int s0 = 0; s0 < nparts; s0 += U) {
-    float mv[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) mv[u] = part_ml[(base + min(s0 + u, nparts - 1) * pstr) * 2];
-#pragma unroll
-    for (int u = 0; u < U; ++u) mm = fmaxf(mm, mv[u]);
-  }
-  float acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ll = 0.f;
-  for (int s0 = 0; s0 < nparts; s0 += U) {
-    float2 ml[U];
-    float4 a[U], c[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const size_t prow = base + min(s0 + u, nparts - 1) * pstr;
-      ml[u] = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
-      a[u] = *reinterpret_cast<const float4 *>(part_o + prow * HD + e0);
-      c[u] = *reinterpret_cast<const float4 *>(part_o + prow * HD + e0 + 4);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
+  // All loads of a batch of parts are issued before the first use: one part per iteration would put a full memory
+  // round trip into every step of this short loop.  Up to sixteen parts (the usual case) are merged from one batch,
+  // maxima and values fetched together; more take a pass for the maximum and a pass for the sums, eight at a time.
+  // The sums always run in part order.
+  float mm = -INFINITY, acc[8] = {0, 0, 0, 0, 0, 0, 0, 0}, ll = 0.f;
+  auto merge = [&](int s0, int n, const float2 *ml, const float4 *a, const float4 *c) {
+    for (int u = 0; u < n; ++u) {
       const float f = (s0 + u >= nparts || ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[u].x - mm);
       ll += ml[u].y * f;
       acc[0] += a[u].x * f; acc[1] += a[u].y * f; acc[2] += a[u].z * f; acc[3] += a[u].w * f;
       acc[4] += c[u].x * f; acc[5] += c[u].y * f; acc[6] += c[u].z * f; acc[7] += c[u].w * f;
+    }
+  };
+  auto fetch = [&](int s0, int u, float2 &ml, float4 &a, float4 &c) {
+    const size_t prow = base + min(s0 + u, nparts - 1) * pstr;
+    ml = *reinterpret_cast<const float2 *>(part_ml + prow * 2);
+    a = *reinterpret_cast<const float4 *>(part_o + prow * HD + e0);
+    c = *reinterpret_cast<const float4 *>(part_o + prow * HD + e0 + 4);
+  };
+  if (nparts <= 16) {
+    float2 ml[16];
+    float4 a[16], c[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) fetch(0, u, ml[u], a[u], c[u]);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) mm = fmaxf(mm, ml[u].x);  // entries beyond nparts repeat the last part
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+      const float f = (u >= nparts || ml[u].x == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(ml[u].x - mm);
+      ll += ml[u].y * f;
+      acc[0] += a[u].x * f; acc[1] += a[u].y * f; acc[2] += a[u].z * f; acc[3] += a[u].w * f;
+      acc[4] += c[u].x * f; acc[5] += c[u].y * f; acc[6] += c[u].z * f; acc[7] += c[u].w * f;
+    }
+  } else {
+    constexpr int U = 8;
+    for (int s0 = 0; s0 < nparts; s0 += U) {
+      float mv[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) mv[u] = part_ml[(base + min(s0 + u, nparts - 1) * pstr) * 2];
+#pragma unroll
+      for (int u = 0; u < U; ++u) mm = fmaxf(mm, mv[u]);
+    }
+    for (int s0 = 0; s0 < nparts; s0 += U) {
+      float2 ml[U];
+      float4 a[U], c[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) fetch(s0, u, ml[u], a[u], c[u]);
+      merge(s0, U, ml, a, c);
     }
   }
   const float inv = 1.0f / ll;

@@ -46,7 +46,8 @@ struct fsv_ctx {
   // weights (library-owned)
   void *embed = nullptr, *final_norm = nullptr, *lm_head = nullptr;
   std::vector<fsv_layer_w> layers;
-  float *inv_freq = nullptr;        // [head_dim/2] rotary frequencies (bf16 path)
+  float *inv_freq = nullptr;        // [head_dim/2] rotary frequencies (bf16 path; fp64 values)
+  float *rope_tab = nullptr;        // [max_rows][head_dim/2][2] cos, sin of the rows of the current call
 
   // row map, built per call on the device
   int32_t *row_req = nullptr, *row_idx = nullptr, *row_pos = nullptr, *row_tok = nullptr;

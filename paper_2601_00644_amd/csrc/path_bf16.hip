@@ -193,7 +193,18 @@ __global__ void k_kv_copy(int Hkv, int hd, int num_pages, const int32_t *__restr
 // ---------------------------------------------------------------------------------------------
 // rotary embedding + KV append; consumes the split partials of the QKV projection
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, const double *__restrict__ inv_freq,
+// cos / sin of every row's rotation angles, once per call (the angles depend on the row's position only, not on the
+// layer): tab[(row * hd/2 + i) * 2 + {0, 1}].  The angle is formed and reduced in fp64.
+__global__ void k_rope_table(int M, int half, const double *__restrict__ inv_freq, const int32_t *__restrict__ row_pos,
+                             float *__restrict__ tab) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= M * half) return;
+  double sn, cs;
+  sincos((double)row_pos[t / half] * inv_freq[t % half], &sn, &cs);
+  reinterpret_cast<float2 *>(tab)[t] = make_float2((float)cs, (float)sn);
+}
+
+__global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, const float *__restrict__ rope_tab,
                                                      const float *__restrict__ part, int S, int Mpad,
                                                      const int32_t *__restrict__ row_req,
                                                      const int32_t *__restrict__ row_idx,
@@ -207,10 +218,9 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
   const int h0 = blockIdx.y * 8, h1 = min(h0 + 8, heads);
   const int b = row_req[r], i_row = row_idx[r], pos = row_pos[r];
   if (threadIdx.x < half) {
-    double sn, cs;
-    sincos((double)pos * inv_freq[threadIdx.x], &sn, &cs);
-    s_cos[threadIdx.x] = (float)cs;
-    s_sin[threadIdx.x] = (float)sn;
+    const float2 cs = reinterpret_cast<const float2 *>(rope_tab)[(size_t)r * half + threadIdx.x];
+    s_cos[threadIdx.x] = cs.x;
+    s_sin[threadIdx.x] = cs.y;
   }
   __syncthreads();
   const int page = min(max(page_table[(size_t)b * max_pages + (pos >> 4)], 0), num_pages - 1), t = pos & 15;
@@ -351,6 +361,7 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
     FSV_HIP(c, hipMalloc((void **)&c->inv_freq, sizeof(double) * f.size()));
     FSV_HIP(c, hipMemcpy(c->inv_freq, f.data(), sizeof(double) * f.size(), hipMemcpyHostToDevice));
   }
+  FSV_HIP(c, hipMalloc((void **)&c->rope_tab, sizeof(float) * (size_t)c->max_rows * d.head_dim));
   const int MtMax = fsv_ceil_div(c->max_rows, 32);
   const size_t rows_pad = (size_t)MtMax * 32;
   auto zalloc = [&](void **p, size_t bytes) -> int {
@@ -390,6 +401,11 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
   fsv_attn_plan pl;
   if ((rc = fsv_bf16_attn_plan(c, b, &pl, s))) return rc;
   {
+    const int n = M * (d.head_dim / 2);
+    hipLaunchKernelGGL(k_rope_table, dim3(fsv_ceil_div(n, 256)), dim3(256), 0, s, M, d.head_dim / 2,
+                       (const double *)c->inv_freq, c->row_pos, (float *)c->rope_tab);
+  }
+  {
     fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
     hipLaunchKernelGGL(k_resid_norm<1>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
                        (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
@@ -402,7 +418,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
     {
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
       hipLaunchKernelGGL(k_rope_append, dim3(M, fsv_ceil_div(d.n_heads + 2 * d.n_kv_heads, 8)), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim,
-                         (const double *)c->inv_freq, part, spq, Mpad, c->row_req, c->row_idx, c->row_pos, b->page_table,
+                         (const float *)c->rope_tab, part, spq, Mpad, c->row_req, c->row_idx, c->row_pos, b->page_table,
                          d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, (uint16_t *)b->k_pool,
                          (uint16_t *)b->v_pool);
     }
