@@ -4,7 +4,9 @@
 One step = one fsv_verify() call on the 8B-shape, batch-16 workload (ragged gamma 1..8, contexts
 512..4096, paged KV, temperature 0.8): target forward over every request's pending token and
 drafts, acceptance tests, correction / bonus token, rollback.  All inputs are resident in HBM
-before the timed region.  Prints ONE JSON line (see README for the fields).
+before the timed region.  Prints ONE JSON line: metric / value / ms_per_step, a `roofline` object for the dominant
+kernel (gate|up GEMM: algorithmic bytes over its measured duration against the 8 TB/s HBM peak, plus counter-measured
+traffic) and a `cpu_baseline` object (the oracle timed on one request of the same workload).
 """
 from __future__ import annotations
 
@@ -170,8 +172,8 @@ def main():
                     help="also run three plain 1 GiB device copies, the known-size reference the HBM counters are scaled by")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build runs on ONE GPU (requests are independent; see DESIGN.md for how the step "
-              "would shard); rerun with --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on ONE GPU (requests are independent, so a multi-GPU deployment shards by "
+              "request and needs no exchange); rerun with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
     import torch
