@@ -217,6 +217,50 @@ int fsv_profile_enable(fsv_ctx *ctx, uint32_t class_mask);
 int fsv_profile_read(fsv_ctx *ctx, fsv_kernel_time *out, int32_t cap);
 const char *fsv_kernel_class_name(int32_t kernel_class);
 
+/*
+ * State around the verification step (host only; no device memory, no stream).
+ *
+ * Stride selection (Sec. IV-B, refined latency model and throughput objective; Alg. 2 step 1): with
+ *   T_fixed    = t_prop + t_base + t_down + header_bits / rate + beta
+ *   T_marginal = alpha_edge + bits_per_token / rate + delta_cloud                  (times in seconds, rate in bit/s)
+ * fsv_policy_stride returns K* = argmax over K in 1..k_max of E[tokens | K] / (T_fixed + K T_marginal), ties to the
+ * smallest K, where E[tokens | K] = 1 + gamma_hat K (FSV_TAU_LINEAR, the numerator Alg. 2 prints) or
+ * 1 + gamma_hat + ... + gamma_hat^K (FSV_TAU_GEOMETRIC, the geometric decay model Sec. IV-B names).  The linear
+ * numerator makes the objective monotone in K, so its optimum is always 1 or k_max.  *objective_out (may be NULL)
+ * receives the objective at K* in tokens per second.  Returns K* >= 1, or a negative fsv_status on a bad argument.
+ *
+ * fsv_policy_ema is the acceptance-rate average of Alg. 2 step 3: (1 - mu) gamma_hat + mu tau / k (started at 0.8
+ * by the algorithm); k <= 0 leaves gamma_hat unchanged.
+ */
+typedef struct {
+  double alpha_edge, beta;             /* edge drafting time: alpha_edge K + beta                        */
+  double bits_per_token, header_bits;  /* uplink payload: K b + O_header bits                             */
+  double t_prop, t_base, delta_cloud, t_down; /* propagation, cloud base cost, cloud cost per token, downlink */
+} fsv_latency_model;
+enum { FSV_TAU_LINEAR = 0, FSV_TAU_GEOMETRIC = 1 };
+int fsv_policy_stride(const fsv_latency_model *model, double rate, double gamma_hat, int32_t k_max, int32_t tau_model,
+                      double *objective_out);
+double fsv_policy_ema(double gamma_hat, int32_t tau, int32_t k, double mu);
+
+/*
+ * Page bookkeeping of the persistent per-user KV sessions (Sec. IV-C): which physical pages of the pools a session
+ * owns.  HOST only; the caller uploads the page-table rows it passes to fsv_verify.  Not thread safe.
+ *   fsv_pager_reserve: make session own ceil(n_positions / 16) pages (it keeps what it has, takes the lowest free
+ *     ids for the rest) and write its pages, in logical order, to page_table_row (HOST, at least that many entries;
+ *     may be NULL).  FSV_E_CAPACITY when the pool or max_pages_per_session cannot cover it: nothing is taken then.
+ *     Call it with seq_len + gamma + 1 before a verification call.
+ *   fsv_pager_trim: give back the tail pages beyond ceil(n_positions / 16) (the rollback of rejected positions: pass
+ *     new_seq_lens[b]); returns the number of pages released, which equals pages_released[b] of that call.
+ *     n_positions = 0 ends the session.
+ */
+typedef struct fsv_pager fsv_pager;
+int fsv_pager_create(int32_t num_pages, int32_t max_sessions, int32_t max_pages_per_session, fsv_pager **out);
+void fsv_pager_destroy(fsv_pager *pager);
+int fsv_pager_reserve(fsv_pager *pager, int32_t session, int32_t n_positions, int32_t *page_table_row);
+int fsv_pager_trim(fsv_pager *pager, int32_t session, int32_t n_positions);
+int32_t fsv_pager_free_pages(const fsv_pager *pager);
+int32_t fsv_pager_session_pages(const fsv_pager *pager, int32_t session);
+
 const char *fsv_strerror(int status);
 /* Last failure's detail message for this context (HOST string owned by the context). */
 const char *fsv_last_error(const fsv_ctx *ctx);

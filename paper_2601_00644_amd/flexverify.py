@@ -21,7 +21,8 @@ W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
 EXPORTS = ["fsv_create", "fsv_destroy", "fsv_verify", "fsv_sample", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
            "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
-           "fsv_strerror", "fsv_last_error"]
+           "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_pager_create",
+           "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
 
 
 class ModelDesc(C.Structure):
@@ -50,6 +51,14 @@ class KernelTime(C.Structure):
     _fields_ = [("kernel_class", C.c_int32), ("launches", C.c_int32), ("total_ms", C.c_double), ("bytes", C.c_double)]
 
 
+class LatencyModel(C.Structure):
+    _fields_ = [(n, C.c_double) for n in ("alpha_edge", "beta", "bits_per_token", "header_bits", "t_prop", "t_base",
+                                          "delta_cloud", "t_down")]
+
+
+TAU_LINEAR, TAU_GEOMETRIC = 0, 1
+
+
 class FsvError(RuntimeError):
     def __init__(self, status, what, detail=""):
         super().__init__(f"{what}: {status} ({detail})")
@@ -75,6 +84,17 @@ def lib():
         _lib.fsv_kernel_class_name.restype = C.c_char_p
         _lib.fsv_destroy.argtypes = [C.c_void_p]
         _lib.fsv_destroy.restype = None
+        _lib.fsv_policy_stride.argtypes = [C.POINTER(LatencyModel), C.c_double, C.c_double, C.c_int32, C.c_int32,
+                                           C.POINTER(C.c_double)]
+        _lib.fsv_policy_ema.argtypes = [C.c_double, C.c_int32, C.c_int32, C.c_double]
+        _lib.fsv_policy_ema.restype = C.c_double
+        _lib.fsv_pager_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
+        _lib.fsv_pager_destroy.argtypes = [C.c_void_p]
+        _lib.fsv_pager_destroy.restype = None
+        _lib.fsv_pager_reserve.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p]
+        _lib.fsv_pager_trim.argtypes = [C.c_void_p, C.c_int32, C.c_int32]
+        _lib.fsv_pager_free_pages.argtypes = [C.c_void_p]
+        _lib.fsv_pager_session_pages.argtypes = [C.c_void_p, C.c_int32]
     return _lib
 
 
@@ -263,6 +283,63 @@ class Context:
             self._check(n, "fsv_profile_read")
         return {lib().fsv_kernel_class_name(buf[i].kernel_class).decode():
                 dict(launches=buf[i].launches, total_ms=buf[i].total_ms, bytes=buf[i].bytes) for i in range(n)}
+
+
+def policy_stride(model: LatencyModel, rate: float, gamma_hat: float, k_max: int, tau_model: int = TAU_GEOMETRIC):
+    """(K*, objective) of fsv_policy_stride."""
+    obj = C.c_double(0.0)
+    k = lib().fsv_policy_stride(C.byref(model), float(rate), float(gamma_hat), int(k_max), int(tau_model), C.byref(obj))
+    if k < 1:
+        raise FsvError(k, "fsv_policy_stride", lib().fsv_strerror(k).decode())
+    return k, obj.value
+
+
+def policy_ema(gamma_hat: float, tau: int, k: int, mu: float) -> float:
+    return lib().fsv_policy_ema(float(gamma_hat), int(tau), int(k), float(mu))
+
+
+class Pager:
+    """Owns one fsv_pager; page-table rows are numpy int32 arrays the caller uploads."""
+
+    def __init__(self, num_pages: int, max_sessions: int, max_pages_per_session: int):
+        self._h = C.c_void_p(0)
+        self.max_pages_per_session = max_pages_per_session
+        rc = lib().fsv_pager_create(num_pages, max_sessions, max_pages_per_session, C.byref(self._h))
+        if rc != 0:
+            raise FsvError(rc, "fsv_pager_create", lib().fsv_strerror(rc).decode())
+
+    def reserve(self, session: int, n_positions: int, row: np.ndarray | None = None) -> None:
+        ptr = None
+        if row is not None:
+            assert row.dtype == np.int32 and row.flags.c_contiguous and row.shape[0] >= self.max_pages_per_session
+            ptr = row.ctypes.data
+        rc = lib().fsv_pager_reserve(self._h, int(session), int(n_positions), ptr)
+        if rc != 0:
+            raise FsvError(rc, "fsv_pager_reserve", lib().fsv_strerror(rc).decode())
+
+    def trim(self, session: int, n_positions: int) -> int:
+        rc = lib().fsv_pager_trim(self._h, int(session), int(n_positions))
+        if rc < 0:
+            raise FsvError(rc, "fsv_pager_trim", lib().fsv_strerror(rc).decode())
+        return rc
+
+    @property
+    def free_pages(self) -> int:
+        return lib().fsv_pager_free_pages(self._h)
+
+    def session_pages(self, session: int) -> int:
+        return lib().fsv_pager_session_pages(self._h, int(session))
+
+    def close(self):
+        if self._h:
+            lib().fsv_pager_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
 
 
 def pool_shape(cfg, num_pages: int):
