@@ -157,6 +157,63 @@ def gemm_sweep(args, torch, fv, synth):
                       "config": {"workload": "gemm_sweep"}, "dtype": "bf16", "data": "synthetic", "sweep": table}), flush=True)
 
 
+def serve_loop(args, torch, fv, synth):
+    """Alg. 2 in a loop at the 8B shapes: 16 persistent sessions, the stride of every session picked each round from a
+    lognormal link-rate trace and its acceptance average, drafts from the synthetic edge model, fsv_verify, state update.
+    The cloud term of the latency model is FITTED from measured verification times (T_cloud = T_base + K delta_cloud,
+    Sec. IV-B); the report is the effective token generation rate (Sec. III) under that model."""
+    from paper_2601_00644_amd import serve
+    cfg = synth.MODELS["llama8b"]
+    S, kmax, rounds, seed = 16, 8, args.steps, args.seed
+    log("workload serve_8b: weights")
+    weights = synth.make_weights(cfg, seed, device="cuda")
+    lm = fv.LatencyModel(alpha_edge=0.012, beta=0.002, bits_per_token=17.0, header_bits=320.0, t_prop=0.020, t_base=0.006,
+                         delta_cloud=0.0, t_down=0.005)
+    req = synth.make_requests(synth.WORKLOADS["c3_8b_b16"], cfg, seed)
+    MP = (4096 + rounds * (kmax + 1) + 15) // 16 + 1
+    srv = serve.Server(cfg, weights, S, S * MP, kmax, MP, lm, mu=0.1, temperature=0.8, sigma=0.7, seed=seed)
+    for s in range(S):
+        k, v = synth.make_kv_context(cfg, int(req.seq_lens[s]), seed, s, device="cuda")
+        srv.open_session(s, k, v, int(req.last_token[s]))
+        del k, v
+    log("sessions restored; fitting T_cloud(K) from fixed-stride rounds")
+    pts = []
+    for K in (1, 2, 4, 6, 8, 1, 2, 4, 6, 8):
+        saved = srv.model
+        srv.model = fv.LatencyModel(alpha_edge=0.0, beta=0.0, bits_per_token=0.0, header_bits=0.0, t_prop=1.0, t_base=0.0,
+                                    delta_cloud=0.0, t_down=0.0)      # a link on which the longest stride always wins
+        out = srv.round(np.full(S, 1e9), k_max=K)
+        srv.model = saved
+        pts.append((K, out["cloud_ms"] * 1e-3))
+    ks, ts = np.array([p[0] for p in pts[5:]], float), np.array([p[1] for p in pts[5:]], float)   # second sweep: warm
+    delta, base = np.polyfit(ks, ts, 1)
+    lm.t_base, lm.delta_cloud = float(base), float(max(delta, 0.0))
+    log(f"fit: T_cloud(K) = {base * 1e3:.3f} ms + K * {delta * 1e3:.4f} ms  (measured {[round(t * 1e3, 3) for t in ts]} ms at K = {ks.tolist()})")
+    for ss in srv.sessions:
+        ss.emitted, ss.gamma_hat = 0, 0.8
+    hist, t_model, emitted, drafted, accepted, cloud = {}, 0.0, 0, 0, 0, []
+    for rnd in range(rounds):
+        rates = serve.lognormal_rates(S, 2.0e3, 1.5, seed, 10_000 + rnd)
+        out = srv.round(rates, k_max=kmax)
+        cloud.append(out["cloud_ms"])
+        for j, s in enumerate(out["sessions"]):
+            K, tau = int(out["K"][j]), int(out["tau"][j])
+            hist[K] = hist.get(K, 0) + 1
+            t_model += fv.policy_step_time(lm, float(rates[s]), K, out["cloud_ms"] * 1e-3)
+            emitted += tau + 1
+            drafted += K
+            accepted += tau
+    out = {"metric": "effective token generation rate per session under the latency model, cloud term measured",
+           "value": emitted / t_model, "unit": "tokens/s per session", "config": {"workload": "serve_8b", "sessions": S,
+           "rounds": rounds, "k_max": kmax, "rate_median_bps": 2.0e3, "rate_sigma": 1.5},
+           "t_cloud_fit_ms": {"t_base": base * 1e3, "delta_cloud": delta * 1e3},
+           "stride_histogram": {str(k): hist[k] for k in sorted(hist)}, "acceptance": accepted / max(drafted, 1),
+           "mean_cloud_ms": float(np.mean(cloud)), "tokens_per_round": emitted / rounds,
+           "cloud_tokens_per_s_all_sessions": emitted / (sum(cloud) * 1e-3), "dtype": "bf16", "data": "synthetic"}
+    print(json.dumps(out), flush=True)
+    srv.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -185,6 +242,8 @@ def main():
         return sampler_bench(args, torch, fv, synth)
     if args.workload == "gemm_sweep":
         return gemm_sweep(args, torch, fv, synth)
+    if args.workload == "serve_8b":
+        return serve_loop(args, torch, fv, synth)
     wl = synth.WORKLOADS[args.workload]
     if args.pages:
         from dataclasses import replace

@@ -241,6 +241,10 @@ enum { FSV_TAU_LINEAR = 0, FSV_TAU_GEOMETRIC = 1 };
 int fsv_policy_stride(const fsv_latency_model *model, double rate, double gamma_hat, int32_t k_max, int32_t tau_model,
                       double *objective_out);
 double fsv_policy_ema(double gamma_hat, int32_t tau, int32_t k, double mu);
+/* T_step(K, R) = T_edge + T_up + T_cloud + T_down of the same model (Sec. III, step latency; Sec. IV-B for the terms),
+ * in seconds; cloud_seconds >= 0 replaces the modelled T_cloud = t_base + K delta_cloud by a measured verification
+ * time.  Returns -1 on a bad argument. */
+double fsv_policy_step_time(const fsv_latency_model *model, double rate, int32_t k, double cloud_seconds);
 
 /*
  * Page bookkeeping of the persistent per-user KV sessions (Sec. IV-C): which physical pages of the pools a session

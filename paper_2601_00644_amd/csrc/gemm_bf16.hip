@@ -244,7 +244,10 @@ template <int EPI>
 int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits,
              int KBo, hipStream_t st) {
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = K / 256, KB = K / 16;
-  const int mt_blk = Mt >= 4 ? 4 : Mt, mblocks = fsv_ceil_div(Mt, mt_blk);
+  // row tiles per block: the fewest row blocks of at most four tiles (more do not fit the 256 registers a wave of a
+  // six-wave block may use), the tiles spread evenly over them (five tiles are taken as 3 + 2, not 4 + 1: a block
+  // works on its full tile count whatever the number of real rows)
+  const int mblocks = fsv_ceil_div(Mt, 4), mt_blk = fsv_ceil_div(Mt, mblocks);
   const size_t wbytes = (size_t)NTpad * KB * 1024;
   if (wbytes > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
   if (splits < 1 || splits > nchunks) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad split count %d for %d granules", splits, nchunks);

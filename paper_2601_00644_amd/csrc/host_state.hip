@@ -37,6 +37,12 @@ int fsv_policy_stride(const fsv_latency_model *m, double rate, double gamma_hat,
   return best_k;
 }
 
+double fsv_policy_step_time(const fsv_latency_model *m, double rate, int32_t k, double cloud_seconds) {
+  if (!m || !(rate > 0.0) || k < 0) return -1.0;
+  const double t_cloud = (cloud_seconds >= 0.0) ? cloud_seconds : m->t_base + k * m->delta_cloud;
+  return (m->alpha_edge * k + m->beta) + (m->t_prop + (k * m->bits_per_token + m->header_bits) / rate) + t_cloud + m->t_down;
+}
+
 double fsv_policy_ema(double gamma_hat, int32_t tau, int32_t k, double mu) {
   if (k <= 0) return gamma_hat;
   return (1.0 - mu) * gamma_hat + mu * ((double)tau / (double)k);

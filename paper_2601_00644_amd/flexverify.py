@@ -21,7 +21,7 @@ W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
 EXPORTS = ["fsv_create", "fsv_destroy", "fsv_verify", "fsv_sample", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
            "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
-           "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_pager_create",
+           "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_policy_step_time", "fsv_pager_create",
            "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
 
 
@@ -88,6 +88,8 @@ def lib():
                                            C.POINTER(C.c_double)]
         _lib.fsv_policy_ema.argtypes = [C.c_double, C.c_int32, C.c_int32, C.c_double]
         _lib.fsv_policy_ema.restype = C.c_double
+        _lib.fsv_policy_step_time.argtypes = [C.POINTER(LatencyModel), C.c_double, C.c_int32, C.c_double]
+        _lib.fsv_policy_step_time.restype = C.c_double
         _lib.fsv_pager_create.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_void_p)]
         _lib.fsv_pager_destroy.argtypes = [C.c_void_p]
         _lib.fsv_pager_destroy.restype = None
@@ -296,6 +298,10 @@ def policy_stride(model: LatencyModel, rate: float, gamma_hat: float, k_max: int
 
 def policy_ema(gamma_hat: float, tau: int, k: int, mu: float) -> float:
     return lib().fsv_policy_ema(float(gamma_hat), int(tau), int(k), float(mu))
+
+
+def policy_step_time(model: LatencyModel, rate: float, k: int, cloud_seconds: float = -1.0) -> float:
+    return lib().fsv_policy_step_time(C.byref(model), float(rate), int(k), float(cloud_seconds))
 
 
 class Pager:

@@ -33,6 +33,17 @@ def test_stride_matches_oracle_on_a_seeded_grid():
     assert len(seen) >= 8     # the grid exercises short and long strides
 
 
+def test_step_time_matches_oracle():
+    rng = np.random.default_rng(8)
+    for _ in range(300):
+        mo, ml = _pair(rng)
+        rate, k = 10 ** rng.uniform(2, 9), int(rng.integers(0, 17))
+        assert fv.policy_step_time(ml, rate, k) == pytest.approx(P.t_step(mo, rate, k), rel=1e-13)
+        assert fv.policy_step_time(ml, rate, k, 0.0123) == pytest.approx(
+            P.t_step(mo, rate, k) - (mo.t_base + k * mo.delta_cloud) + 0.0123, rel=1e-12)
+    assert fv.policy_step_time(_pair(rng)[1], 0.0, 3) == -1.0
+
+
 def test_stride_rejects_bad_arguments():
     _, ml = _pair(np.random.default_rng(0))
     for args in ((0.0, 0.8, 8, 1), (1e6, 0.8, 0, 1), (1e6, -0.1, 8, 1), (1e6, 0.8, 8, 7)):
