@@ -19,7 +19,10 @@
  *                   probability min(1, p/q), on rejection resample from the
  *                   normalised positive part of p - q, bonus token from p when
  *                   every draft is accepted), which keeps the output law equal
- *                   to the target model's (Sec. II, Regime B of Sec. V).
+ *                   to the target model's (Sec. II, Regime B of Sec. V).  With
+ *                   top_p < 1 the target law is first cut to its nucleus (Regime B
+ *                   samples with top-p 0.9): the rule then keeps the output law
+ *                   equal to the nucleus-cut target law.
  *   - orc_rollback: the KV rollback of Sec. IV-C (positions from the first
  *                   rejected draft onward are discarded).
  *
@@ -198,6 +201,7 @@ typedef struct {
   int32_t pad_;
   double accept_margin; /* min over tested drafts of |u_i - min(1, p/q)|; +inf if none      */
   double cdf_margin;    /* distance of u_sample from the chosen token's CDF edges (normalised) */
+  double nucleus_margin;/* min over the rows used of the distance of top_p from the cumulative masses at the cut */
 } orc_sample_out;
 
 static void softmax_row(const double *lg, int V, double T, double *p) {
@@ -205,6 +209,37 @@ static void softmax_row(const double *lg, int V, double T, double *p) {
   for (int x = 0; x < V; ++x) if (lg[x] / T > mx) mx = lg[x] / T;
   for (int x = 0; x < V; ++x) { p[x] = exp(lg[x] / T - mx); den += p[x]; }
   for (int x = 0; x < V; ++x) p[x] /= den;
+}
+
+/*
+ * Nucleus (top-p) cut of a probability row: order the tokens by probability, keep the most probable ones up to and
+ * including the one with which the kept mass first reaches top_p, keep every token tied with that last one as well
+ * (so the set does not depend on how ties are ordered), zero the rest and renormalise.  top_p >= 1 keeps the row.
+ * *margin (may be NULL) gets min(top_p - mass strictly above the last kept value, mass at or above it - top_p).
+ */
+typedef struct { double p; int x; } orc_px;
+static int px_desc(const void *a, const void *b) {
+  const orc_px *u = a, *v = b;
+  if (u->p != v->p) return (u->p < v->p) ? 1 : -1;
+  return (u->x > v->x) - (u->x < v->x);
+}
+static int nucleus_row(double *p, int V, double top_p, double *margin) {
+  if (margin) *margin = INFINITY;
+  if (!(top_p < 1.0)) return 0;
+  orc_px *s = malloc(sizeof(orc_px) * V);
+  if (!s) return -1;
+  for (int x = 0; x < V; ++x) { s[x].p = p[x]; s[x].x = x; }
+  qsort(s, V, sizeof(orc_px), px_desc);
+  double cum = 0.0;
+  int k = V - 1;
+  for (int i = 0; i < V; ++i) { cum += s[i].p; if (cum >= top_p) { k = i; break; } }
+  const double cut = s[k].p;
+  double gt = 0.0, ge = 0.0;
+  for (int i = 0; i < V; ++i) { if (s[i].p > cut) gt += s[i].p; if (s[i].p >= cut) ge += s[i].p; }
+  if (margin) { double a = top_p - gt, b = ge - top_p; *margin = (a < b) ? a : b; }
+  for (int x = 0; x < V; ++x) p[x] = (p[x] >= cut) ? p[x] / ge : 0.0;
+  free(s);
+  return 0;
 }
 
 static int argmax_row(const double *lg, int V) { /* lowest index wins ties */
@@ -245,10 +280,12 @@ static int inverse_cdf(const double *mass, int V, double u, double *margin) {
  *   a_out  : optional [gamma], acceptance probabilities of the drafts that were tested.
  * T == 0 is greedy decoding (Alg. 2): accept while draft == argmax, emit argmax.
  */
-int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
-               const float *u_acc, float u_smp, double T, orc_sample_out *out, double *a_out) {
-  if (V <= 0 || gamma < 0 || T < 0.0) return -1;
+int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
+                    const float *u_acc, float u_smp, double T, double top_p, orc_sample_out *out, double *a_out) {
+  if (V <= 0 || gamma < 0 || T < 0.0 || !(top_p > 0.0)) return -1;
   out->tau = 0; out->used_residual = 0; out->accept_margin = INFINITY; out->cdf_margin = INFINITY;
+  out->nucleus_margin = INFINITY;
+  double nm;
   if (T == 0.0) {
     int tau = 0;
     while (tau < gamma && draft[tau] == argmax_row(logits + (size_t)tau * V, V)) ++tau;
@@ -263,6 +300,8 @@ int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, con
     int dtok = draft[i - 1];
     if (dtok < 0 || dtok >= V) { free(p); free(r); return -1; }
     softmax_row(logits + (size_t)(i - 1) * V, V, T, p);
+    if (nucleus_row(p, V, top_p, &nm)) { free(p); free(r); return -1; }
+    if (nm < out->nucleus_margin) out->nucleus_margin = nm;
     double qd = (double)q[(size_t)(i - 1) * V + dtok];
     double ratio = p[dtok] / qd;              /* qd == 0 gives +inf (or NaN for 0/0) */
     double a = (ratio >= 1.0) ? 1.0 : ratio;
@@ -274,6 +313,8 @@ int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, con
   }
   out->tau = tau;
   softmax_row(logits + (size_t)tau * V, V, T, p);
+  if (nucleus_row(p, V, top_p, &nm)) { free(p); free(r); return -1; }
+  if (nm < out->nucleus_margin) out->nucleus_margin = nm;
   if (tau < gamma) {
     double Z = 0.0;
     for (int x = 0; x < V; ++x) {
@@ -291,6 +332,11 @@ int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, con
   out->next_token = inverse_cdf(p, V, (double)u_smp, &out->cdf_margin);
   free(p); free(r);
   return 0;
+}
+
+int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
+               const float *u_acc, float u_smp, double T, orc_sample_out *out, double *a_out) {
+  return orc_sample_warp(logits, V, gamma, draft, q, u_acc, u_smp, T, 1.0, out, a_out);
 }
 
 /*

@@ -40,7 +40,7 @@ class _Weights(C.Structure):
 
 class _SampleOut(C.Structure):
     _fields_ = [("tau", C.c_int32), ("next_token", C.c_int32), ("used_residual", C.c_int32), ("pad_", C.c_int32),
-                ("accept_margin", C.c_double), ("cdf_margin", C.c_double)]
+                ("accept_margin", C.c_double), ("cdf_margin", C.c_double), ("nucleus_margin", C.c_double)]
 
 
 _lib = None
@@ -52,6 +52,7 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_forward.restype = C.c_int
         _lib.orc_sample.restype = C.c_int
+        _lib.orc_sample_warp.restype = C.c_int
         _lib.orc_rollback.restype = C.c_int
         _lib.orc_linear.restype = None
         _lib.orc_attention.restype = None
@@ -66,6 +67,7 @@ class SampleResult:
     accept_margin: float
     cdf_margin: float
     accept_prob: np.ndarray
+    nucleus_margin: float = float("inf")
 
 
 def _model_struct(cfg) -> _Model:
@@ -150,8 +152,10 @@ def attention(q, kl, vl, L: int):
     return out
 
 
-def sample(logits, draft, q, u_acc, u_smp: float, T: float) -> SampleResult:
-    """Acceptance loop + correction/bonus token for one request (Alg. 2 step 2; speculative sampling for T>0)."""
+def sample(logits, draft, q, u_acc, u_smp: float, T: float, top_p: float = 1.0) -> SampleResult:
+    """Acceptance loop + correction/bonus token for one request (Alg. 2 step 2; speculative sampling for T>0).
+
+    top_p < 1 cuts the target law of every row to its nucleus first (Regime B of Sec. V samples with top-p)."""
     logits = np.ascontiguousarray(logits, np.float64)
     gamma = int(len(draft))
     V = int(logits.shape[1])
@@ -166,12 +170,13 @@ def sample(logits, draft, q, u_acc, u_smp: float, T: float) -> SampleResult:
         qp = C.c_void_p(0)
     out = _SampleOut()
     a = np.full(gamma, np.nan, np.float64)
-    rc = lib().orc_sample(C.c_void_p(logits.ctypes.data), C.c_int(V), C.c_int(gamma), C.c_void_p(draft.ctypes.data),
-                          qp, C.c_void_p(u_acc.ctypes.data), C.c_float(float(u_smp)), C.c_double(float(T)),
-                          C.byref(out), C.c_void_p(a.ctypes.data))
+    rc = lib().orc_sample_warp(C.c_void_p(logits.ctypes.data), C.c_int(V), C.c_int(gamma), C.c_void_p(draft.ctypes.data),
+                               qp, C.c_void_p(u_acc.ctypes.data), C.c_float(float(u_smp)), C.c_double(float(T)),
+                               C.c_double(float(top_p)), C.byref(out), C.c_void_p(a.ctypes.data))
     if rc != 0:
-        raise ValueError("orc_sample rejected its arguments")
-    return SampleResult(out.tau, out.next_token, bool(out.used_residual), out.accept_margin, out.cdf_margin, a)
+        raise ValueError("orc_sample_warp rejected its arguments")
+    return SampleResult(out.tau, out.next_token, bool(out.used_residual), out.accept_margin, out.cdf_margin, a,
+                        out.nucleus_margin)
 
 
 def rollback(L: int, gamma: int, tau: int, page_size: int):

@@ -230,3 +230,112 @@ def test_accept_test_is_strict():
     assert oracle.sample(logits, [0], q, [0.5 - 2.0 ** -24], 0.1, 1.0).tau == 1
     # rejected: residual is max(0, p - q) = (0, 1/2) -> token 1 for every u_sample
     assert oracle.sample(logits, [0], q, [0.5], 0.0, 1.0).next_token == 1
+
+
+# ---- nucleus (top-p) cut of the target law -------------------------------------------------------------
+
+def _nucleus_cases():
+    path = os.path.join(HERE, "golden", "nucleus_worked_cases.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, p, tp, kept, pp = [f.strip() for f in line.split("|")]
+        yield name, np.array([float(x) for x in p.split(",")]), float(tp), [int(x) for x in kept.split(",")], \
+            np.array([float(x) for x in pp.split(",")])
+
+
+def _bonus_law_through_the_sampler(p, top_p, N=4000):
+    """The law of the emitted token for a request without drafts, read off the oracle on a fine uniform grid."""
+    V = len(p)
+    lg = np.log(p)[None, :]
+    counts = np.zeros(V)
+    for k in range(N):
+        s = oracle.sample(lg, np.zeros(0, np.int32), None, np.zeros(0, np.float32), (k + 0.5) / N, 1.0, top_p=top_p)
+        counts[s.next_token] += 1
+    return counts / N
+
+
+@pytest.mark.parametrize("case", list(_nucleus_cases()), ids=lambda c: c[0])
+def test_nucleus_hand_worked_cases(case):
+    name, p, top_p, kept, want = case
+    law = _bonus_law_through_the_sampler(p, top_p)
+    assert sorted(np.nonzero(law)[0].tolist()) == kept
+    assert np.abs(law - want).max() < 1.0 / 4000 + 1e-12
+
+
+def test_nucleus_margin_reports_the_distance_to_the_cut():
+    p = np.array([0.5, 0.3, 0.15, 0.05])
+    s = oracle.sample(np.log(p)[None, :], np.zeros(0, np.int32), None, np.zeros(0, np.float32), 0.3, 1.0, top_p=0.9)
+    assert s.nucleus_margin == pytest.approx(0.05, abs=1e-12)      # min(0.9 - 0.8, 0.95 - 0.9)
+    s = oracle.sample(np.log(p)[None, :], np.zeros(0, np.int32), None, np.zeros(0, np.float32), 0.3, 1.0, top_p=1.0)
+    assert s.nucleus_margin == float("inf")
+
+
+@pytest.mark.parametrize("V,gamma,N,top_p", [(5, 1, 400, 0.8), (4, 2, 128, 0.7), (6, 0, 4000, 0.6)])
+def test_output_law_equals_nucleus_cut_target_bruteforce(V, gamma, N, top_p):
+    """Speculative sampling on the cut law: every emitted token, given the ones before it, follows the target law
+    cut to its nucleus, whatever the draft law is (brute force over all drafts and a grid of uniforms)."""
+    p, q = _random_tables(V, gamma, seed=100 * V + gamma, peaky=1.0)
+    logits = np.log(p)
+    hist = np.zeros(_level_offset(V, gamma + 2), np.float64)
+    drv = _driver()
+    drv.brute_force_warp.restype = C.c_int
+    rc = drv.brute_force_warp(C.c_int(V), C.c_int(gamma), C.c_int(N), C.c_double(1.0), C.c_double(top_p),
+                              C.c_void_p(logits.ctypes.data), C.c_void_p(q.ctypes.data), C.c_void_p(hist.ctypes.data))
+    assert rc == 0
+
+    def cut(row):   # the definition, written with numpy: sort, cumulate, keep ties of the last kept value
+        order = np.argsort(-row, kind="stable")
+        k = int(np.searchsorted(np.cumsum(row[order]), top_p, side="left"))
+        thr = row[order[min(k, V - 1)]]
+        out = np.where(row >= thr, row, 0.0)
+        return out / out.sum()
+
+    tol = 0.5 * (gamma + 1) / N
+    first = np.zeros(V)
+    for b in range(V):     # law of the first emitted token
+        first[b] = hist[1 + b]
+        for m in range(2, gamma + 2):
+            ext = V ** (m - 1)
+            first[b] += hist[_level_offset(V, m) + b * ext: _level_offset(V, m) + (b + 1) * ext].sum()
+    want = cut(p[0])
+    assert np.abs(first - want).max() < 2 * tol + 1e-9, (first, want)
+    assert (first[want == 0] == 0).all()          # nothing outside the nucleus is ever emitted
+    if gamma >= 1:         # second token given an accepted-or-corrected first token b
+        for b in range(V):
+            if first[b] < 16 * tol:
+                continue
+            joint = np.zeros(V)
+            for c in range(V):
+                joint[c] = hist[_level_offset(V, 2) + b * V + c]
+                for m in range(3, gamma + 2):
+                    ext = V ** (m - 2)
+                    base = _level_offset(V, m) + (b * V + c) * ext
+                    joint[c] += hist[base: base + ext].sum()
+            # sequences that stop after the first token (a rejection at draft 1) carry no second token: condition
+            # on those that continue
+            if joint.sum() < 16 * tol * float(q[0][b]):
+                continue
+            cond = joint / joint.sum()
+            want2 = cut(p[1 + b])
+            assert np.abs(cond - want2).max() < 4 * tol / joint.sum() + 1e-9, (b, cond, want2)
+
+
+def test_accepts_everything_when_draft_equals_the_cut_target():
+    rng = np.random.default_rng(3)
+    V, gamma, top_p = 50, 4, 0.85
+    p = rng.dirichlet(np.full(V, 0.5), size=gamma + 1)
+    lg = np.log(p)
+
+    def cut(row):
+        order = np.argsort(-row, kind="stable")
+        k = int(np.searchsorted(np.cumsum(row[order]), top_p, side="left"))
+        out = np.where(row >= row[order[min(k, V - 1)]], row, 0.0)
+        return out / out.sum()
+
+    q = np.stack([cut(p[i]) for i in range(gamma)]).astype(np.float32)
+    for trial in range(50):
+        d = np.array([rng.choice(V, p=q[i].astype(np.float64) / q[i].astype(np.float64).sum()) for i in range(gamma)], np.int32)
+        u = rng.random(gamma).astype(np.float32) * 0.999
+        s = oracle.sample(lg, d, q, u, 0.5, 1.0, top_p=top_p)
+        assert s.tau == gamma      # fp32 storage of q can only make q slightly smaller or larger than p'; u < 0.999
