@@ -115,6 +115,12 @@ typedef struct {
   const int32_t *page_table;         /* DEVICE [B][max_pages_per_req] physical page of each logical
                                         page; must cover positions < seq_lens[b] + gamma_b + 1        */
   void *k_pool, *v_pool;             /* DEVICE, read and written                                      */
+  const float *top_p;                /* DEVICE [B]   nucleus mass in (0,1] (1 = no cut), or NULL: the target law
+                                                     of every row is cut to its nucleus before the acceptance test
+                                                     (Regime B of Sec. V samples with top-p): the most probable
+                                                     tokens whose mass first reaches top_p, with every token tied
+                                                     with the last one kept; ignored where T_b = 0                */
+  const float *top_p_host;           /* HOST   [B]   same values (NULL with top_p NULL)                           */
 } fsv_batch;
 
 typedef struct {
@@ -124,7 +130,9 @@ typedef struct {
   int32_t *pages_released; /* DEVICE [B] tail pages that hold no valid position any more              */
   uint32_t *flags;         /* DEVICE [B] bit0: some tested draft had |u - min(1,p/q)| < 1e-4;
                                          bit1: the emitted token's CDF edge is within 1e-6 of u_sample;
-                                         bit2: the token was drawn from the residual max(0, p - q)    */
+                                         bit2: the token was drawn from the residual max(0, p - q);
+                                         bit3: on a row the outcome rests on, the nucleus cut lies within 1e-6
+                                               (of the row's mass) of top_p                                   */
   float *logits_out;       /* DEVICE [M][vocab] fp32 target logits, or NULL                           */
 } fsv_result;
 

@@ -47,6 +47,12 @@ int check_batch(fsv_ctx *c, const fsv_batch *b, bool need_kv, bool need_sampling
     }
     if (any_pos && G > 0 && (!b->draft_probs || !b->u_accept))
       FSV_FAIL(c, FSV_E_INVALID_ARG, "draft_probs and u_accept required when a temperature is positive");
+    if ((b->top_p != nullptr) != (b->top_p_host != nullptr))
+      FSV_FAIL(c, FSV_E_INVALID_ARG, "top_p needs both its device and its host copy (or neither)");
+    if (b->top_p_host)
+      for (int i = 0; i < b->batch; ++i)
+        if (!(b->top_p_host[i] > 0.f) || !(b->top_p_host[i] <= 1.f))
+          FSV_FAIL(c, FSV_E_INVALID_ARG, "top_p of request %d is not in (0, 1]", i);
   }
   if (need_kv) {
     if (!b->seq_lens || !b->seq_lens_host || !b->page_table || !b->k_pool || !b->v_pool)
@@ -87,7 +93,8 @@ void fsv_destroy(fsv_ctx *c) {
   if (!c) return;
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
-                  c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->x, c->logits,
+                  c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->rowkey, c->nuc_prefix,
+                  c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->x, c->logits,
                   c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
@@ -136,6 +143,9 @@ int fsv_create(const fsv_model_desc *desc, const fsv_weights *w, fsv_ctx **out) 
   A(dev_alloc(c, &c->pmax, R * c->nc)); A(dev_alloc(c, &c->psum, R * c->nc)); A(dev_alloc(c, &c->parg, R * c->nc));
   A(dev_alloc(c, &c->bsum, B * c->nsb)); A(dev_alloc(c, &c->tau_ws, B)); A(dev_alloc(c, &c->rowstat, 2 * B));
   A(dev_alloc(c, &c->acc_scratch, B));
+  A(dev_alloc(c, &c->rowkey, B));
+  A(dev_alloc(c, &c->nuc_prefix, R)); A(dev_alloc(c, &c->nuc_key, R)); A(dev_alloc(c, &c->nuc_above, R));
+  A(dev_alloc(c, &c->nuc_total, R)); A(dev_alloc(c, &c->nuc_S, R)); A(dev_alloc(c, &c->nuc_near, R));
   if (rc == FSV_OK && d.n_layers > 0) {
     const size_t rows_pad = (R + 31) / 32 * 32;
     A(dev_alloc(c, &c->x, rows_pad * d.d_model));

@@ -60,6 +60,12 @@ struct fsv_ctx {
   int32_t *tau_ws = nullptr;   // [max_batch]
   double *rowstat = nullptr;   // [max_batch][2]: max (as double), 1/S of the row the token is drawn from
   int32_t *acc_scratch = nullptr;  // [max_batch] accepted_len when the caller passes none
+  uint32_t *rowkey = nullptr;      // [max_batch] nucleus cut key of the row the token is drawn from (0 = no cut)
+  // nucleus (top-p) selection, per logits row: digit-by-digit state, then the cut key, the kept mass, the near flag
+  uint32_t *nuc_prefix = nullptr, *nuc_key = nullptr;
+  unsigned long long *nuc_above = nullptr, *nuc_total = nullptr;
+  double *nuc_S = nullptr;
+  int32_t *nuc_near = nullptr;
 
   // model workspace (both paths)
   float *x = nullptr;       // [rows_pad][d_model] residual stream, fp32

@@ -198,11 +198,117 @@ __global__ __launch_bounds__(256) void k_row_stats(const LT *__restrict__ logits
   }
 }
 
+// ---- nucleus (top-p) cut of the target law ------------------------------------------------------------------
+// The cut keeps every token whose logit is at least the cut value: the largest value for which the kept mass reaches
+// top_p (tokens tied at the cut value are all kept, so the set does not depend on an order among ties).  The cut value
+// is found digit by digit on a monotone 32-bit key of the logit: one pass over the row per digit builds a histogram of
+// the mass per digit value (in LDS, in 2^-40 fixed point, so that the sums do not depend on the order of the atomic
+// adds), and a scan from the top picks the digit at which the kept mass crosses top_p of the total.
+__device__ inline uint32_t okey(float f) {  // monotone: a < b  <=>  okey(a) < okey(b)
+  const uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+constexpr int FSV_NUC_BINS = 2048;
+constexpr double kNucScale = 1099511627776.0;  // 2^40
+
+// LEVEL 0: key bits 31..21, LEVEL 1: bits 20..10, LEVEL 2: bits 9..0.  LAST marks the level that fixes the whole key
+// (level 1 for bf16 logits, whose keys have no information below bit 16; level 2 for fp32 logits).  grid = rows.
+template <typename LT, int LEVEL, bool LAST>
+__global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits, int V, int nc,
+                                                  const int32_t *__restrict__ row_req,
+                                                  const float *__restrict__ temperature, const float *__restrict__ top_p,
+                                                  const float *__restrict__ pmax, uint32_t *__restrict__ st_prefix,
+                                                  unsigned long long *__restrict__ st_above,
+                                                  unsigned long long *__restrict__ st_total, uint32_t *__restrict__ nuc_key,
+                                                  double *__restrict__ nuc_S, int32_t *__restrict__ nuc_near, int vec) {
+  constexpr int SHIFT = (LEVEL == 0) ? 21 : (LEVEL == 1 ? 10 : 0), BITS = (LEVEL == 2) ? 10 : 11;
+  const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int b = row_req[r];
+  const float T = temperature[b], tp = top_p[b];
+  if (!(T > 0.f) || !(tp < 1.f)) {  // no cut for this row
+    if (LEVEL == 0 && tid == 0) { nuc_key[r] = 0u; nuc_S[r] = -1.0; nuc_near[r] = 0; }
+    return;
+  }
+  __shared__ unsigned long long hist[FSV_NUC_BINS];
+  __shared__ float s_m;
+  __shared__ unsigned long long s_sums[64];
+  for (int i = tid; i < FSV_NUC_BINS; i += 1024) hist[i] = 0ull;
+  if (tid < 64) {
+    float mx = -INFINITY;
+    for (int c = lane; c < nc; c += 64) mx = fmaxf(mx, pmax[(size_t)r * nc + c]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off, 64));
+    if (lane == 0) s_m = mx;
+  }
+  __syncthreads();
+  const float m = s_m;
+  const exp_scale k = make_exp_scale(kLog2e / (double)T);
+  const uint32_t prefix = (LEVEL > 0) ? st_prefix[r] : 0u;
+  const LT *row = logits + (size_t)r * V;
+  for (int i0 = tid * 8; i0 < V; i0 += 1024 * 8) {
+    float v[8];
+    if (vec && i0 + 8 <= V) loader<LT>::load8_fast(row, i0, v);
+    else loader<LT>::load8(row, i0, V, vec != 0, -INFINITY, v);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t key = okey(v[j]);
+      if (LEVEL > 0 && (key >> (SHIFT + BITS)) != prefix) continue;
+      const unsigned long long q = (unsigned long long)((double)exp_scaled(v[j] - m, k) * kNucScale + 0.5);
+      if (q) atomicAdd(&hist[(key >> SHIFT) & ((1u << BITS) - 1u)], q);
+    }
+  }
+  __syncthreads();
+  if (tid >= 64) return;
+  // lane l owns the 32 digit values below (64 - l) * 32, the highest values in lane 0: masses above each lane's group
+  constexpr int PER = FSV_NUC_BINS / 64;
+  unsigned long long mine = 0ull;
+  const int top = (63 - lane) * PER + PER - 1;
+#pragma unroll
+  for (int i = 0; i < PER; ++i) mine += hist[top - i];
+  unsigned long long incl = mine;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned long long t = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += t;
+  }
+  unsigned long long total = (LEVEL == 0) ? __shfl(incl, 63, 64) : st_total[r];
+  const unsigned long long above0 = (LEVEL == 0) ? 0ull : st_above[r];
+  const double target = (double)tp * (double)total;
+  const unsigned long long before = above0 + (incl - mine);  // mass strictly above this lane's group
+  const bool crosses = (double)(before + mine) >= target;
+  const unsigned long long ballot = __ballot(crosses);
+  // rounding cannot leave the ballot empty at level 0 (the last lane holds the total); at deeper levels the digit group
+  // was chosen because it crosses, so some lane does as well; the guard only keeps the index in range
+  const int pick_lane = ballot ? (int)__builtin_ctzll(ballot) : 63;
+  if (lane != pick_lane) return;
+  unsigned long long acc = before;
+  int digit = top - (PER - 1);
+  for (int i = 0; i < PER; ++i) {
+    const unsigned long long hbin = hist[top - i];
+    if ((double)(acc + hbin) >= target || i == PER - 1) { digit = top - i; break; }
+    acc += hbin;
+  }
+  const uint32_t newprefix = (prefix << BITS) | (uint32_t)digit;
+  if (!LAST) {
+    st_prefix[r] = newprefix;
+    st_above[r] = acc;
+    if (LEVEL == 0) st_total[r] = total;
+  } else {
+    const unsigned long long kept = acc + hist[digit];
+    nuc_key[r] = newprefix << SHIFT;
+    nuc_S[r] = (double)kept / kNucScale;
+    const double lo = target - (double)acc, hi = (double)kept - target;
+    nuc_near[r] = (fmin(lo, hi) < 1e-6 * (double)total) ? 1 : 0;
+  }
+}
+
 #define FSV_MAX_GAMMA 16
 
 template <typename LT>
 __device__ inline double thread_masses(const LT *lrow, const float *qrow, int i0, int V, bool lvec, bool qvec,
-                                       float m, exp_scale k, double invS, bool residual, bool fast, double (&mass)[8]) {
+                                       float m, exp_scale k, double invS, bool residual, bool fast, uint32_t cutkey,
+                                       double (&mass)[8]) {
   float lv[8], qv[8];
   if (fast) {  // the caller has checked alignment and range for the whole sub-block
     loader<LT>::load8_fast(lrow, i0, lv);
@@ -214,7 +320,7 @@ __device__ inline double thread_masses(const LT *lrow, const float *qrow, int i0
   double t = 0.0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    double p = (double)exp_scaled(lv[j] - m, k) * invS;
+    double p = (okey(lv[j]) >= cutkey) ? (double)exp_scaled(lv[j] - m, k) * invS : 0.0;  // cutkey 0: nothing is cut
     if (residual) {
       p -= (double)qv[j];
       p = p > 0.0 ? p : 0.0;
@@ -234,7 +340,8 @@ __global__ __launch_bounds__(256) void k_accept(
     const float *__restrict__ q, const float *__restrict__ u_acc, const float *__restrict__ temperature,
     const float *__restrict__ pmax, const double *__restrict__ psum, const int32_t *__restrict__ parg,
     int32_t *__restrict__ tau_ws, double *__restrict__ rowstat, int32_t *__restrict__ accepted_len,
-    int32_t *__restrict__ next_token, uint32_t *__restrict__ flags) {
+    int32_t *__restrict__ next_token, uint32_t *__restrict__ flags, const uint32_t *__restrict__ nuc_key,
+    const double *__restrict__ nuc_S, const int32_t *__restrict__ nuc_near, uint32_t *__restrict__ rowkey) {
   const int b = blockIdx.x, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const int o = off[b], gamma = min(off[b + 1] - o, FSV_MAX_GAMMA), rs = o + b;
   const float T = temperature[b];
@@ -257,7 +364,12 @@ __global__ __launch_bounds__(256) void k_accept(
     if (T > 0.f && lane < nc) term = ps * ((pm == mx) ? 1.0 : exp(((double)pm - (double)mx) * invT));
 #pragma unroll
     for (int sh = 32; sh > 0; sh >>= 1) term += __shfl_xor(term, sh, 64);
-    if (lane == 0) { s_m[i] = (double)mx; s_S[i] = term; s_arg[i] = ai; }
+    if (lane == 0) {
+      s_m[i] = (double)mx;
+      // a row cut to its nucleus is normalised by the kept mass; its cut key masks the tokens outside
+      s_S[i] = (nuc_S && nuc_S[rs + i] >= 0.0) ? nuc_S[rs + i] : term;
+      s_arg[i] = ai;
+    }
   }
   __syncthreads();
   if (T <= 0.f) {  // greedy (Alg. 2): accept while the draft equals the argmax, emit the argmax
@@ -276,7 +388,8 @@ __global__ __launch_bounds__(256) void k_accept(
     float lv;
     if constexpr (sizeof(LT) == 2) lv = __uint_as_float((uint32_t)logits[(size_t)r * V + d] << 16);
     else lv = logits[(size_t)r * V + d];
-    const double p = exp(((double)lv - s_m[tid]) * invT) / s_S[tid];
+    const bool kept = !nuc_key || okey(lv) >= nuc_key[r];
+    const double p = kept ? exp(((double)lv - s_m[tid]) * invT) / s_S[tid] : 0.0;
     const double qd = (double)q[(size_t)(o + tid) * V + d];
     const double ratio = p / qd;
     double a = (ratio >= 1.0) ? 1.0 : ratio;
@@ -291,11 +404,14 @@ __global__ __launch_bounds__(256) void k_accept(
     while (tau < gamma && s_acc[tau]) ++tau;
     uint32_t f = (tau < gamma) ? 4u : 0u;
     for (int i = 0; i < gamma && i <= tau; ++i) f |= s_near[i] ? 1u : 0u;
+    if (nuc_near)
+      for (int i = 0; i <= tau; ++i) f |= nuc_near[rs + i] ? 8u : 0u;   // rows 0..tau are the ones the outcome rests on
     tau_ws[b] = tau;
     accepted_len[b] = tau;
     flags[b] = f;
     rowstat[2 * b] = s_m[tau];
     rowstat[2 * b + 1] = 1.0 / s_S[tau];
+    rowkey[b] = nuc_key ? nuc_key[rs + tau] : 0u;
   }
 }
 
@@ -306,13 +422,15 @@ template <typename LT>
 __global__ __launch_bounds__(256) void k_mass(const LT *__restrict__ logits, int V, int nsb, const int32_t *__restrict__ off,
                                               const float *__restrict__ q, const float *__restrict__ temperature,
                                               const int32_t *__restrict__ tau_ws, const double *__restrict__ rowstat,
-                                              double *__restrict__ bsum, int lvec, int qvec) {
+                                              const uint32_t *__restrict__ rowkey, double *__restrict__ bsum, int lvec,
+                                              int qvec) {
   const int b = blockIdx.y, tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
   const float T = temperature[b];
   if (T <= 0.f) return;
   const int o = off[b], gamma = min(off[b + 1] - o, FSV_MAX_GAMMA), rs = o + b, tau = tau_ws[b];
   const bool residual = tau < gamma;
   const double m = rowstat[2 * b], invS = rowstat[2 * b + 1];
+  const uint32_t cutkey = rowkey[b];
   const exp_scale k = make_exp_scale(kLog2e / (double)T);
   const LT *lrow = logits + (size_t)(rs + tau) * V;
   const float *qrow = residual ? q + (size_t)(o + tau) * V : nullptr;
@@ -323,7 +441,7 @@ __global__ __launch_bounds__(256) void k_mass(const LT *__restrict__ logits, int
     for (int part = 0; part < FSV_SBK / 512; ++part) {
       double mass[8];
       tot += thread_masses<LT>(lrow, qrow, sb * FSV_SBK + part * 512 + lane * 8, V, lvec != 0, qvec != 0, (float)m, k, invS,
-                               residual, fast, mass);
+                               residual, fast, cutkey, mass);
     }
 #pragma unroll
     for (int sh = 32; sh > 0; sh >>= 1) tot += __shfl_xor(tot, sh, 64);
@@ -337,9 +455,9 @@ template <typename LT>
 __global__ __launch_bounds__(256) void k_select(
     const LT *__restrict__ logits, int V, int nsb, const int32_t *__restrict__ off, const float *__restrict__ q,
     const float *__restrict__ u_smp, const float *__restrict__ temperature, const double *__restrict__ bsum,
-    const int32_t *__restrict__ tau_ws, const double *__restrict__ rowstat, int32_t *__restrict__ next_token,
-    uint32_t *__restrict__ flags, const int32_t *__restrict__ seq_lens, int32_t *__restrict__ new_seq_lens,
-    int32_t *__restrict__ pages_released, int page_size, int lvec, int qvec) {
+    const int32_t *__restrict__ tau_ws, const double *__restrict__ rowstat, const uint32_t *__restrict__ rowkey,
+    int32_t *__restrict__ next_token, uint32_t *__restrict__ flags, const int32_t *__restrict__ seq_lens,
+    int32_t *__restrict__ new_seq_lens, int32_t *__restrict__ pages_released, int page_size, int lvec, int qvec) {
   const int b = blockIdx.x, tid = threadIdx.x;
   const int o = off[b], gamma = min(off[b + 1] - o, FSV_MAX_GAMMA), rs = o + b;
   const int tau = tau_ws[b];
@@ -357,6 +475,7 @@ __global__ __launch_bounds__(256) void k_select(
   __shared__ int s_pick, s_first, s_lastpos;
   bool residual = tau < gamma;
   const double m = rowstat[2 * b], invS = rowstat[2 * b + 1];
+  const uint32_t cutkey = rowkey[b];
   const exp_scale k = make_exp_scale(kLog2e / (double)T);
   const LT *lrow = logits + (size_t)(rs + tau) * V;
   const float *qrow = residual ? q + (size_t)(o + tau) * V : nullptr;
@@ -376,7 +495,7 @@ __global__ __launch_bounds__(256) void k_select(
     for (int sb = 0; sb < nsb; ++sb) {
       double mass[8], tot;
       double t = thread_masses<LT>(lrow, qrow, sb * FSV_SBK + tid * 8, V, lvec != 0, qvec != 0, (float)m, k, invS,
-                                   false, false, mass);
+                                   false, false, cutkey, mass);
       block_incl_scan(t, s_w, &tot);
       if (tid == 0) s_sb[sb] = tot;
     }
@@ -409,7 +528,7 @@ __global__ __launch_bounds__(256) void k_select(
   const double lo = s_lo;
   double mass[8];
   const int i0 = sb * FSV_SBK + tid * 8;
-  double t = thread_masses<LT>(lrow, qrow, i0, V, lvec != 0, qvec != 0, (float)m, k, invS, residual, false, mass);
+  double t = thread_masses<LT>(lrow, qrow, i0, V, lvec != 0, qvec != 0, (float)m, k, invS, residual, false, cutkey, mass);
   double incl = block_incl_scan(t, s_w, nullptr);
   const bool crosses = (lo + incl) > target;  // false for every thread when lo == inf
   if (crosses) atomicMin(&s_first, tid);
@@ -470,18 +589,38 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
     hipLaunchKernelGGL(k_row_stats<LT>, dim3(fsv_ceil_div(nc, 4), M), dim3(256), 0, s, logits, V, nc, c->row_req, b->temperature,
                        c->pmax, c->psum, c->parg, lvec);
   }
+  // Nucleus cut (top-p): only when some request asks for it; one pass over every logits row per key digit.
+  bool nucleus = false;
+  if (b->top_p && b->top_p_host)
+    for (int i = 0; i < B; ++i)
+      nucleus |= b->top_p_host[i] < 1.f && (!b->temperature_host || b->temperature_host[i] > 0.f);
+  if (nucleus) {
+    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_STATS, (double)M * V * sizeof(LT) * (sizeof(LT) == 2 ? 2 : 3));
+#define FSV_NUC(LEVEL, LAST)                                                                                          \
+  hipLaunchKernelGGL((k_nucleus<LT, LEVEL, LAST>), dim3(M), dim3(1024), 0, s, logits, V, nc, c->row_req, b->temperature, \
+                     b->top_p, c->pmax, c->nuc_prefix, c->nuc_above, c->nuc_total, c->nuc_key, c->nuc_S, c->nuc_near, lvec)
+    FSV_NUC(0, false);
+    if (sizeof(LT) == 2) {
+      FSV_NUC(1, true);
+    } else {
+      FSV_NUC(1, false);
+      FSV_NUC(2, true);
+    }
+#undef FSV_NUC
+  }
   {
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_ACCEPT, (double)B * V * (sizeof(LT) + 4));
     hipLaunchKernelGGL(k_accept<LT>, dim3(B), dim3(256), 0, s, logits, V, nc, b->draft_offsets, b->draft_tokens,
                        b->draft_probs, b->u_accept, b->temperature, c->pmax, c->psum, c->parg, c->tau_ws, c->rowstat, acc,
-                       r->next_token, r->flags);
+                       r->next_token, r->flags, nucleus ? c->nuc_key : nullptr, nucleus ? c->nuc_S : nullptr,
+                       nucleus ? c->nuc_near : nullptr, c->rowkey);
     hipLaunchKernelGGL(k_mass<LT>, dim3(fsv_ceil_div(nsb, 4), B), dim3(256), 0, s, logits, V, nsb, b->draft_offsets,
-                       b->draft_probs, b->temperature, c->tau_ws, c->rowstat, c->bsum, lvec, qvec);
+                       b->draft_probs, b->temperature, c->tau_ws, c->rowstat, c->rowkey, c->bsum, lvec, qvec);
   }
   {
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_SELECT, (double)B * FSV_SBK * (sizeof(LT) + 4));
     hipLaunchKernelGGL(k_select<LT>, dim3(B), dim3(256), 0, s, logits, V, nsb, b->draft_offsets, b->draft_probs,
-                       b->u_sample, b->temperature, c->bsum, c->tau_ws, c->rowstat, r->next_token, r->flags,
+                       b->u_sample, b->temperature, c->bsum, c->tau_ws, c->rowstat, c->rowkey, r->next_token, r->flags,
                        with_rollback ? b->seq_lens : nullptr, with_rollback ? r->new_seq_lens : nullptr,
                        with_rollback ? r->pages_released : nullptr, c->d.page_size, lvec, qvec);
   }

@@ -39,7 +39,8 @@ class Weights(C.Structure):
 class Batch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_pages", C.c_int32)] + [(n, C.c_void_p) for n in (
         "seq_lens", "seq_lens_host", "last_token", "draft_offsets", "draft_offsets_host", "draft_tokens", "draft_probs",
-        "u_accept", "u_sample", "temperature", "temperature_host", "page_table", "k_pool", "v_pool")]
+        "u_accept", "u_sample", "temperature", "temperature_host", "page_table", "k_pool", "v_pool", "top_p",
+        "top_p_host")]
 
 
 class Result(C.Structure):
@@ -134,6 +135,8 @@ class DeviceBatch:
     seq_lens_host: np.ndarray | None
     draft_offsets_host: np.ndarray
     temperature_host: np.ndarray | None = None
+    top_p: torch.Tensor | None = None          # [B] nucleus mass per request (None = no cut)
+    top_p_host: np.ndarray | None = None
 
     @property
     def batch(self):
@@ -148,7 +151,7 @@ class DeviceBatch:
                      _ptr(self.last_token), _ptr(self.draft_offsets), _ptr(self.draft_offsets_host),
                      _ptr(self.draft_tokens), _ptr(self.draft_probs), _ptr(self.u_accept), _ptr(self.u_sample),
                      _ptr(self.temperature), _ptr(self.temperature_host), _ptr(self.page_table), _ptr(self.k_pool),
-                     _ptr(self.v_pool))
+                     _ptr(self.v_pool), _ptr(self.top_p), _ptr(self.top_p_host))
 
 
 @dataclass

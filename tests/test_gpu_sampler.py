@@ -138,3 +138,68 @@ def test_empty_batch_and_capacity_errors():
                         None, None, None, 0, None, np.zeros(1, np.int32), None)
     ctx.sample(torch.zeros((1, 4096), device="cuda"), B0, fv.DeviceResult.alloc(1))
     ctx.close()
+
+
+@pytest.mark.parametrize("vocab,batch,gmax,dtype,seed", [
+    (5000, 8, 6, "bf16", 21),        # bf16 logits: many tokens tie at the cut value
+    (5003, 6, 5, "f32", 22),         # odd vocabulary, fp32 keys (three digits)
+    (30000, 6, 8, "f32", 23),
+    (152064, 10, 12, "bf16", 24),    # the full vocabulary of the sampling configuration
+])
+def test_nucleus_cut_matches_oracle(vocab, batch, gmax, dtype, seed):
+    """top-p per request (Regime B samples with top-p): 1.0 (off), 0.9 and a tight 0.5 mixed in one batch."""
+    fv, ctx = _ctx(vocab, batch, 16)
+    case = synth.make_sampler_case(batch, 1, gmax, vocab, 0.5, 0.7, seed, logits_dtype=dtype)
+    top_p = np.array([(1.0, 0.9, 0.5)[b % 3] for b in range(batch)], np.float32)
+    B = batch
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device="cuda")
+    bt = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs.cuda(),
+                        t(case.u_accept), t(case.u_sample), t(case.temperature), None, None, None, 0, None,
+                        np.ascontiguousarray(case.draft_offsets), np.ascontiguousarray(case.temperature),
+                        t(top_p), top_p)
+    res = fv.DeviceResult.alloc(B)
+    ctx.sample(case.logits.cuda(), bt, res)
+    torch.cuda.synchronize()
+    tau, nxt, flags = res.accepted_len.cpu().numpy(), res.next_token.cpu().numpy(), res.flags.cpu().numpy()
+    lg = case.logits.float().numpy().astype(np.float64)
+    q = case.draft_probs.numpy()
+    exp, near = [], 0
+    for b in range(B):
+        o, e = int(case.draft_offsets[b]), int(case.draft_offsets[b + 1])
+        s = oracle.sample(lg[o + b: e + b + 1], case.draft_tokens[o:e], q[o:e], case.u_accept[o:e],
+                          float(case.u_sample[b]), 0.7, top_p=float(top_p[b]))
+        if s.nucleus_margin < 1e-6:       # the cut itself is within rounding of top_p: either neighbour is right
+            near += 1
+            exp.append(None)
+        else:
+            exp.append(type("R", (), {"sample": s})())
+    bad, excused, flagged = compare_decisions(exp, tau, nxt)
+    changed = 0
+    for b in range(B):    # the cut must matter for some request, or the test shows nothing
+        o, e = int(case.draft_offsets[b]), int(case.draft_offsets[b + 1])
+        s0 = oracle.sample(lg[o + b: e + b + 1], case.draft_tokens[o:e], q[o:e], case.u_accept[o:e],
+                           float(case.u_sample[b]), 0.7)
+        if exp[b] is not None and (s0.tau, s0.next_token) != (exp[b].sample.tau, exp[b].sample.next_token):
+            changed += 1
+    print(f"V={vocab}: accepted {tau.sum()}/{case.draft_offsets[-1]}, requests the cut changes {changed}, "
+          f"near the cut {near}, flagged {flagged}, excused {excused}")
+    assert not bad, bad
+    assert changed >= 1
+    for b in range(B):
+        if top_p[b] == 1.0:
+            assert not (flags[b] & 8)
+    ctx.close()
+
+
+def test_nucleus_rejects_bad_top_p():
+    fv, ctx = _ctx(4096, 2, 4)
+    case = synth.make_sampler_case(2, 1, 3, 4096, 0.5, 0.7, 3, logits_dtype="bf16")
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device="cuda")
+    for bad in (np.array([0.9, 0.0], np.float32), np.array([1.5, 0.9], np.float32)):
+        bt = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs.cuda(),
+                            t(case.u_accept), t(case.u_sample), t(case.temperature), None, None, None, 0, None,
+                            np.ascontiguousarray(case.draft_offsets), np.ascontiguousarray(case.temperature), t(bad), bad)
+        with pytest.raises(fv.FsvError) as ei:
+            ctx.sample(case.logits.cuda(), bt, fv.DeviceResult.alloc(2))
+        assert ei.value.status == -1
+    ctx.close()
