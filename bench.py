@@ -88,6 +88,9 @@ def sampler_bench(args, torch, fv, synth):
     batch = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs, t(case.u_accept),
                            t(case.u_sample), t(case.temperature), None, None, None, 0, None,
                            np.ascontiguousarray(case.draft_offsets), np.ascontiguousarray(case.temperature))
+    if args.top_p < 1.0:
+        batch.top_p_host = np.full(B, args.top_p, np.float32)
+        batch.top_p = t(batch.top_p_host)
     res = fv.DeviceResult.alloc(B)
     for _ in range(args.warmup):
         ctx.sample(case.logits, batch, res)
@@ -111,6 +114,7 @@ def sampler_bench(args, torch, fv, synth):
            "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
            "data": "synthetic",
            "config": {"workload": "c4_sampler", "batch": B, "drafts": G, "rows": M, "vocab": V, "temperature": T,
+                      "top_p": args.top_p,
                       "draft_noise_sigma": sigma, "accepted_drafts": int(tau.sum())},
            "roofline": {"bound": "hbm", "kernel": "k_row_stats (one pass over every logits row)",
                         "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -224,6 +228,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pages", default=None, choices=["interleaved", "permuted", "contiguous"],
                     help="page-table layout of the KV sessions (default: the workload's own, interleaved)")
+    ap.add_argument("--top-p", type=float, default=1.0,
+                    help="nucleus mass applied to the target law of every request (1 = off, the configurations' setting)")
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (one extra untimed pass)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, the known-size reference the HBM counters are scaled by")
@@ -255,6 +261,9 @@ def main():
     req, ctx = w.req, w.ctx
     B, G, M = req.batch, w.drafts, w.drafts + req.batch
     res = fv.DeviceResult.alloc(B)
+    if args.top_p < 1.0:
+        w.batch.top_p_host = np.full(B, args.top_p, np.float32)
+        w.batch.top_p = torch.as_tensor(w.batch.top_p_host, device="cuda")
 
     def step():
         ctx.verify(w.batch, res)
@@ -288,7 +297,7 @@ def main():
            "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
            "data": "synthetic",
            "config": {"workload": wl.name, "model_shape": cfg.name, "batch": B, "drafts": G, "rows": M,
-                      "kv_tokens": int(req.seq_lens.sum()), "temperature": wl.temperature, "draft_noise_sigma": wl.sigma,
+                      "kv_tokens": int(req.seq_lens.sum()), "temperature": wl.temperature, "top_p": args.top_p, "draft_noise_sigma": wl.sigma,
                       "accepted_drafts": int(tau.sum()), "emitted_tokens": int(tau.sum()) + B},
            "roofline": roofline}
     # whole-step algorithmic bytes: weights once + KV of every cached position + logits

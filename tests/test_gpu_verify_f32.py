@@ -199,3 +199,47 @@ def test_sessions_over_several_rounds_f32():
         assert np.abs(gk.cpu().numpy() - kc[:, :L[b]]).max() <= 1e-4 * max(1.0, float(np.abs(kc[:, :L[b]]).max()))
         assert np.abs(gv.cpu().numpy() - vc[:, :L[b]]).max() <= 1e-4 * max(1.0, float(np.abs(vc[:, :L[b]]).max()))
     ctx.close()
+
+
+def test_regime_b_top_p_end_to_end_f32():
+    """The whole step with the sampling set-up of Regime B (Sec. V): temperature 1, top-p 0.9 on the target law."""
+    from oracle import oracle
+    from paper_2601_00644_amd import flexverify as fv
+    cfg = synth.MODELS["minif32"]
+    wl = synth.Workload("t", "minif32", 6, 3, 90, "uniform", 0, 7, "uniform", 0.7, 1.0, "permuted")
+    case = build_case(cfg, wl, seed=12, weight_std=0.3, run_oracle=False)     # wide logits: the nucleus is a real subset
+    req = case.req
+    top_p = np.full(req.batch, 0.9, np.float32)
+    ctx = fv.Context(cfg, {k: v.cuda() for k, v in case.weights.items()}, max_batch=req.batch, max_gamma=16,
+                     max_pages_per_req=req.page_table.shape[1])
+    kp, vp = fv.alloc_pools(cfg, req.num_pages)
+    pt = torch.as_tensor(req.page_table).cuda()
+    for b in range(req.batch):
+        ctx.kv_import(kp, vp, req.num_pages, pt[b], 0, case.ctx_k[b].cuda(), case.ctx_v[b].cuda())
+    batch = fv.device_batch(req, case.draft_tokens, case.draft_probs.cuda(), kp, vp)
+    batch.top_p, batch.top_p_host = torch.as_tensor(top_p).cuda(), top_p
+    res = fv.DeviceResult.alloc(req.batch, batch.rows, cfg.vocab, want_logits=True)
+    ctx.verify(batch, res)
+    torch.cuda.synchronize()
+    tau, nxt = res.accepted_len.cpu().numpy(), res.next_token.cpu().numpy()
+    lg = res.logits_out.cpu().numpy().astype(np.float64)
+    exp, exp_off, cut_matters = [], [], 0
+    for b in range(req.batch):
+        L, g, o = int(req.seq_lens[b]), int(req.gammas[b]), int(req.draft_offsets[b])
+        kc, vc = oracle.new_cache(cfg, L + g + 1)
+        kc[:, :L], vc[:, :L] = synth.kv_to_f64(case.ctx_k[b]), synth.kv_to_f64(case.ctx_v[b])
+        toks = np.concatenate([[req.last_token[b]], case.draft_tokens[o:o + g]]).astype(np.int32)
+        ref = oracle.forward(cfg, case.weights_np, kc, vc, L, toks)
+        ok, ratio = logits_close(lg[o + b: o + b + g + 1], ref, 1e-4)
+        assert ok, (b, ratio)
+        args = (ref, case.draft_tokens[o:o + g], case.draft_probs[o:o + g].numpy(), req.u_accept[o:o + g],
+                float(req.u_sample[b]), 1.0)
+        s = oracle.sample(*args, top_p=0.9)
+        s0 = oracle.sample(*args)
+        cut_matters += int((s.tau, s.next_token) != (s0.tau, s0.next_token))
+        exp.append(None if s.nucleus_margin < 1e-5 else type("R", (), {"sample": s})())
+    bad, excused, flagged = compare_decisions(exp, tau, nxt)
+    print(f"regime B: accepted {int(tau.sum())}/{int(req.draft_offsets[-1])}, requests the cut changes {cut_matters}")
+    assert not bad, bad
+    assert (res.new_seq_lens.cpu().numpy() == req.seq_lens + 1 + tau).all()
+    ctx.close()
