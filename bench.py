@@ -23,9 +23,9 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 # HBM bytes one launch of the dominant kernel (gate|up GEMM at 97 rows) moves, from the two rocprofv3 --pmc passes recorded
-# in profiles/verify_c3_8b_b16_hbm_traffic.txt: FETCH_SIZE 118886.0 counts x 2.0 KiB + WRITE_SIZE 3584.0 counts x 1.0 KiB
+# in profiles/verify_c3_8b_b16_hbm_traffic.txt: FETCH_SIZE 118862.5 counts x 2.0 KiB + WRITE_SIZE 3584.0 counts x 1.0 KiB
 # (the scale factors are what the same counters read for a plain 1 GiB copy).  Only valid for the default workload.
-GATE_UP_TRAFFIC_BYTES = (118886.0 * 2.0 + 3584.0 * 1.0) * 1024.0
+GATE_UP_TRAFFIC_BYTES = (118862.5 * 2.0 + 3584.0 * 1.0) * 1024.0
 
 
 def log(msg):
