@@ -207,7 +207,11 @@ int fsv_attention(fsv_ctx *ctx, int32_t layer, const void *q, const fsv_batch *b
  * Per-kernel timing with HIP events on the call's stream.  fsv_profile_enable(ctx, mask) makes every
  * later fsv_verify / fsv_sample / fsv_linear / fsv_attention record an event pair around each launch
  * of the kernel classes whose bit (1u << FSV_K_*) is set in mask (0 = off, 0xffffffff = all; at most
- * 8192 launches are kept, later ones are not recorded); fsv_profile_read() waits for the recorded
+ * 8192 launches are kept, later ones are not recorded).  For the GEMM and attention classes the pair
+ * rides on the dispatch itself (start and stop of the kernel); for the other classes it is recorded on
+ * the stream before and after the launches and so includes the dispatch gaps.  A class whose step takes
+ * several launches (FSV_K_SAMPLE_ACCEPT: acceptance + masses; FSV_K_SAMPLE_STATS with a nucleus cut:
+ * statistics, then the cut passes) reports them as they were bracketed.  fsv_profile_read() waits for the recorded
  * events and returns, per class, the number of launches, their summed duration and the algorithmic
  * bytes the host computed for them (weights for a GEMM, K and V for attention, logits and draft law
  * for the sampling kernels), then clears the records.  Returns the number of classes written (<= cap).

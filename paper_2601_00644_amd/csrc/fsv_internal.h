@@ -16,9 +16,10 @@ typedef __attribute__((ext_vector_type(16))) float f32x16_t;   // one 32x32 MFMA
 typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 
 // ---- sampler geometry -------------------------------------------------------------------------
-// A vocabulary row is cut into sub-blocks of SBK ids (256 threads x 8 consecutive ids) and chunks
-// of SPC sub-blocks; the statistics kernel keeps one (max, sum) pair per chunk, the mass kernel one
-// sum per sub-block.
+// A vocabulary row is cut into sub-blocks of SBK ids and chunks of SPC sub-blocks; the statistics
+// kernel keeps one (max, sum, argmax) triple per chunk (one wave per chunk), the mass kernel one sum
+// per sub-block (one wave per sub-block); the selection kernel scans one sub-block with 256 threads
+// x 8 consecutive ids.
 #define FSV_SBK 2048
 #define FSV_SPC 4
 #define FSV_CHUNK (FSV_SBK * FSV_SPC)

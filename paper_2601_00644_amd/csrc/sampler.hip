@@ -4,12 +4,15 @@
 // Sec. II and Regime B of Sec. V) and the rollback of Sec. IV-C.
 //
 // Four launches; the two that stream logits from HBM (k_row_stats, k_mass) carry the time:
-//   k_row_stats   grid (chunks / 4, rows)  one pass over every logits row: per chunk (max, sum e^{(l-max)/T}, argmax)
+//   k_row_stats   grid (chunks / 4, rows)  one pass over every logits row: per chunk (max, sum e^{(l-max)/T}) or argmax
 //   k_accept      grid (requests)          row statistics combined, acceptance tests from gathered scalars
 //   k_mass        grid (slices, requests)  one pass over the single row the emitted token is drawn from (and its
 //                                          draft-law row) producing the mass of every 2048-id sub-block
 //   k_select      grid (requests)          locate the sub-block and the id by inverse CDF, emit flags, roll back
-// Every floating-point sum is taken in a fixed order (no atomics), so results are reproducible.
+// plus, when a request asks for a nucleus (top-p) cut of the target law, k_nucleus: one more pass over every logits
+// row per digit of the cut value (two for bf16 logits, three for fp32), between k_row_stats and k_accept.
+// Every floating-point sum is taken in a fixed order; the only atomics are integer adds into the nucleus histograms,
+// whose result does not depend on their order, so results are reproducible.
 #include <limits.h>
 #include <math.h>
 
