@@ -203,3 +203,49 @@ def test_nucleus_rejects_bad_top_p():
             ctx.sample(case.logits.cuda(), bt, fv.DeviceResult.alloc(2))
         assert ei.value.status == -1
     ctx.close()
+
+
+def test_many_small_seeded_cases_against_oracle():
+    """Eighty small seeded cases sweeping vocabulary size (aligned and ragged), logit type, gamma, temperature,
+    draft noise and top-p, mixed greedy / sampling requests: decisions equal the oracle's except flagged draws."""
+    fv = None
+    rng = np.random.default_rng(2024)
+    total = flagged_total = excused_total = 0
+    ctxs = {}
+    for case_no in range(80):
+        vocab = int(rng.choice([257, 1000, 2048, 2056, 4099, 8192, 8200, 12345]))
+        batch = int(rng.integers(1, 9))
+        gmax = int(rng.integers(0, 17))
+        dtype = "bf16" if rng.random() < 0.5 else "f32"
+        sigma = float(rng.choice([0.0, 0.3, 0.8, 1.5]))
+        T = float(rng.choice([0.5, 0.7, 1.0, 1.3]))
+        if vocab not in ctxs:
+            fv, ctxs[vocab] = _ctx(vocab, 8, 16)
+        ctx = ctxs[vocab]
+        case = synth.make_sampler_case(batch, 0, gmax, vocab, sigma, T, 1000 + case_no, logits_dtype=dtype)
+        temp = np.where(rng.random(batch) < 0.2, 0.0, T).astype(np.float32)        # some greedy requests
+        top_p = rng.choice([1.0, 1.0, 0.95, 0.8, 0.4], size=batch).astype(np.float32)
+        t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device="cuda")
+        bt = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs.cuda(),
+                            t(case.u_accept), t(case.u_sample), t(temp), None, None, None, 0, None,
+                            np.ascontiguousarray(case.draft_offsets), temp, t(top_p), top_p)
+        res = fv.DeviceResult.alloc(batch)
+        ctx.sample(case.logits.cuda(), bt, res)
+        torch.cuda.synchronize()
+        tau, nxt = res.accepted_len.cpu().numpy(), res.next_token.cpu().numpy()
+        lg = case.logits.float().numpy().astype(np.float64)
+        q = case.draft_probs.numpy()
+        exp = []
+        for b in range(batch):
+            o, e = int(case.draft_offsets[b]), int(case.draft_offsets[b + 1])
+            s = oracle.sample(lg[o + b: e + b + 1], case.draft_tokens[o:e], q[o:e], case.u_accept[o:e],
+                              float(case.u_sample[b]), float(temp[b]), top_p=float(top_p[b]))
+            exp.append(None if s.nucleus_margin < 1e-6 else type("R", (), {"sample": s})())
+        bad, excused, flagged = compare_decisions(exp, tau, nxt)
+        assert not bad, (case_no, vocab, batch, dtype, T, bad)
+        total += batch
+        flagged_total += flagged
+        excused_total += excused
+    print(f"{total} requests in 80 cases: flagged {flagged_total}, excused {excused_total}")
+    for c in ctxs.values():
+        c.close()
