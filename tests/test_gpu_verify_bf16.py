@@ -78,3 +78,36 @@ def test_bf16_fused_step_uses_the_same_sampler_as_fsv_sample():
     torch.cuda.synchronize()
     assert torch.equal(res.accepted_len, res2.accepted_len) and torch.equal(res.next_token, res2.next_token)
     ctx.close()
+
+
+def test_bf16_seeded_shape_sweep():
+    """Eight seeded shapes of the whole bf16 step (both head sizes, batch 1..12, contexts from empty to 1500, gamma up
+    to 16, every page layout): logits against the oracle, rollback outputs against their closed form."""
+    rng = np.random.default_rng(77)
+    for case_no in range(8):
+        name = ("mini128", "mini64")[case_no % 2]
+        cfg = synth.MODELS[name]
+        batch = int(rng.integers(1, 13))
+        ctx_hi = int(rng.choice([0, 40, 300, 900, 1500]))
+        gmax = int(rng.choice([1, 4, 9, 16]))
+        pages = ("interleaved", "permuted", "contiguous")[case_no % 3]
+        wl = synth.Workload("t", name, batch, 0, ctx_hi, "uniform", 0, gmax, "uniform", 0.7, 0.8, pages)
+        case = build_case(cfg, wl, seed=200 + case_no, weight_std=0.04)
+        ctx, batch_d, res, kp, vp, pt = run_library(case)
+        req = case.req
+        lg = res.logits_out.cpu().numpy().astype(np.float64)
+        worst = 0.0
+        for b, e in enumerate(case.expected):
+            rs = int(req.draft_offsets[b]) + b
+            ok, ratio, l2 = logits_close_bf16(lg[rs: rs + int(req.gammas[b]) + 1], e.logits, 2e-2)
+            worst = max(worst, ratio, l2)
+            assert ok, (case_no, name, b, ratio, l2)
+        tau = res.accepted_len.cpu().numpy()
+        bad, excused, flagged = compare_decisions(case.expected, tau, res.next_token.cpu().numpy(), ACCEPT_BF16, CDF_BF16)
+        assert not bad, (case_no, bad)
+        nl, pr = res.new_seq_lens.cpu().numpy(), res.pages_released.cpu().numpy()
+        for b in range(req.batch):
+            L, g = int(req.seq_lens[b]), int(req.gammas[b])
+            assert nl[b] == L + 1 + tau[b] and pr[b] == (L + 1 + g + 15) // 16 - (int(nl[b]) + 15) // 16
+        print(f"case {case_no}: {name} B={batch} ctx<={ctx_hi} gamma<={gmax} {pages}: worst logit ratio {worst:.3e}")
+        ctx.close()
