@@ -25,6 +25,14 @@
  *                   equal to the nucleus-cut target law.
  *   - orc_rollback: the KV rollback of Sec. IV-C (positions from the first
  *                   rejected draft onward are discarded).
+ *   - orc_forward_stored : the same forward with chosen intermediate tensors ROUNDED TO
+ *                   bf16 where a bf16 deployment stores them between steps (the
+ *                   configurations run the 1B / 8B targets "in bf16": weights, the KV
+ *                   cache and the activations handed from one step to the next are
+ *                   bf16 tensors).  All arithmetic stays fp64; only the named tensors
+ *                   are rounded (round to nearest, ties to even).  With mask 0 it IS
+ *                   orc_forward.  The difference between the two is the error that
+ *                   bf16 storage alone causes, whatever computes the steps.
  *
  * Parity pins for every function live in tests/test_oracle_*.py.
  */
@@ -60,6 +68,31 @@ static inline double widen(const void *w, int bf16, size_t idx) {
     return (double)f;
   }
   return (double)((const float *)w)[idx];
+}
+
+/* Storage points of a bf16 deployment (orc_forward_stored): which tensors are rounded to bf16. */
+enum {
+  ORC_ST_A = 1,    /* normalised activations entering the QKV, gate|up and LM-head projections */
+  ORC_ST_Q = 2,    /* rotated queries                                                          */
+  ORC_ST_KV = 4,   /* rotated keys and values of the new rows, as written to the KV cache       */
+  ORC_ST_P = 8,    /* attention probabilities relative to the row maximum, exp(s - max)         */
+  ORC_ST_O = 16,   /* attention output entering the O projection                                */
+  ORC_ST_ACT = 32  /* SwiGLU output entering the down projection                                */
+};
+
+/* Nearest bf16 (8 significant bits, fp32 exponent range), ties to even, of a double; returned as a double. */
+double orc_round_bf16(double x) {
+  if (x == 0.0 || x != x || isinf(x)) return x;
+  int e;
+  (void)frexp(x, &e);                    /* x = m 2^e, 0.5 <= |m| < 1 */
+  int qe = e - 8;                        /* quantum 2^(e-8): 8 significant bits */
+  if (qe < -133) qe = -133;              /* subnormal range of the fp32 exponent: fixed quantum 2^-133 */
+  double r = ldexp(nearbyint(ldexp(x, -qe)), qe);   /* default rounding mode: nearest, ties to even */
+  if (fabs(r) >= ldexp(1.0, 128)) r = (x > 0) ? INFINITY : -INFINITY;
+  return r;
+}
+static void round_rows(double *v, size_t n) {
+  for (size_t i = 0; i < n; ++i) v[i] = orc_round_bf16(v[i]);
 }
 
 /* Dense projection, the definition: y[m][o] = sum_k x[m][k] * W[o][k]   (x: [n][in], y: [n][out]) */
@@ -104,8 +137,8 @@ static void rope(double *vec, int hd, int pos, double theta) {
  *   kl,vl: [>= L+n][Hkv*hd] keys / values of this layer
  *   out : [n][H*hd]
  */
-void orc_attention(const double *q, int q_stride, const double *kl, const double *vl, int L, int n, int H, int Hkv,
-                   int hd, double *out) {
+static void attention_impl(const double *q, int q_stride, const double *kl, const double *vl, int L, int n, int H,
+                           int Hkv, int hd, double *out, int round_p) {
   const int kvdim = Hkv * hd, group = H / Hkv;
   double *sc = malloc(sizeof(double) * (L + n));
   for (int i = 0; i < n; ++i) {
@@ -127,12 +160,18 @@ void orc_attention(const double *q, int q_stride, const double *kl, const double
       for (int e = 0; e < hd; ++e) o[e] = 0.0;
       for (int j = 0; j < nkeys; ++j) {
         const double *vv = vl + (size_t)j * kvdim + kvh * hd;
-        double p = sc[j] / den;
+        /* ORC_ST_P: the numerator uses the stored (rounded) exp(s - max), the normaliser the exact sum */
+        double p = (round_p ? orc_round_bf16(sc[j]) : sc[j]) / den;
         for (int e = 0; e < hd; ++e) o[e] += p * vv[e];
       }
     }
   }
   free(sc);
+}
+
+void orc_attention(const double *q, int q_stride, const double *kl, const double *vl, int L, int n, int H, int Hkv,
+                   int hd, double *out) {
+  attention_impl(q, q_stride, kl, vl, L, n, H, Hkv, hd, out, 0);
 }
 
 /*
@@ -145,8 +184,8 @@ void orc_attention(const double *q, int q_stride, const double *kl, const double
  * Query i attends to keys 0 .. L+i (context plus the block up to itself).
  * Returns 0, or -1 on bad arguments / out of memory.
  */
-int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
-                const int32_t *tokens, int n, double *logits, double *hidden) {
+int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
+                       const int32_t *tokens, int n, double *logits, double *hidden, int stored) {
   const int d = mo->d_model, H = mo->n_heads, Hkv = mo->n_kv_heads, hd = mo->head_dim;
   const int F = mo->d_ffn, V = mo->vocab, bf = mo->weights_bf16;
   if (n <= 0 || L < 0 || L + n > cap || H % Hkv != 0 || hd % 2 != 0) return -1;
@@ -165,33 +204,45 @@ int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *v
   for (int l = 0; l < mo->n_layers; ++l) {
     double *kl = kc + (size_t)l * cap * kvdim, *vl = vc + (size_t)l * cap * kvdim;
     rmsnorm(h, w->attn_norm[l], bf, d, mo->rms_eps, n, a);
+    if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
     orc_linear(w->w_qkv[l], bf, qkvdim, d, a, n, qkv);
     for (int i = 0; i < n; ++i) {
       double *row = qkv + (size_t)i * qkvdim;
       int pos = L + i;
       for (int hh = 0; hh < H; ++hh) rope(row + hh * hd, hd, pos, mo->rope_theta);
       for (int hh = 0; hh < Hkv; ++hh) rope(row + qdim + hh * hd, hd, pos, mo->rope_theta);
+      if (stored & ORC_ST_Q) round_rows(row, qdim);
+      if (stored & ORC_ST_KV) round_rows(row + qdim, 2 * (size_t)kvdim);
       memcpy(kl + (size_t)pos * kvdim, row + qdim, sizeof(double) * kvdim);
       memcpy(vl + (size_t)pos * kvdim, row + qdim + kvdim, sizeof(double) * kvdim);
     }
-    orc_attention(qkv, qkvdim, kl, vl, L, n, H, Hkv, hd, att);
+    attention_impl(qkv, qkvdim, kl, vl, L, n, H, Hkv, hd, att, stored & ORC_ST_P);
+    if (stored & ORC_ST_O) round_rows(att, (size_t)n * qdim);
     orc_linear(w->w_o[l], bf, d, qdim, att, n, upd);
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
     rmsnorm(h, w->mlp_norm[l], bf, d, mo->rms_eps, n, a);
+    if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
     orc_linear(w->w_gate_up[l], bf, 2 * F, d, a, n, gu);
     for (int i = 0; i < n; ++i)
       for (int f = 0; f < F; ++f) {
         double g = gu[(size_t)i * 2 * F + f], u = gu[(size_t)i * 2 * F + F + f];
         act[(size_t)i * F + f] = g / (1.0 + exp(-g)) * u; /* silu(g) * u */
       }
+    if (stored & ORC_ST_ACT) round_rows(act, (size_t)n * F);
     orc_linear(w->w_down[l], bf, d, F, act, n, upd);
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
   }
   if (hidden) memcpy(hidden, h, sizeof(double) * n * d);
   rmsnorm(h, w->final_norm, bf, d, mo->rms_eps, n, a);
+  if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
   orc_linear(w->lm_head, bf, V, d, a, n, logits);
   free(h); free(a); free(qkv); free(att); free(gu); free(act); free(upd);
   return 0;
+}
+
+int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
+                const int32_t *tokens, int n, double *logits, double *hidden) {
+  return orc_forward_stored(mo, w, kc, vc, cap, L, tokens, n, logits, hidden, 0);
 }
 
 typedef struct {

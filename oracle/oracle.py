@@ -51,6 +51,9 @@ def lib():
     if _lib is None:
         _lib = C.CDLL(build())
         _lib.orc_forward.restype = C.c_int
+        _lib.orc_forward_stored.restype = C.c_int
+        _lib.orc_round_bf16.restype = C.c_double
+        _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_sample.restype = C.c_int
         _lib.orc_sample_warp.restype = C.c_int
         _lib.orc_rollback.restype = C.c_int
@@ -103,10 +106,25 @@ def new_cache(cfg, cap: int):
     return np.zeros(shape, np.float64), np.zeros(shape, np.float64)
 
 
-def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False):
+# Tensors a bf16 deployment stores between steps (bit mask for forward(..., stored=)): normalised activations entering
+# a projection, rotated queries, the new rows' keys / values, probabilities relative to the row maximum, the attention
+# output, the SwiGLU output.  ST_BF16 is what "the model runs in bf16" means for the configurations: every tensor that
+# one step hands to the next through memory; the probabilities never leave the attention step and are not part of it.
+ST_A, ST_Q, ST_KV, ST_P, ST_O, ST_ACT = 1, 2, 4, 8, 16, 32
+ST_BF16 = ST_A | ST_Q | ST_KV | ST_O | ST_ACT
+ST_NAMES = {"a": ST_A, "q": ST_Q, "kv": ST_KV, "p": ST_P, "o": ST_O, "act": ST_ACT}
+
+
+def round_bf16(x: float) -> float:
+    """Nearest bf16 value (ties to even) of a double."""
+    return float(lib().orc_round_bf16(float(x)))
+
+
+def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False, stored: int = 0):
     """Target forward over tokens placed at positions L.. on top of cache (kc, vc); appends their KV.
 
     Returns logits [n][vocab] fp64 (and the pre-norm hidden state if asked).  Alg. 2 step 2.
+    stored: mask of ST_* tensors rounded to bf16 (fp64 arithmetic otherwise); 0 = the plain fp64 definition.
     """
     tokens = np.ascontiguousarray(tokens, np.int32)
     n = int(tokens.shape[0])
@@ -116,10 +134,10 @@ def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False):
     hidden = np.empty((n, cfg.d_model), np.float64) if want_hidden else None
     ms = _model_struct(cfg)
     ws, keep = _weights_struct(cfg, w)
-    rc = lib().orc_forward(C.byref(ms), C.byref(ws), C.c_void_p(kc.ctypes.data), C.c_void_p(vc.ctypes.data),
-                           C.c_int(cap), C.c_int(L), C.c_void_p(tokens.ctypes.data), C.c_int(n),
-                           C.c_void_p(logits.ctypes.data),
-                           C.c_void_p(hidden.ctypes.data) if want_hidden else C.c_void_p(0))
+    rc = lib().orc_forward_stored(C.byref(ms), C.byref(ws), C.c_void_p(kc.ctypes.data), C.c_void_p(vc.ctypes.data),
+                                  C.c_int(cap), C.c_int(L), C.c_void_p(tokens.ctypes.data), C.c_int(n),
+                                  C.c_void_p(logits.ctypes.data),
+                                  C.c_void_p(hidden.ctypes.data) if want_hidden else C.c_void_p(0), C.c_int(int(stored)))
     del keep
     if rc != 0:
         raise ValueError("orc_forward rejected its arguments")
@@ -196,10 +214,11 @@ class VerifyResult:
     pages_released: int
 
 
-def verify(cfg, w, kc, vc, L: int, last_token: int, draft, q, u_acc, u_smp: float, T: float) -> VerifyResult:
+def verify(cfg, w, kc, vc, L: int, last_token: int, draft, q, u_acc, u_smp: float, T: float,
+           stored: int = 0) -> VerifyResult:
     """One request of the verification step: score [last_token, drafts], accept/reject, roll back."""
     toks = np.concatenate([[last_token], np.asarray(draft, np.int64)]).astype(np.int32)
-    logits = forward(cfg, w, kc, vc, L, toks)
+    logits = forward(cfg, w, kc, vc, L, toks, stored=stored)
     s = sample(logits, draft, q, u_acc, u_smp, T)
     nl, pr = rollback(L, len(draft), s.tau, cfg.page_size)
     return VerifyResult(logits, s, nl, pr)
