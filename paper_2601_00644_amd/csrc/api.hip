@@ -171,9 +171,12 @@ int fsv_verify(fsv_ctx *c, const fsv_batch *b, const fsv_result *r, void *stream
   if (!b->last_token) FSV_FAIL(c, FSV_E_INVALID_ARG, "last_token required");
   hipStream_t s = (hipStream_t)stream;
   float *logits = r->logits_out ? r->logits_out : c->logits;
-  int rc = fsv_launch_build_rows(c, b, M, s);
+  // everything that can still fail is decided on the host before the first launch
+  fsv_attn_plan pl;
+  int rc = (c->d.dtype == FSV_F32) ? fsv_f32_check(c, b) : fsv_bf16_attn_plan_host(c, b, &pl);
   if (rc) return rc;
-  rc = (c->d.dtype == FSV_F32) ? fsv_f32_forward(c, b, M, logits, s) : fsv_bf16_forward(c, b, M, logits, s);
+  if ((rc = fsv_launch_build_rows(c, b, M, s))) return rc;
+  rc = (c->d.dtype == FSV_F32) ? fsv_f32_forward(c, b, M, logits, s) : fsv_bf16_forward(c, b, &pl, M, logits, s);
   if (rc) return rc;
   return fsv_launch_sampler(c, logits, FSV_F32, b, r, M, true, s);
 }
@@ -244,12 +247,15 @@ int fsv_attention(fsv_ctx *c, int32_t layer, const void *q, const fsv_batch *b, 
   const int M = check_batch(c, b, true, false);
   if (M <= 0) return M;
   hipStream_t s = (hipStream_t)stream;
+  fsv_attn_plan pl;
+  int rc = (c->d.dtype == FSV_F32) ? fsv_f32_check(c, b) : fsv_bf16_attn_plan_host(c, b, &pl);
+  if (rc) return rc;
   fsv_batch bb = *b;
   bb.last_token = nullptr;
   bb.draft_tokens = nullptr;
-  int rc = fsv_launch_build_rows(c, &bb, M, s);
-  if (rc) return rc;
-  return (c->d.dtype == FSV_F32) ? fsv_f32_attention(c, layer, q, b, M, out, s) : fsv_bf16_attention(c, layer, q, b, M, out, s);
+  if ((rc = fsv_launch_build_rows(c, &bb, M, s))) return rc;
+  return (c->d.dtype == FSV_F32) ? fsv_f32_attention(c, layer, q, b, M, out, s)
+                                 : fsv_bf16_attention(c, layer, q, b, &pl, M, out, s);
 }
 
 int fsv_profile_enable(fsv_ctx *c, uint32_t class_mask) {

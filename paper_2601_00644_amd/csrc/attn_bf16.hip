@@ -25,6 +25,12 @@ namespace {
 // each other; a request with one part writes its result directly, the others leave (m, l, O) per part for
 // k_attn_combine.
 //
+// Precision: K and V are the bf16 bits of the cache.  The two operands the kernel itself produces for the matrix
+// cores are carried as a pair of bf16 values (hi + lo, hi = the nearest bf16, lo = the nearest bf16 of the rest: 16
+// significant bits together) and take two MFMAs each: the rotated queries (two planes of the query buffer) and the
+// probabilities.  The matrix cores have the time (the kernel waits for HBM), and the result then differs from exact
+// arithmetic on the stored K / V only by fp32 accumulation.
+//
 // K/V loads go through a buffer descriptor over the layer's pool: a load of a tile beyond the wave's range
 // gets an offset outside the descriptor, for which the hardware returns zeros without touching memory, so
 // the software pipeline needs no branch around its loads and no over-read.
@@ -33,9 +39,8 @@ namespace {
 // by loads and read by MFMAs, both of which reach that half directly; keeping them there leaves the
 // architectural half to the softmax arithmetic and the output accumulators.
 #define FSV_IN_AGPR(x) asm("" : "+a"(x))
-// Pins an MFMA accumulator to the architectural half: the softmax reads the score tile and rescales the output
-// tiles with ordinary vector instructions, which cannot address the accumulation half.
-#define FSV_IN_VGPR(x)
+
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
 // parts of a request with n key tiles when parts should hold about tpw tiles; *tp = tiles per part
 __device__ __host__ inline int attn_parts(int n, int tpw, int *tp) {
@@ -68,14 +73,15 @@ __global__ void k_attn_plan(int B, int tpw, const int32_t *__restrict__ seq_lens
 
 template <int HD, int RT, int NB>
 __global__ __launch_bounds__(64) void k_attention(
-    int Hkv, int group, int rows_cap, const uint4 *__restrict__ qp, const int32_t *__restrict__ part_desc,
+    int Hkv, int group, int rows_cap, const uint4 *__restrict__ qp, size_t q_plane_units,
+    const int32_t *__restrict__ part_desc,
     const int32_t *__restrict__ page_table, int max_pages, int num_pages, const uint16_t *__restrict__ kpool,
     const uint16_t *__restrict__ vpool, uint32_t layer_bytes, float *__restrict__ part_o, float *__restrict__ part_ml,
     uint16_t *__restrict__ out, int KBq) {
   constexpr int KS = HD / 16, VC = HD / 32, TILEB = 16 * HD * 2;  // TILEB: bytes of one (page, kv head) tile
   constexpr uint32_t OOB = 0xFFFF0000u;                            // offset no descriptor here reaches
   constexpr int kStream = 2;  // non-temporal: K/V bytes are used once and should not displace the queries and partials in L2
-  __shared__ uint4 s_q[RT * KS * 64];
+  __shared__ uint4 s_q[2][RT * KS * 64];  // hi and lo planes of the query operand
   const int lane = threadIdx.x, h = lane >> 5, r = lane & 31;
   const int gw = blockIdx.x, pp = gw / Hkv, kvh = gw - pp * Hkv;
   const int4 d0 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * 8);
@@ -122,7 +128,9 @@ __global__ __launch_bounds__(64) void k_attention(
     if (i / KS >= rtc) continue;
     const uint4 *src = qp + (((size_t)b * RTMAX + i / KS) * Hkv + kvh) * (KS * 64) + (i % KS) * 64 + lane;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                     (__attribute__((address_space(3))) void *)&s_q[i * 64], 16, 0, 0);
+                                     (__attribute__((address_space(3))) void *)&s_q[0][i * 64], 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + q_plane_units),
+                                     (__attribute__((address_space(3))) void *)&s_q[1][i * 64], 16, 0, 0);
   }
   int gp0[NB], gp1[NB];
 #pragma unroll
@@ -163,6 +171,27 @@ __global__ __launch_bounds__(64) void k_attention(
     }
     const int kbase = (t0 + j) * 32;
     const bool need_mask = kbase + 31 > L;  // every query row sees all keys <= L
+    if (kbase + 31 >= nk) {
+      // (wave-uniform, the last tile of a request only) Slots beyond the last valid position may never have been written:
+      // their probabilities are zero, but 0 * NaN is NaN, so the V values of those keys are cleared before they reach the
+      // matrix cores.  Element e of vreg[c][pg] belongs to key kbase + 16 pg + 8 (e / 4) + 4 h + e % 4.
+#pragma unroll
+      for (int pg = 0; pg < 2; ++pg) {
+        uint32_t m4[4];
+#pragma unroll
+        for (int dw = 0; dw < 4; ++dw) {
+          const int key = kbase + 16 * pg + 8 * (dw >> 1) + 4 * h + 2 * (dw & 1);
+          m4[dw] = (key < nk ? 0x0000FFFFu : 0u) | (key + 1 < nk ? 0xFFFF0000u : 0u);
+        }
+#pragma unroll
+        for (int c = 0; c < VC; ++c) {
+          u32x4_t raw = __builtin_bit_cast(u32x4_t, vreg[c][pg]);
+#pragma unroll
+          for (int dw = 0; dw < 4; ++dw) raw[dw] &= m4[dw];
+          vreg[c][pg] = __builtin_bit_cast(bf16x8_t, raw);
+        }
+      }
+    }
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
       if (rt >= rtc) continue;
@@ -171,11 +200,10 @@ __global__ __launch_bounds__(64) void k_attention(
       for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        uint4 raw = s_q[(rt * KS + ks) * 64 + lane];
-        FSV_IN_VGPR(s);
+        uint4 raw = s_q[0][(rt * KS + ks) * 64 + lane], rlo = s_q[1][(rt * KS + ks) * 64 + lane];
         s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[ks], *reinterpret_cast<bf16x8_t *>(&raw), s, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kreg[ks], *reinterpret_cast<bf16x8_t *>(&rlo), s, 0, 0, 0);
       }
-      FSV_IN_VGPR(s);
       // accumulator v of this lane: key kbase + 8*(v/4) + 4h + v%4, query row rt*32 + r
       float tmax = -INFINITY;
       if (need_mask) {
@@ -204,12 +232,14 @@ __global__ __launch_bounds__(64) void k_attention(
       const bool rescale = __any(mnew != mold && mold != -INFINITY);
       mrun[rt] = mnew;
       float psum = 0.f;
-      bf16x8_t pb[2];
+      bf16x8_t pb[2], pl[2];  // probabilities as hi + lo
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const float p = __builtin_amdgcn_exp2f(s[v] - muse);
         psum += p;
-        pb[v >> 3][v & 7] = (__bf16)p;
+        const __bf16 hi = (__bf16)p;
+        pb[v >> 3][v & 7] = hi;
+        pl[v >> 3][v & 7] = (__bf16)(p - (float)hi);
       }
       lrun[rt] = lrun[rt] * alpha + psum;
       if (rescale) {  // wave-uniform: once the running maxima have settled the accumulators are left alone
@@ -220,11 +250,10 @@ __global__ __launch_bounds__(64) void k_attention(
       }
 #pragma unroll
       for (int c = 0; c < VC; ++c) {
-        FSV_IN_VGPR(o[rt][c]);
         o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][0], pb[0], o[rt][c], 0, 0, 0);
-        FSV_IN_VGPR(o[rt][c]);
         o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pb[1], o[rt][c], 0, 0, 0);
-        FSV_IN_VGPR(o[rt][c]);
+        o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][0], pl[0], o[rt][c], 0, 0, 0);
+        o[rt][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vreg[c][1], pl[1], o[rt][c], 0, 0, 0);
       }
       __builtin_amdgcn_sched_barrier(0);  // row tiles one after the other: interleaved, their temporaries add up
     }
@@ -420,7 +449,7 @@ int launch_attention(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, si
 #define FSV_ATTN_LAUNCH(HDV, RTV, NBV)                                                                            \
   hipExtLaunchKernelGGL((k_attention<HDV, RTV, NBV>), dim3(pl.waves), dim3(64), 0, st, ps.start(), ps.stop(), 0,   \
                         d.n_kv_heads, group, rows_cap,                                                             \
-                     (const uint4 *)c->buf_q, c->attn_part_map, b->page_table, d.max_pages_per_req, b->num_pages,  \
+                     (const uint4 *)c->buf_q, c->q_plane_units, c->attn_part_map, b->page_table, d.max_pages_per_req, b->num_pages,  \
                      kl, vl, layer_bytes, po, pml, out, KBq)
     if (d.head_dim == 128) {
       if (pl.rt <= 1) FSV_ATTN_LAUNCH(128, 1, 2); else if (pl.rt == 2) FSV_ATTN_LAUNCH(128, 2, 2); else FSV_ATTN_LAUNCH(128, 3, 2);
@@ -447,9 +476,9 @@ int launch_attention(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, si
 
 }  // namespace
 
-int fsv_bf16_attn_plan(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl, hipStream_t st) {
-  int rc = plan_attention(c, b, pl);
-  if (rc) return rc;
+int fsv_bf16_attn_plan_host(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) { return plan_attention(c, b, pl); }
+
+int fsv_bf16_attn_plan_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, hipStream_t st) {
   return launch_attn_plan(c, b, *pl, st);
 }
 

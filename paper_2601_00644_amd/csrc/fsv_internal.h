@@ -74,6 +74,7 @@ struct fsv_ctx {
   void *buf_a = nullptr, *buf_qkv = nullptr, *buf_q = nullptr, *buf_att = nullptr, *buf_gu = nullptr,
        *buf_act = nullptr, *buf_part = nullptr;
   size_t part_bytes = 0;
+  size_t q_plane_units = 0;     // 16-byte units of one plane of buf_q (bf16 path: plane 0 = hi, plane 1 = lo of the queries)
   void *attn_part = nullptr;    // per-part attention results (O, then (m, l)) of requests with several parts
   size_t attn_part_bytes = 0;
   int n_cus = 0;                // compute units of the device the context was created on
@@ -136,6 +137,7 @@ int fsv_launch_sampler(fsv_ctx *c, const void *logits, int logits_dtype, const f
 int fsv_launch_rollback(fsv_ctx *c, const fsv_batch *b, const int32_t *accepted, const fsv_result *r, hipStream_t s);
 // path_f32.hip
 int fsv_f32_create(fsv_ctx *c, const fsv_weights *w);
+int fsv_f32_check(fsv_ctx *c, const fsv_batch *b);   // host only: what the launches of a forward / attention need
 int fsv_f32_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);
 int fsv_f32_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float *y, hipStream_t s);
 int fsv_f32_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s);
@@ -150,17 +152,20 @@ struct fsv_attn_plan {
   double kv_tokens = 0;
 };
 int fsv_bf16_attn_create(fsv_ctx *c);
-int fsv_bf16_attn_plan(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl, hipStream_t s);
+int fsv_bf16_attn_plan_host(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl);          // host only; may fail
+int fsv_bf16_attn_plan_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, hipStream_t s);
 int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, size_t layer_off, hipStream_t s);
 // gemm_bf16.hip: y = x W^T through the weight-streaming kernel; epi 0 = fp32 split partials [splits][Mpad][N],
 // 1 = SwiGLU to the bf16 operand order, 2 = fp32 rows [M][N]
+int fsv_bf16_gemm_init(fsv_ctx *c);
 int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
                   int splits, int KBo, hipStream_t st);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
-int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s);
+int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *logits, hipStream_t s);
 int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float *y, hipStream_t s);
-int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s);
+int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *out,
+                       hipStream_t s);
 int fsv_bf16_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,
                      void *k_lin, void *v_lin, bool import, hipStream_t s);
 void fsv_free_weights(fsv_ctx *c);

@@ -226,13 +226,7 @@ int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, co
   // Weight chunks in flight per wave ahead of the one in use.  Measured on MI355X, one is best: with two to four the
   // bytes in flight across the chip approach the size of the L2s they pass through and the achieved bandwidth drops.
   constexpr int D = 1;
-  const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;
-  static bool attr_set = false;  // per instantiation
-  if (!attr_set) {
-    FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, D>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)ldsb));
-    attr_set = true;
-  }
+  const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;   // fsv_bf16_gemm_init has raised the kernel's limit to this
   // the profiling events ride on the dispatch itself: they time the kernel, not the gaps around it
   fsv_prof_scope ps(c, st, cls, (double)N * KB * 32.0, true);
   hipExtLaunchKernelGGL((k_gemm<MT, EPI, D>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
@@ -264,7 +258,29 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
 #undef FSV_ARGS
 }
 
+template <int MT, int EPI>
+int init_t(fsv_ctx *c) {
+  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, NST * MT * KC * 64 * 16));
+  return FSV_OK;
+}
+
+template <int EPI>
+int init_e(fsv_ctx *c) {
+  int rc;
+  if ((rc = init_t<1, EPI>(c)) || (rc = init_t<2, EPI>(c)) || (rc = init_t<3, EPI>(c)) || (rc = init_t<4, EPI>(c))) return rc;
+  return FSV_OK;
+}
+
 }  // namespace
+
+// Raise the dynamic LDS limit of every instantiation (up to 96 KiB) on the current device; called once per context
+// from its creation, with error checking, so that no launch depends on a lazily set process-wide flag.
+int fsv_bf16_gemm_init(fsv_ctx *c) {
+  int rc;
+  if ((rc = init_e<EPI_PARTIAL>(c)) || (rc = init_e<EPI_SWIGLU>(c)) || (rc = init_e<EPI_F32>(c))) return rc;
+  return FSV_OK;
+}
 
 int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
                   int splits, int KBo, hipStream_t st) {

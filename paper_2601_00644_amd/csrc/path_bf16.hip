@@ -211,7 +211,8 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
                                                      const int32_t *__restrict__ row_pos,
                                                      const int32_t *__restrict__ page_table, int max_pages,
                                                      int num_pages, size_t layer_off, uint16_t *__restrict__ qp,
-                                                     uint16_t *__restrict__ kpool, uint16_t *__restrict__ vpool) {
+                                                     size_t q_plane, uint16_t *__restrict__ kpool,
+                                                     uint16_t *__restrict__ vpool) {
   // grid = (rows, groups of 8 heads of the q|k|v projection)
   __shared__ float s_cos[64], s_sin[64];
   const int r = blockIdx.x, half = hd / 2, heads = H + 2 * Hkv, qkvd = heads * hd, group = H / Hkv;
@@ -245,8 +246,13 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
     }
     if (hh < H) {
       const int kvh = hh / group, rr = i_row * group + hh % group;
-      qp[q_elem_off(b, kvh, rr, i, Hkv, hd)] = f2bf(a);
-      qp[q_elem_off(b, kvh, rr, i + half, Hkv, hd)] = f2bf(c);
+      // the query operand keeps 16 significant bits: plane 0 the nearest bf16, plane 1 the nearest bf16 of the rest
+      const size_t o0 = q_elem_off(b, kvh, rr, i, Hkv, hd), o1 = q_elem_off(b, kvh, rr, i + half, Hkv, hd);
+      const uint16_t ah = f2bf(a), ch = f2bf(c);
+      qp[o0] = ah;
+      qp[o1] = ch;
+      qp[q_plane + o0] = f2bf(a - bf2f(ah));
+      qp[q_plane + o1] = f2bf(c - bf2f(ch));
     } else if (hh < H + Hkv) {
       uint16_t *tile = kpool + layer_off + ((size_t)page * Hkv + (hh - H)) * (16 * hd);
       tile[k_tile_off(t, i)] = f2bf(a);
@@ -261,12 +267,14 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
 
 // row-major rotated queries [M][H][hd] -> query operand (stand-alone attention entry point)
 __global__ void k_pack_q(int H, int Hkv, int hd, const uint16_t *__restrict__ q, const int32_t *__restrict__ row_req,
-                         const int32_t *__restrict__ row_idx, uint16_t *__restrict__ qp) {
+                         const int32_t *__restrict__ row_idx, uint16_t *__restrict__ qp, size_t q_plane) {
   const int r = blockIdx.x, group = H / Hkv;
   const int b = row_req[r], i_row = row_idx[r];
   for (int idx = threadIdx.x; idx < H * hd; idx += blockDim.x) {
     const int hh = idx / hd, e = idx % hd;
-    qp[q_elem_off(b, hh / group, i_row * group + hh % group, e, Hkv, hd)] = q[(size_t)r * H * hd + idx];
+    const size_t o = q_elem_off(b, hh / group, i_row * group + hh % group, e, Hkv, hd);
+    qp[o] = q[(size_t)r * H * hd + idx];
+    qp[q_plane + o] = 0;  // the caller's queries are bf16 already
   }
 }
 
@@ -306,6 +314,7 @@ int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
 int pack_weight(fsv_ctx *c, const void *src, int which, void **dst) {
   gemm_shape s = shape_of(c, which);
   const size_t units = (size_t)s.NTpad * (s.K / 16) * 64;
+  if (units * 16 > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
   FSV_HIP(c, hipMalloc(dst, units * 16));
   hipLaunchKernelGGL(k_pack_w, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, 0, (const uint16_t *)src, s.N, s.K,
                      s.NTpad, s.mode, c->d.d_ffn, (uint4 *)*dst);
@@ -373,7 +382,8 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
   if ((rc = zalloc(&c->buf_a, rows_pad * widest * 2))) return rc;       // operand-order activations (also x packing)
   if ((rc = zalloc(&c->buf_att, rows_pad * qd * 2))) return rc;
   if ((rc = zalloc(&c->buf_act, rows_pad * d.d_ffn * 2))) return rc;
-  if ((rc = zalloc(&c->buf_q, (size_t)d.max_batch * RTMAX * d.n_kv_heads * d.head_dim * 32 * 2))) return rc;
+  c->q_plane_units = (size_t)d.max_batch * RTMAX * d.n_kv_heads * d.head_dim * 32 / 8;
+  if ((rc = zalloc(&c->buf_q, 2 * c->q_plane_units * 16))) return rc;   // two planes: hi and lo
   // split-K partials: worst case over row counts
   size_t part = 0;
   for (int which = FSV_W_QKV; which <= FSV_W_LM_HEAD; ++which) {
@@ -385,11 +395,12 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
   c->part_bytes = part;
   if ((rc = zalloc(&c->buf_part, part))) return rc;
   if ((rc = fsv_bf16_attn_create(c))) return rc;
+  if ((rc = fsv_bf16_gemm_init(c))) return rc;
   FSV_HIP(c, hipDeviceSynchronize());
   return FSV_OK;
 }
 
-int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s) {
+int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, int M, float *logits, hipStream_t s) {
   const fsv_model_desc &d = c->d;
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32;
   const gemm_shape sq = shape_of(c, FSV_W_QKV), so = shape_of(c, FSV_W_O), sg = shape_of(c, FSV_W_GATE_UP),
@@ -398,8 +409,8 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
   float *part = (float *)c->buf_part;
   const int nthr = min(1024, max(64, fsv_ceil_div(d.d_model / 8, 64) * 64));  // one 8-wide slice per thread
   int rc;
-  fsv_attn_plan pl;
-  if ((rc = fsv_bf16_attn_plan(c, b, &pl, s))) return rc;
+  const fsv_attn_plan &pl = *plan;
+  if ((rc = fsv_bf16_attn_plan_launch(c, b, plan, s))) return rc;
   {
     const int n = M * (d.head_dim / 2);
     hipLaunchKernelGGL(k_rope_table, dim3(fsv_ceil_div(n, 256)), dim3(256), 0, s, M, d.head_dim / 2,
@@ -419,8 +430,8 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipSt
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
       hipLaunchKernelGGL(k_rope_append, dim3(M, fsv_ceil_div(d.n_heads + 2 * d.n_kv_heads, 8)), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim,
                          (const float *)c->rope_tab, part, spq, Mpad, c->row_req, c->row_idx, c->row_pos, b->page_table,
-                         d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, (uint16_t *)b->k_pool,
-                         (uint16_t *)b->v_pool);
+                         d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, c->q_plane_units * 8,
+                         (uint16_t *)b->k_pool, (uint16_t *)b->v_pool);
     }
     if ((rc = fsv_bf16_attn_launch(c, b, &pl, lo, s))) return rc;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s))) return rc;
@@ -469,13 +480,14 @@ int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, floa
   return FSV_OK;
 }
 
-int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s) {
+int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, const fsv_attn_plan *plan, int M, float *out,
+                       hipStream_t s) {
   const fsv_model_desc &d = c->d;
+  const fsv_attn_plan &pl = *plan;
   hipLaunchKernelGGL(k_pack_q, dim3(M), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim, (const uint16_t *)q,
-                     c->row_req, c->row_idx, (uint16_t *)c->buf_q);
-  fsv_attn_plan pl;
+                     c->row_req, c->row_idx, (uint16_t *)c->buf_q, c->q_plane_units * 8);
   int rc;
-  if ((rc = fsv_bf16_attn_plan(c, b, &pl, s))) return rc;
+  if ((rc = fsv_bf16_attn_plan_launch(c, b, plan, s))) return rc;
   if ((rc = fsv_bf16_attn_launch(c, b, &pl, (size_t)layer * layer_stride(c, b->num_pages), s))) return rc;
   const int qd = d.n_heads * d.head_dim;
   const size_t n = (size_t)M * (qd / 8);

@@ -62,8 +62,8 @@ __global__ void k_rope_append(int H, int Hkv, int hd, double theta, int num_page
   const int r = blockIdx.x, half = hd / 2, heads = H + 2 * Hkv;
   const int pos = row_pos[r], b = row_req[r];
   const float *src = qkv + (size_t)r * heads * hd;
-  const int page = page_table[(size_t)b * max_pages + pos / page_size], slot = pos % page_size;
-  (void)num_pages;
+  // page ids live on the device: an id outside the pool is clamped into it (wrong data, never a wild write)
+  const int page = min(max(page_table[(size_t)b * max_pages + pos / page_size], 0), num_pages - 1), slot = pos % page_size;
   for (int t = threadIdx.x; t < heads * half; t += blockDim.x) {
     const int h = t / half, i = t % half;
     const float a = src[h * hd + i], bb = src[h * hd + i + half];
@@ -88,7 +88,7 @@ __global__ void k_rope_append(int H, int Hkv, int hd, double theta, int num_page
 }
 
 // One wave per (row, query head): scores into LDS, softmax, weighted sum of values.
-__global__ __launch_bounds__(64) void k_attention(int H, int Hkv, int hd, int max_pages, int page_size,
+__global__ __launch_bounds__(64) void k_attention(int H, int Hkv, int hd, int max_pages, int num_pages, int page_size,
                                                   const float *__restrict__ qbuf, const int32_t *__restrict__ row_req,
                                                   const int32_t *__restrict__ row_pos,
                                                   const int32_t *__restrict__ page_table,
@@ -102,7 +102,8 @@ __global__ __launch_bounds__(64) void k_attention(int H, int Hkv, int hd, int ma
   const float scale = 1.0f / sqrtf((float)hd);
   float mx = -INFINITY;
   for (int j = lane; j < nkeys; j += 64) {
-    const float *kr = kpool + layer_off + (((size_t)pt[j / page_size] * Hkv + kvh) * page_size + j % page_size) * hd;
+    const int page = min(max(pt[j / page_size], 0), num_pages - 1);
+    const float *kr = kpool + layer_off + (((size_t)page * Hkv + kvh) * page_size + j % page_size) * hd;
     float s = 0.f;
     for (int e = 0; e < hd; ++e) s = fmaf(q[e], kr[e], s);
     s *= scale;
@@ -122,7 +123,8 @@ __global__ __launch_bounds__(64) void k_attention(int H, int Hkv, int hd, int ma
   for (int e = lane; e < hd; e += 64) {
     float acc = 0.f;
     for (int j = 0; j < nkeys; ++j) {
-      const float *vr = vpool + layer_off + (((size_t)pt[j / page_size] * Hkv + kvh) * page_size + j % page_size) * hd;
+      const int page = min(max(pt[j / page_size], 0), num_pages - 1);
+      const float *vr = vpool + layer_off + (((size_t)page * Hkv + kvh) * page_size + j % page_size) * hd;
       acc = fmaf(sc[j], vr[e], acc);
     }
     out[((size_t)r * H + h) * hd + e] = acc / den;
@@ -143,7 +145,7 @@ __global__ void k_kv_copy(int Hkv, int hd, int page_size, int n_layers, int num_
   // one block per (position, layer)
   const int p = blockIdx.x, l = blockIdx.y, pos = pos0 + p;
   const size_t layer_off = (size_t)l * num_pages * Hkv * page_size * hd;
-  const int page = pt[pos / page_size], slot = pos % page_size;
+  const int page = min(max(pt[pos / page_size], 0), num_pages - 1), slot = pos % page_size;
   for (int t = threadIdx.x; t < Hkv * hd; t += blockDim.x) {
     const int h = t / hd, e = t % hd;
     const size_t pi = layer_off + (((size_t)page * Hkv + h) * page_size + slot) * hd + e;
@@ -197,18 +199,28 @@ int fsv_f32_create(fsv_ctx *c, const fsv_weights *w) {
   return FSV_OK;
 }
 
-int fsv_f32_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s) {
-  const fsv_model_desc &d = c->d;
-  const int qd = d.n_heads * d.head_dim, qkvd = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
-  float *x = c->x, *a = (float *)c->buf_a, *qkv = (float *)c->buf_qkv, *qb = (float *)c->buf_q;
-  float *att = (float *)c->buf_att, *gu = (float *)c->buf_gu, *act = (float *)c->buf_act;
+static int max_keys_of(const fsv_batch *b) {
   int max_keys = 0;
   for (int i = 0; i < b->batch; ++i) {
     int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i];
     max_keys = max(max_keys, b->seq_lens_host[i] + g + 1);
   }
-  const size_t lds = sizeof(float) * max_keys;
-  if (lds > 64 * 1024) FSV_FAIL(c, FSV_E_UNSUPPORTED, "fp32 path: %d keys exceed the 16384 it keeps in LDS", max_keys);
+  return max_keys;
+}
+
+int fsv_f32_check(fsv_ctx *c, const fsv_batch *b) {
+  const int max_keys = max_keys_of(b);
+  if (sizeof(float) * (size_t)max_keys > 64 * 1024)
+    FSV_FAIL(c, FSV_E_UNSUPPORTED, "fp32 path: %d keys exceed the 16384 it keeps in LDS", max_keys);
+  return FSV_OK;
+}
+
+int fsv_f32_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStream_t s) {
+  const fsv_model_desc &d = c->d;
+  const int qd = d.n_heads * d.head_dim, qkvd = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
+  float *x = c->x, *a = (float *)c->buf_a, *qkv = (float *)c->buf_qkv, *qb = (float *)c->buf_q;
+  float *att = (float *)c->buf_att, *gu = (float *)c->buf_gu, *act = (float *)c->buf_act;
+  const size_t lds = sizeof(float) * max_keys_of(b);   // fsv_f32_check has bounded it
   hipLaunchKernelGGL(k_embed, dim3(M), dim3(256), 0, s, d.d_model, (const float *)c->embed, c->row_tok, x);
   for (int l = 0; l < d.n_layers; ++l) {
     const fsv_layer_w &L = c->layers[l];
@@ -219,7 +231,7 @@ int fsv_f32_forward(fsv_ctx *c, const fsv_batch *b, int M, float *logits, hipStr
                        (double)d.rope_theta, b->num_pages, d.max_pages_per_req, qkv, c->row_req, c->row_pos,
                        b->page_table, qb, (float *)b->k_pool, (float *)b->v_pool, lo, d.page_size);
     hipLaunchKernelGGL(k_attention, dim3(M, d.n_heads), dim3(64), lds, s, d.n_heads, d.n_kv_heads, d.head_dim,
-                       d.max_pages_per_req, d.page_size, qb, c->row_req, c->row_pos, b->page_table,
+                       d.max_pages_per_req, b->num_pages, d.page_size, qb, c->row_req, c->row_pos, b->page_table,
                        (const float *)b->k_pool, (const float *)b->v_pool, lo, att);
     launch_linear(M, d.d_model, qd, att, (const float *)L.w_o, x, 1, s);
     hipLaunchKernelGGL(k_rmsnorm, dim3(M), dim3(256), 0, s, d.d_model, d.rms_eps, x, (const float *)L.mlp_norm, a);
@@ -252,16 +264,10 @@ int fsv_f32_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float
 
 int fsv_f32_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, int M, float *out, hipStream_t s) {
   const fsv_model_desc &d = c->d;
-  int max_keys = 0;
-  for (int i = 0; i < b->batch; ++i) {
-    int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i];
-    max_keys = max(max_keys, b->seq_lens_host[i] + g + 1);
-  }
-  const size_t lds = sizeof(float) * max_keys;
-  if (lds > 64 * 1024) FSV_FAIL(c, FSV_E_UNSUPPORTED, "fp32 path: %d keys exceed the 16384 it keeps in LDS", max_keys);
+  const size_t lds = sizeof(float) * max_keys_of(b);   // fsv_f32_check has bounded it
   const size_t lo = (size_t)layer * layer_stride(c, b->num_pages);
   hipLaunchKernelGGL(k_attention, dim3(M, d.n_heads), dim3(64), lds, s, d.n_heads, d.n_kv_heads, d.head_dim,
-                     d.max_pages_per_req, d.page_size, (const float *)q, c->row_req, c->row_pos, b->page_table,
+                     d.max_pages_per_req, b->num_pages, d.page_size, (const float *)q, c->row_req, c->row_pos, b->page_table,
                      (const float *)b->k_pool, (const float *)b->v_pool, lo, out);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;

@@ -12,6 +12,13 @@ from paper_2601_00644_amd import synth
 ACCEPT_FLAG = 1e-4     # draws this close to an acceptance threshold may legitimately differ (counted, not failed)
 CDF_FLAG = 1e-6        # same for the emitted token's inverse-CDF edges (normalised mass)
 
+# The tensors the library's bf16 configuration keeps in bf16 between kernels: the normalised activations entering a
+# projection, the new rows' keys and values in the cache, the attention output, the SwiGLU output.  (Queries and
+# probabilities are carried with 16 significant bits inside the attention kernel and are not storage points.)
+# oracle.forward(..., stored=STORED_BF16) is the same fp64 forward with exactly these tensors rounded to bf16.
+STORED_BF16 = oracle.ST_A | oracle.ST_KV | oracle.ST_O | oracle.ST_ACT
+BF16_TOL = 2e-2        # the bf16 logit bar
+
 
 @dataclass
 class Case:
@@ -25,6 +32,8 @@ class Case:
     draft_probs: torch.Tensor     # [G, V] fp32 host
     expected: list = field(default_factory=list)   # oracle.VerifyResult per request
     caches: list = field(default_factory=list)     # oracle caches after the call
+    expected_st: list = field(default_factory=list)   # the same with the bf16 storage points rounded (bf16 models)
+    caches_st: list = field(default_factory=list)
 
 
 def oracle_cache_from_context(cfg, k, v, cap):
@@ -89,20 +98,26 @@ def build_case(cfg, wl: synth.Workload, seed: int, batch=None, ctx_hi=None, weig
 
 
 def run_oracle_on(case: Case, only=None):
+    """The oracle on every request (or those in `only`): the fp64 definition, and for bf16 models also the forward
+    with the bf16 storage points rounded (STORED_BF16)."""
     cfg, req = case.cfg, case.req
-    case.expected, case.caches = [], []
-    for b in range(req.batch):
-        if only is not None and b not in only:
-            case.expected.append(None)
-            case.caches.append(None)
-            continue
-        L, g, o = int(req.seq_lens[b]), int(req.gammas[b]), int(req.draft_offsets[b])
-        kc, vc = oracle_cache_from_context(cfg, case.ctx_k[b], case.ctx_v[b], L + g + 1)
-        r = oracle.verify(cfg, case.weights_np, kc, vc, L, int(req.last_token[b]), case.draft_tokens[o:o + g],
-                          case.draft_probs[o:o + g].numpy(), req.u_accept[o:o + g], float(req.u_sample[b]),
-                          float(req.temperature[b]))
-        case.expected.append(r)
-        case.caches.append((kc, vc))
+    case.expected, case.caches, case.expected_st, case.caches_st = [], [], [], []
+    modes = [(0, case.expected, case.caches)]
+    if cfg.dtype == "bf16":
+        modes.append((STORED_BF16, case.expected_st, case.caches_st))
+    for stored, exp, caches in modes:
+        for b in range(req.batch):
+            if only is not None and b not in only:
+                exp.append(None)
+                caches.append(None)
+                continue
+            L, g, o = int(req.seq_lens[b]), int(req.gammas[b]), int(req.draft_offsets[b])
+            kc, vc = oracle_cache_from_context(cfg, case.ctx_k[b], case.ctx_v[b], L + g + 1)
+            r = oracle.verify(cfg, case.weights_np, kc, vc, L, int(req.last_token[b]), case.draft_tokens[o:o + g],
+                              case.draft_probs[o:o + g].numpy(), req.u_accept[o:o + g], float(req.u_sample[b]),
+                              float(req.temperature[b]), stored=stored)
+            exp.append(r)
+            caches.append((kc, vc))
 
 
 def logits_close(got: np.ndarray, ref: np.ndarray, tol: float):
@@ -113,30 +128,67 @@ def logits_close(got: np.ndarray, ref: np.ndarray, tol: float):
     return bool((ratio <= tol).all()), float(ratio.max())
 
 
-def logits_close_bf16(got: np.ndarray, ref: np.ndarray, tol: float = 2e-2):
-    """The bf16 bar: every element within tol of the row's scale max|ref|, and every row within tol in L2.
+def logit_metrics(got: np.ndarray, ref: np.ndarray, tol: float = BF16_TOL) -> dict:
+    """The ways a block of logits rows is compared with a reference.
 
-    Storing activations in bf16 between kernels (what the bf16 configuration means) by itself leaves an
-    rms logit error of 0.6 % (2 layers) to 1.3 % (24 layers) against an fp64 forward, whatever the
-    kernels do, so single elements cannot be held to tol of their own magnitude; the row scale can.
-    Returns (ok, worst element ratio, worst row L2 ratio).
+    elem : max |got - ref| / max(|ref|, rms(ref row)), per element (each element against its own size, or the row's
+           rms where the element is smaller than that);
+    above: how many elements exceed tol in that measure, and of how many;
+    row  : max |got - ref| / max|ref row| (each element against the row's scale);
+    l2   : max over rows of ||got - ref|| / ||ref||;
+    abs  : max |got - ref|.
     """
-    scale = np.abs(ref).max(axis=-1, keepdims=True)
-    elem = float((np.abs(got - ref) / scale).max())
-    l2 = float((np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)).max())
-    return (elem <= tol and l2 <= tol), elem, l2
+    rms = np.sqrt((ref * ref).mean(axis=-1, keepdims=True))
+    ratio = np.abs(got - ref) / np.maximum(np.abs(ref), rms)
+    return {"elem": float(ratio.max()), "above": int((ratio > tol).sum()), "of": int(ratio.size),
+            "row": float((np.abs(got - ref) / np.abs(ref).max(axis=-1, keepdims=True)).max()),
+            "l2": float((np.linalg.norm(got - ref, axis=-1) / np.linalg.norm(ref, axis=-1)).max()),
+            "abs": float(np.abs(got - ref).max())}
 
 
-def bf16_logit_tol(n_layers: int) -> float:
-    """The bf16 logit bar as a function of depth: 2e-2 up to 4 layers, then 9.6e-3 * sqrt(n_layers).
+def check_bf16_logits(got: np.ndarray, ref64: np.ndarray, ref_st: np.ndarray, what: str = "", flat: bool = True,
+                      tol: float = BF16_TOL) -> dict:
+    """The bf16 logit bar.
 
-    An exact (fp64) forward that merely STORES bf16 where the bf16 configuration does (GEMM inputs, q/k/v,
-    probabilities, attention output, SwiGLU output) differs from the fp64 forward by a worst-row L2 error of
-    0.64 % after 1 layer, 1.6 % after 8, 2.3 % after 16 and 3.3 % after 32 at the 8B shapes (measured with
-    plain torch fp64, independent of the library): about 6.4e-3 * sqrt(n_layers).  No kernel can do better
-    than that against the fp64 oracle, so beyond a few layers the bar is 1.5 times this inherent figure.
+    Against the plain fp64 oracle (ref64): every row within `bar` in L2 and every element within `bar` of the row's
+    scale.  bar = tol (2e-2, flat) for models of up to 16 layers; deeper (`flat` False), max(tol, 1.25 x the same two
+    measures of ref_st against ref64), where ref_st is the oracle's forward with the library's bf16 storage points
+    rounded: the error that bf16 storage alone causes ON THIS REQUEST, computed here by the oracle, which no kernel that
+    stores bf16 can undercut.  Elements above tol of max(|ref|, row rms) are counted and returned, never hidden.
+
+    The library is also measured against ref_st itself (returned and printed, not asserted): the two agree exactly up to
+    the first attention output (the layer-0 cache rows are compared bit for bit elsewhere) and then drift apart, because a
+    difference of one fp32 rounding moves some element across a bf16 rounding boundary at every storage point, and each
+    such flip is a full bf16 step; after a few storage points the two carry independent rounding noise of the same size,
+    so at depth this distance is about as large as either one's distance from the fp64 forward.
+    Returns the metric dicts; raises AssertionError with the numbers on failure.
     """
-    return max(2e-2, 9.6e-3 * float(np.sqrt(n_layers)))
+    m_st, m_64, m_in = logit_metrics(got, ref_st, tol), logit_metrics(got, ref64, tol), logit_metrics(ref_st, ref64, tol)
+    bar = tol if flat else max(tol, 1.25 * max(m_in["l2"], m_in["row"]))
+    rep = {"vs_stored": m_st, "vs_fp64": m_64, "storage_alone": m_in, "bar_fp64": bar}
+    assert m_64["l2"] <= bar and m_64["row"] <= bar, (what, "against the fp64 oracle", m_64, "bar", bar, "storage alone", m_in)
+    return rep
+
+
+def fmt_bf16_report(rep: dict) -> str:
+    a, b, c = rep["vs_stored"], rep["vs_fp64"], rep["storage_alone"]
+    return (f"vs fp64 oracle: row L2 {b['l2']:.2e}, elem/row max {b['row']:.2e} (bar {rep['bar_fp64']:.2e}), "
+            f"elem/max(|ref|,rms) {b['elem']:.2e} with {b['above']}/{b['of']} above 2e-2; "
+            f"bf16 storage alone (oracle): row L2 {c['l2']:.2e}, elem/row max {c['row']:.2e}; "
+            f"vs bf16-storage oracle: row L2 {a['l2']:.2e}")
+
+
+def decision_margins(delta_abs: float, temperature: float):
+    """How far a logit error of at most delta_abs can move an acceptance threshold and a normalised CDF edge.
+
+    p(x) = e^{l_x/T} / sum: ln p moves by at most 2 delta/T, so min(1, p/q) <= 1 moves by at most e^{2 delta/T} - 1, and a
+    normalised running mass by at most twice that (numerator and total both move); residual masses max(0, p - q) can
+    move more when little mass is left, which the factor 4 on the CDF margin allows for.
+    """
+    if temperature <= 0:
+        return ACCEPT_FLAG, CDF_FLAG
+    m = float(np.expm1(2.0 * delta_abs / temperature))
+    return max(ACCEPT_FLAG, m), max(CDF_FLAG, 8.0 * m)
 
 
 def compare_decisions(exp_list, tau, nxt, accept_flag=ACCEPT_FLAG, cdf_flag=CDF_FLAG):
@@ -164,3 +216,46 @@ def compare_decisions(exp_list, tau, nxt, accept_flag=ACCEPT_FLAG, cdf_flag=CDF_
             else:
                 bad.append((b, "next", int(nxt[b]), s.next_token, s.cdf_margin))
     return bad, excused, flagged
+
+
+def check_bf16_requests(cfg, req, expected, expected_st, logits, tau, nxt, flat=True, label=""):
+    """Logits and decisions of the library's bf16 step against the oracle, for the requests that have oracle results.
+
+    Logits: check_bf16_logits.  Decisions: against the fp64 oracle's decisions, exact except draws whose margin
+    (acceptance threshold, CDF edge) is inside what the measured logit difference can move (decision_margins); those are
+    counted and returned.  Returns (per-request reports, excused, flagged)."""
+    reports, worst_delta = {}, 0.0
+    for b, (e, es) in enumerate(zip(expected, expected_st)):
+        if e is None:
+            continue
+        rs, g = int(req.draft_offsets[b]) + b, int(req.gammas[b])
+        rep = check_bf16_logits(logits[rs: rs + g + 1], e.logits, es.logits, f"{label} request {b}", flat)
+        reports[b] = rep
+        worst_delta = max(worst_delta, rep["vs_fp64"]["abs"])
+    t_min = min([float(t) for t in req.temperature if t > 0] or [0.0])
+    acc_m, cdf_m = decision_margins(worst_delta, t_min)
+    bad, excused, flagged = compare_decisions(expected, tau, nxt, acc_m, cdf_m)
+    assert not bad, (label, bad, "margins", acc_m, cdf_m)
+    return reports, excused, flagged
+
+
+def check_bf16_kv(got: np.ndarray, ref_st: np.ndarray, layer0_exact: bool = True, what="", bar: float = BF16_TOL):
+    """Appended KV rows [layers][positions][features] (bf16) against the bf16-storage oracle's cache.
+
+    Layer 0 (embedding, norm, QKV projection, rotation, bf16 store: everything before the first attention) must agree
+    BIT FOR BIT but for isolated elements where fp32 against fp64 accumulation lands on the other side of a bf16 rounding
+    boundary (at most 1 in 200 elements, each by one bf16 step).  Deeper layers drift as the logits do (see
+    check_bf16_logits) and are held per (layer, position) row to `bar` in L2 and per element against the row's scale."""
+    if layer0_exact and got.shape[1] > 0:
+        d0 = got[0] != ref_st[0]
+        assert d0.mean() <= 5e-3, (what, "layer 0 differs in", int(d0.sum()), "of", d0.size)
+        if d0.any():
+            # one bf16 step of the element, or (for elements near zero, whose own step is smaller than the fp32
+            # accumulation error of the projection) 1e-5 of the row's scale
+            allowed = 2.0 ** -7 * np.abs(ref_st[0]) + 1e-5 * np.abs(ref_st[0]).max(axis=-1, keepdims=True)
+            over = np.abs(got[0] - ref_st[0]) / allowed
+            assert over.max() <= 1.0, (what, "layer 0 differs by more than one bf16 step", float(over.max()))
+    g2, r2 = got.reshape(-1, got.shape[-1]), ref_st.reshape(-1, ref_st.shape[-1])
+    m = logit_metrics(g2, r2)
+    assert m["l2"] <= bar and m["row"] <= bar, (what, m, bar)
+    return m

@@ -4,10 +4,14 @@ The oracle cannot score a whole 8B-shape batch in test time, but requests are in
 step of the verification path, so a subset is exact: a few sampled requests are given drafts the
 ORACLE stepped (nothing the oracle consumes comes from the library), the library verifies the full
 batch, and for the sampled requests logits, decisions, rollback and appended KV are compared with
-the oracle (the bf16 bar of test_gpu_verify_bf16.py, scaled with depth: helpers.bf16_logit_tol).  For every request of the batch the accept /
-resample arithmetic is compared exactly on identical logits: the oracle's sampler is run on the
-logits the library produced (flagged draws counted), and the rollback outputs against their closed
-form.  The sampling configuration (logits are inputs) is compared in full.
+the oracle.  The logit bar is helpers.check_bf16_logits: against the plain fp64 oracle a flat 2e-2
+for the 16-layer 1B shapes and, at the 32 layers of the 8B shapes, 1.25 times what bf16 storage alone
+costs on the same request (the oracle's two modes compared in the test); the appended cache rows of
+layer 0 equal the bf16-storage oracle's bit for bit, deeper layers within the same bar.
+For every request of the batch the accept / resample arithmetic is compared exactly on identical
+logits: the oracle's sampler is run on the logits the library produced (flagged draws counted), and
+the rollback outputs against their closed form.  The sampling configuration (logits are inputs) is
+compared in full at all five noise levels.
 """
 import numpy as np
 import pytest
@@ -15,11 +19,11 @@ import torch
 
 from oracle import oracle
 from paper_2601_00644_amd import synth
-from tests.helpers import bf16_logit_tol, compare_decisions, logits_close_bf16
+from tests.helpers import (STORED_BF16, check_bf16_kv, check_bf16_logits, compare_decisions, decision_margins,
+                           fmt_bf16_report)
 
 pytestmark = pytest.mark.gpu
 
-ACCEPT_BF16, CDF_BF16 = 0.1, 1e-2     # margins a 2e-2 logit error can move (see test_gpu_verify_bf16.py)
 
 
 def _oracle_drafts(cfg, wn, wl, req, seed, b):
@@ -42,7 +46,7 @@ def _oracle_drafts(cfg, wn, wl, req, seed, b):
     return d, q, (kc, vc)
 
 
-def _check_workload(wl_name, weights, wn, seed, pick):
+def _check_workload(wl_name, weights, wn, seed, pick, flat):
     from paper_2601_00644_amd import flexverify as fv
     from paper_2601_00644_amd import workload
     wl = synth.WORKLOADS[wl_name]
@@ -79,29 +83,30 @@ def _check_workload(wl_name, weights, wn, seed, pick):
     print(f"{wl_name}: B={B} G={G} accepted {int(tau.sum())}; sampler on identical logits: flagged {flagged}, excused {excused}")
     assert not bad, bad
 
-    # sampled requests: everything against the oracle's own forward
+    # sampled requests: everything against the oracle's own forward, in its two modes
     for b in sampled:
         L, g, o = int(req.seq_lens[b]), int(req.gammas[b]), int(req.draft_offsets[b])
         kc, vc = caches[b]
+        ks, vs = kc.copy(), vc.copy()
         d, q = host_drafts[b]
-        e = oracle.verify(cfg, wn, kc, vc, L, int(req.last_token[b]), d, q.numpy(), req.u_accept[o:o + g],
-                          float(req.u_sample[b]), float(req.temperature[b]))
+        args = (L, int(req.last_token[b]), d, q.numpy(), req.u_accept[o:o + g], float(req.u_sample[b]), float(req.temperature[b]))
+        e = oracle.verify(cfg, wn, kc, vc, *args)
+        es = oracle.verify(cfg, wn, ks, vs, *args, stored=STORED_BF16)
         got = res.logits_out[o + b: o + b + g + 1].cpu().numpy().astype(np.float64)
-        tol = bf16_logit_tol(cfg.n_layers)
-        ok, ratio, l2 = logits_close_bf16(got, e.logits, tol)
-        print(f"  request {b} (L={L}, gamma={g}): logits worst element {ratio:.3e}, worst row L2 {l2:.3e} (bar {tol:.2e}); "
-              f"tau {int(tau[b])} vs {e.sample.tau}")
-        assert ok, (b, ratio, l2)
+        rep = check_bf16_logits(got, e.logits, es.logits, f"{wl_name} request {b}", flat)
+        print(f"  request {b} (L={L}, gamma={g}): {fmt_bf16_report(rep)}; tau {int(tau[b])} vs {es.sample.tau} "
+              f"(fp64 oracle {e.sample.tau})")
         exp = [None] * B
+        exp[b] = es
         exp[b] = e
-        bad, _, _ = compare_decisions(exp, tau, nxt, ACCEPT_BF16, CDF_BF16)
-        assert not bad, bad
-        n_new = int(min(nl[b], e.new_len)) - L
+        acc_m, cdf_m = decision_margins(rep["vs_fp64"]["abs"], float(req.temperature[b]))
+        bad, _, _ = compare_decisions(exp, tau, nxt, acc_m, cdf_m)
+        assert not bad, (bad, acc_m, cdf_m)
+        n_new = int(min(nl[b], es.new_len)) - L
         gk, gv = w.ctx.kv_export(w.k_pool, w.v_pool, req.num_pages, w.page_table[b], L, n_new)
-        for gotkv, ref in ((gk, kc[:, L:L + n_new]), (gv, vc[:, L:L + n_new])):
-            g2 = gotkv.float().cpu().numpy().reshape(cfg.n_layers, -1).astype(np.float64)
-            ok, ratio, l2 = logits_close_bf16(g2, ref.reshape(cfg.n_layers, -1), tol)
-            assert ok, (b, "kv", ratio, l2)
+        for name, gotkv, ref in (("k", gk, ks[:, L:L + n_new]), ("v", gv, vs[:, L:L + n_new])):
+            g2 = gotkv.float().cpu().numpy().astype(np.float64).reshape(cfg.n_layers, n_new, -1)
+            check_bf16_kv(g2, ref.reshape(cfg.n_layers, n_new, -1), True, (b, name), rep["bar_fp64"])
     w.ctx.close()
     del w, res
     torch.cuda.empty_cache()
@@ -119,9 +124,15 @@ def llama8b():
 
 def test_c3_8b_batch16_sampled_requests(llama8b):
     weights, wn = llama8b
-    # the shortest session and the one with the most drafts
-    pick = lambda req: sorted({int(np.argmin(req.seq_lens)), int(np.argmax(req.gammas))})
-    _check_workload("c3_8b_b16", weights, wn, 1, pick)
+    # the shortest and the longest session, the one with the most drafts and the one with the fewest (at least four)
+    def pick(req):
+        want = {int(np.argmin(req.seq_lens)), int(np.argmax(req.seq_lens)), int(np.argmax(req.gammas)), int(np.argmin(req.gammas))}
+        for b in range(req.batch):
+            if len(want) >= 4:
+                break
+            want.add(b)
+        return sorted(want)
+    _check_workload("c3_8b_b16", weights, wn, 1, pick, flat=False)
 
 
 def test_c5_8b_batch128_sampled_requests(llama8b):
@@ -129,25 +140,34 @@ def test_c5_8b_batch128_sampled_requests(llama8b):
     # the shortest session and one of the longest among those with few drafts (the oracle's cost grows with rows)
     def pick(req):
         few = np.nonzero(req.gammas <= 4)[0]
-        return sorted({int(np.argmin(req.seq_lens)), int(few[np.argmax(req.seq_lens[few])])})
-    _check_workload("c5_8b_b128", weights, wn, 1, pick)
+        return sorted({int(np.argmin(req.seq_lens)), int(few[np.argmax(req.seq_lens[few])]), int(np.argmax(req.gammas))})
+    _check_workload("c5_8b_b128", weights, wn, 1, pick, flat=False)
 
 
-@pytest.mark.parametrize("gamma", [2, 5, 8])
-def test_c2_1b_single_request_gamma_sweep(gamma):
-    from dataclasses import replace
+@pytest.fixture(scope="module")
+def llama1b():
     cfg = synth.MODELS["llama1b"]
     weights = synth.make_weights(cfg, 2, device="cuda")
     wn = synth.weights_to_numpy(cfg, weights)
+    yield weights, wn
+    del weights, wn
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("gamma", [2, 3, 4, 5, 6, 7, 8])
+def test_c2_1b_single_request_gamma_sweep(llama1b, gamma):
+    from dataclasses import replace
+    weights, wn = llama1b
     name = f"c2_1b_g{gamma}"
     synth.WORKLOADS[name] = replace(synth.WORKLOADS["c2_1b"], name=name, gamma_lo=gamma, gamma_hi=gamma)
     try:
-        _check_workload(name, weights, wn, 2, lambda req: [0])
+        _check_workload(name, weights, wn, 2, lambda req: [0], flat=True)
     finally:
         del synth.WORKLOADS[name]
 
 
-@pytest.mark.parametrize("sigma,lo,hi", [(0.3, 0.75, 0.99), (0.7, 0.50, 0.90), (1.5, 0.20, 0.70)])
+@pytest.mark.parametrize("sigma,lo,hi", [(0.3, 0.75, 0.99), (0.5, 0.65, 0.95), (0.7, 0.50, 0.90), (1.0, 0.35, 0.80),
+                                         (1.5, 0.20, 0.70)])
 def test_c4_sampler_full_size(sigma, lo, hi):
     """Batch 64, ragged gamma 1..16, vocabulary 152064, bf16 logits ~ N(0,3), temperature 0.7: every request."""
     from paper_2601_00644_amd import flexverify as fv
@@ -177,5 +197,5 @@ def test_c4_sampler_full_size(sigma, lo, hi):
     rate = float(sum(x.sample.tau for x in exp)) / tested
     print(f"sigma {sigma}: acceptance per tested draft {rate:.3f}, flagged {flagged}, excused {excused}")
     assert not bad, bad
-    assert lo <= rate <= hi, rate      # the closed form 2*Phi(-sigma/2) for a diffuse target: 0.88, 0.73, 0.45
+    assert lo <= rate <= hi, rate      # the closed form 2*Phi(-sigma/2) for a diffuse target: 0.88, 0.80, 0.73, 0.62, 0.45
     ctx.close()
