@@ -169,6 +169,20 @@ int fsv_sample(fsv_ctx *ctx, const void *logits, int32_t logits_dtype, const fsv
                const fsv_result *result, void *stream);
 
 /*
+ * fsv_sample for callers that cannot allocate device memory -- code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same inputs, outputs and arithmetic as fsv_sample, but no context: the sampler's
+ * workspace is a fixed 1 MiB device array inside the library (one copy per GPU, held until the process ends), so the
+ * call allocates and frees nothing, on the device or through any library.  Limits: batch <= 128, at most 16 drafts per
+ * request, at most 1024 rows (drafts + requests), vocab <= 327680; beyond them the call returns FSV_E_CAPACITY and
+ * launches nothing.  Every call on a GPU uses that GPU's one array: calls that overlap on one GPU (different streams
+ * or threads) race on it; calls on one stream are ordered and safe.  The array keeps the last call's contents; nothing
+ * in it needs clearing between calls (every entry a call reads it has written first).  No per-call error text
+ * (fsv_last_error needs a context).
+ */
+int fsv_sample_static(int32_t vocab, const void *logits, int32_t logits_dtype, const fsv_batch *batch,
+                      const fsv_result *result, void *stream);
+
+/*
  * KV rollback alone (Sec. IV-C): from seq_lens, draft_offsets and accepted_len (DEVICE [B])
  * compute new_seq_lens and pages_released.  Discarded positions keep stale bytes that no later
  * call reads; the caller returns released pages to its allocator.

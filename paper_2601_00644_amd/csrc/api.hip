@@ -17,8 +17,10 @@ int dev_alloc(fsv_ctx *c, T **p, size_t n) {
   return FSV_OK;
 }
 
+}  // namespace
+
 // Checks shared by verify / sample / attention: CSR shape and capacity.  Returns M (rows) or < 0.
-int check_batch(fsv_ctx *c, const fsv_batch *b, bool need_kv, bool need_sampling) {
+int fsv_check_batch(fsv_ctx *c, const fsv_batch *b, bool need_kv, bool need_sampling) {
   if (!b) FSV_FAIL(c, FSV_E_INVALID_ARG, "batch is NULL");
   if (b->batch < 0) FSV_FAIL(c, FSV_E_INVALID_ARG, "negative batch");
   if (b->batch > c->d.max_batch) FSV_FAIL(c, FSV_E_CAPACITY, "batch %d > max_batch %d", b->batch, c->d.max_batch);
@@ -68,8 +70,6 @@ int check_batch(fsv_ctx *c, const fsv_batch *b, bool need_kv, bool need_sampling
   }
   return M;
 }
-
-}  // namespace
 
 extern "C" {
 
@@ -166,7 +166,7 @@ int fsv_verify(fsv_ctx *c, const fsv_batch *b, const fsv_result *r, void *stream
   if (!c) return FSV_E_INVALID_ARG;
   if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "fsv_verify on a sampler-only context");
   if (!r || !r->next_token || !r->flags || !r->new_seq_lens) FSV_FAIL(c, FSV_E_INVALID_ARG, "result pointers missing");
-  const int M = check_batch(c, b, true, true);
+  const int M = fsv_check_batch(c, b, true, true);
   if (M <= 0) return M;
   if (!b->last_token) FSV_FAIL(c, FSV_E_INVALID_ARG, "last_token required");
   hipStream_t s = (hipStream_t)stream;
@@ -186,7 +186,7 @@ int fsv_sample(fsv_ctx *c, const void *logits, int32_t logits_dtype, const fsv_b
   if (!c) return FSV_E_INVALID_ARG;
   if (!logits || !r || !r->next_token || !r->flags) FSV_FAIL(c, FSV_E_INVALID_ARG, "logits / result pointers missing");
   if (logits_dtype != FSV_F32 && logits_dtype != FSV_BF16) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad logits dtype");
-  const int M = check_batch(c, b, false, true);
+  const int M = fsv_check_batch(c, b, false, true);
   if (M <= 0) return M;
   hipStream_t s = (hipStream_t)stream;
   fsv_batch bb = *b;
@@ -244,7 +244,7 @@ int fsv_attention(fsv_ctx *c, int32_t layer, const void *q, const fsv_batch *b, 
   if (!c) return FSV_E_INVALID_ARG;
   if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "fsv_attention on a sampler-only context");
   if (!q || !out || layer < 0 || layer >= c->d.n_layers) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad argument");
-  const int M = check_batch(c, b, true, false);
+  const int M = fsv_check_batch(c, b, true, false);
   if (M <= 0) return M;
   hipStream_t s = (hipStream_t)stream;
   fsv_attn_plan pl;

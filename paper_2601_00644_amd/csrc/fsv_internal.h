@@ -110,7 +110,7 @@ struct fsv_prof_scope {
   fsv_prof_rec r{};
   bool on, external;
   fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes, bool ext_mode = false)
-      : c(ctx), s(st), on((ctx->prof_mask >> cls) & 1u), external(ext_mode) {
+      : c(ctx), s(st), on(ctx && ((ctx->prof_mask >> cls) & 1u)), external(ext_mode) {
     if (!on) return;
     if (c->prof.size() >= 8192) { on = false; return; }
     r.cls = cls;
@@ -130,6 +130,8 @@ struct fsv_prof_scope {
 static inline int fsv_ceil_div(int a, int b) { return (a + b - 1) / b; }
 
 // ---- entry points of the other translation units ----------------------------------------------
+// api.hip: CSR shape, capacity and pointer checks shared by the entry points.  Returns the number of rows or a status < 0.
+int fsv_check_batch(fsv_ctx *c, const fsv_batch *b, bool need_kv, bool need_sampling);
 // sampler.hip
 int fsv_launch_build_rows(fsv_ctx *c, const fsv_batch *b, int M, hipStream_t s);
 int fsv_launch_sampler(fsv_ctx *c, const void *logits, int logits_dtype, const fsv_batch *b, const fsv_result *r,

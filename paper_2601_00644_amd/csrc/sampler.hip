@@ -15,6 +15,7 @@
 // whose result does not depend on their order, so results are reproducible.
 #include <limits.h>
 #include <math.h>
+#include <mutex>
 
 #include "fsv_internal.h"
 
@@ -654,4 +655,90 @@ int fsv_launch_rollback(fsv_ctx *c, const fsv_batch *b, const int32_t *accepted,
                      b->draft_offsets, accepted, r->new_seq_lens, r->pages_released, c->d.page_size);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// fsv_sample_static: the accept / resample step for callers that cannot allocate device memory.
+// ---------------------------------------------------------------------------------------------
+// The sampler's workspace (row map, per-chunk statistics, per-sub-block masses, nucleus state) lives in a device array
+// of fixed size that is part of the library's code object: every GPU the library runs on holds its own copy at its own
+// address for the life of the process.  The array's name is only a host-side handle; the address kernels can use is
+// asked for once per device (hipGetSymbolAddress, with that device current) and kept.
+#define FSV_STATIC_MAX_BATCH 128
+#define FSV_STATIC_MAX_ROWS 1024
+#define FSV_STATIC_MAX_NSB 160                                            /* vocabulary <= 160 * 2048 = 327680 */
+#define FSV_STATIC_MAX_NC ((FSV_STATIC_MAX_NSB + FSV_SPC - 1) / FSV_SPC)
+#define FSV_STATIC_BYTES (1u << 20)
+
+static __device__ __align__(256) unsigned char scratch[FSV_STATIC_BYTES];
+
+namespace {
+
+struct static_slot {
+  bool ready = false;
+  fsv_ctx ctx;   // a context whose workspace pointers point into this device's copy of `scratch`; owns nothing
+};
+constexpr int kMaxDevices = 64;
+static_slot *g_slots[kMaxDevices] = {};
+std::mutex g_static_mu;
+
+// Carve the workspace out of the array (256-byte aligned pieces, sized for the maxima above).  Returns false if it
+// does not fit, which would be a mistake in the constants above.
+bool carve_static(fsv_ctx &c, unsigned char *base) {
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    void *p = base + off;
+    off += (bytes + 255) & ~(size_t)255;
+    return p;
+  };
+  const size_t R = FSV_STATIC_MAX_ROWS, B = FSV_STATIC_MAX_BATCH, NC = FSV_STATIC_MAX_NC, NSB = FSV_STATIC_MAX_NSB;
+  c.row_req = (int32_t *)take(4 * R); c.row_idx = (int32_t *)take(4 * R); c.row_pos = (int32_t *)take(4 * R);
+  c.row_tok = (int32_t *)take(4 * R);
+  c.pmax = (float *)take(4 * R * NC); c.psum = (double *)take(8 * R * NC); c.parg = (int32_t *)take(4 * R * NC);
+  c.bsum = (double *)take(8 * B * NSB); c.tau_ws = (int32_t *)take(4 * B); c.rowstat = (double *)take(16 * B);
+  c.acc_scratch = (int32_t *)take(4 * B); c.rowkey = (uint32_t *)take(4 * B);
+  c.nuc_prefix = (uint32_t *)take(4 * R); c.nuc_key = (uint32_t *)take(4 * R);
+  c.nuc_above = (unsigned long long *)take(8 * R); c.nuc_total = (unsigned long long *)take(8 * R);
+  c.nuc_S = (double *)take(8 * R); c.nuc_near = (int32_t *)take(4 * R);
+  return off <= FSV_STATIC_BYTES;
+}
+
+}  // namespace
+
+extern "C" int fsv_sample_static(int32_t vocab, const void *logits, int32_t logits_dtype, const fsv_batch *b,
+                                 const fsv_result *r, void *stream) {
+  if (!logits || !b || !r || !r->next_token || !r->flags) return FSV_E_INVALID_ARG;
+  if (logits_dtype != FSV_F32 && logits_dtype != FSV_BF16) return FSV_E_INVALID_ARG;
+  if (vocab <= 0) return FSV_E_INVALID_ARG;
+  if (fsv_ceil_div(vocab, FSV_SBK) > FSV_STATIC_MAX_NSB) return FSV_E_CAPACITY;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return FSV_E_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return FSV_E_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_static_mu);   // the per-device context below is shared by every call on that device
+  if (!g_slots[dev]) g_slots[dev] = new (std::nothrow) static_slot();   // host memory, once per device
+  static_slot *slot = g_slots[dev];
+  if (!slot) return FSV_E_HIP;
+  if (!slot->ready) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return FSV_E_HIP;
+    if (!carve_static(slot->ctx, (unsigned char *)ptr)) return FSV_E_UNSUPPORTED;
+    slot->ctx.d.max_batch = FSV_STATIC_MAX_BATCH;
+    slot->ctx.d.max_gamma = FSV_MAX_GAMMA;
+    slot->ctx.d.page_size = 16;
+    slot->ctx.max_rows = FSV_STATIC_MAX_ROWS;
+    slot->ready = true;
+  }
+  fsv_ctx *c = &slot->ctx;
+  c->d.vocab = vocab;
+  c->nsb = fsv_ceil_div(vocab, FSV_SBK);
+  c->nc = fsv_ceil_div(vocab, FSV_CHUNK);
+  const int M = fsv_check_batch(c, b, false, true);   // batch <= 128, gamma <= 16, rows <= 1024, pointers, temperatures
+  if (M <= 0) return M;
+  hipStream_t s = (hipStream_t)stream;
+  fsv_batch bb = *b;
+  bb.seq_lens = nullptr;
+  bb.last_token = nullptr;
+  int rc = fsv_launch_build_rows(c, &bb, M, s);
+  if (rc) return rc;
+  return fsv_launch_sampler(c, logits, logits_dtype, b, r, M, false, s);
 }

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, os.environ.get("FSV_LIB_NAME", "libflexverify.so"
 F32, BF16 = 0, 1
 W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
-EXPORTS = ["fsv_create", "fsv_destroy", "fsv_verify", "fsv_sample", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
+EXPORTS = ["fsv_create", "fsv_destroy", "fsv_verify", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
            "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
            "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_policy_step_time", "fsv_pager_create",
            "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
@@ -288,6 +288,16 @@ class Context:
             self._check(n, "fsv_profile_read")
         return {lib().fsv_kernel_class_name(buf[i].kernel_class).decode():
                 dict(launches=buf[i].launches, total_ms=buf[i].total_ms, bytes=buf[i].bytes) for i in range(n)}
+
+
+def sample_static(vocab: int, logits: torch.Tensor, batch: DeviceBatch, result: DeviceResult):
+    """fsv_sample_static: the accept / resample step without a context and without any allocation."""
+    dt = BF16 if logits.dtype == torch.bfloat16 else F32
+    assert logits.dtype in (torch.bfloat16, torch.float32) and logits.is_contiguous()
+    b, r = batch.struct(), result.struct()
+    rc = lib().fsv_sample_static(int(vocab), C.c_void_p(logits.data_ptr()), dt, C.byref(b), C.byref(r), _stream())
+    if rc != 0:
+        raise FsvError(rc, "fsv_sample_static", lib().fsv_strerror(rc).decode())
 
 
 def policy_stride(model: LatencyModel, rate: float, gamma_hat: float, k_max: int, tau_model: int = TAU_GEOMETRIC):
