@@ -22,10 +22,26 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes one launch of the dominant kernel (gate|up GEMM at 97 rows) moves, from the two rocprofv3 --pmc passes recorded
-# in profiles/verify_c3_8b_b16_hbm_traffic.txt: FETCH_SIZE 118862.5 counts x 2.0 KiB + WRITE_SIZE 3584.0 counts x 1.0 KiB
-# (the scale factors are what the same counters read for a plain 1 GiB copy).  Only valid for the default workload.
-GATE_UP_TRAFFIC_BYTES = (118862.5 * 2.0 + 3584.0 * 1.0) * 1024.0
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "verify_c3_8b_b16_hbm_traffic.txt")
+
+
+def counter_traffic(workload: str, seed: int, rows: int):
+    """HBM bytes one launch of the dominant kernel (gate|up GEMM) moves, from the tracked rocprofv3 --pmc summary.
+
+    The summary carries one machine-readable line ("# bench: key=value ...") with the mean FETCH_SIZE / WRITE_SIZE counts
+    per dispatch of that kernel, the KiB each count stands for (from the same counters on a plain copy of known size) and
+    the workload, seed and row count it was taken on.  Returns None when the file is missing or was taken on another
+    workload: the figure is never a constant of this script."""
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            line = next(l for l in f if l.startswith("# bench:"))
+        kv = dict(t.split("=", 1) for t in line[len("# bench:"):].split())
+        if kv["workload"] != workload or int(kv["seed"]) != seed or int(kv["rows"]) != rows:
+            return None
+        return (float(kv["fetch_counts"]) * float(kv["fetch_kib_per_count"]) +
+                float(kv["write_counts"]) * float(kv["write_kib_per_count"])) * 1024.0
+    except (OSError, StopIteration, KeyError, ValueError):
+        return None
 
 
 def log(msg):
@@ -72,7 +88,8 @@ def cpu_baseline(cfg, wl, req, weights, seed, budget_rows=9):
     cores = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
     log(f"cpu_baseline: {g} drafts verified in {dt:.2f}s (tau={r.sample.tau}) on {cores} threads")
     return {"value": g / dt, "unit": "verified draft tokens/s", "cores": cores, "kind": "oracle",
-            "sample": f"request {b} of the batch alone (context {L}, gamma {g}, {g + 1} rows): {dt:.2f} s"}
+            "sample": f"ONE request of the batch, not scaled to the batch: request {b} alone (context {L}, gamma {g}, "
+                      f"{g + 1} rows) verified in {dt:.2f} s; the value is its {g} drafts over that time"}
 
 
 def sampler_bench(args, torch, fv, synth):
@@ -111,7 +128,7 @@ def sampler_bench(args, torch, fv, synth):
     tau = res.accepted_len.cpu().numpy()
     out = {"metric": "verified draft tokens/sec on 1 MI355X (rejection sampling alone, vocabulary 152064, batch 64)",
            "value": G / (ms * 1e-3), "unit": "verified draft tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
            "data": "synthetic",
            "config": {"workload": "c4_sampler", "batch": B, "drafts": G, "rows": M, "vocab": V, "temperature": T,
                       "top_p": args.top_p,
@@ -297,7 +314,7 @@ def main():
     roofline = {"bound": "hbm", "kernel": "k_gemm<.,SwiGLU> (gate|up projection, weight streaming)",
                 "achieved": dom_bytes / (dom_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": dom_bytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                "traffic": GATE_UP_TRAFFIC_BYTES if (wl.name == "c3_8b_b16" and args.seed == 1) else None,
+                "traffic": counter_traffic(wl.name, args.seed, M),
                 "launches": dom["launches"], "avg_us": dom_ms * 1e3, "bytes_per_launch": dom_bytes,
                 # the same launch against the matrix cores: 2 * rows * N * K flop over 2.5 PFLOP/s (bf16 dense); far below
                 # the HBM fraction at these row counts, which is why the kernel is priced against HBM

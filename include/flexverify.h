@@ -92,8 +92,8 @@ typedef struct {
  *   FSV_F32 : [position in page][head_dim] for both pools;
  *   FSV_BF16: the order in which the matrix cores consume it, see fsv_kv_import().
  * Use fsv_kv_import()/fsv_kv_export() to move sessions in and out; do not index tiles directly.
- * Zero the pools once after allocating them: positions that were never written are masked out of
- * the softmax but still pass through the matrix cores, so they must not hold NaN or Inf patterns.
+ * Slots that hold no valid position (never written, or left behind by a rollback) may hold any bit pattern,
+ * NaN and Inf included: they are masked out of the softmax and cleared before they reach the matrix cores.
  * The call appends the KV pairs of all M rows (positions seq_lens[b] .. seq_lens[b]+gamma_b).
  */
 typedef struct {
@@ -137,7 +137,9 @@ typedef struct {
 } fsv_result;
 
 /*
- * Create a context: validate the description, copy / re-tile the weights, allocate the workspace.
+ * Create a context for one target model M_t' (the "Require: target model" of Alg. 2; Sec. IV-A: the cloud holds the
+ * evolving target, the edge only a frozen draft): validate the description, copy / re-tile the weights, allocate the
+ * workspace.
  * Supported shapes: page_size 16; head_dim 64 or 128 for FSV_BF16 (any even head_dim for FSV_F32);
  * n_heads a multiple of n_kv_heads with n_heads / n_kv_heads * (max_gamma + 1) <= 96;
  * d_model, d_ffn and n_heads*head_dim multiples of 256 for FSV_BF16; every weight matrix below 4 GiB.
@@ -146,6 +148,8 @@ typedef struct {
  * weights may be NULL only when n_layers == 0.
  */
 int fsv_create(const fsv_model_desc *desc, const fsv_weights *weights, fsv_ctx **out);
+/* Release everything fsv_create allocated (no passage of the paper: lifetime plumbing of the boundary).  The caller's
+ * pools, page tables and sessions are untouched: a session outlives the context that served it (Sec. IV-C). */
 void fsv_destroy(fsv_ctx *ctx);
 
 /*
@@ -160,7 +164,8 @@ void fsv_destroy(fsv_ctx *ctx);
 int fsv_verify(fsv_ctx *ctx, const fsv_batch *batch, const fsv_result *result, void *stream);
 
 /*
- * The accept / resample step alone on caller-provided target logits (DEVICE [M][vocab], row
+ * The accept / resample step alone -- the acceptance loop of Alg. 2 step 2 and its "sample correction token" line, with
+ * the speculative-sampling rule of fsv_verify for T_b > 0 -- on caller-provided target logits (DEVICE [M][vocab], row
  * draft_offsets[b] + b + i scores the token after input row i of request b; dtype FSV_BF16 or
  * FSV_F32).  Uses from batch: batch, draft_offsets(+_host), draft_tokens, draft_probs, u_accept,
  * u_sample, temperature(+_host).  Writes accepted_len, next_token, flags.
@@ -291,6 +296,7 @@ int fsv_pager_trim(fsv_pager *pager, int32_t session, int32_t n_positions);
 int32_t fsv_pager_free_pages(const fsv_pager *pager);
 int32_t fsv_pager_session_pages(const fsv_pager *pager, int32_t session);
 
+/* Text of a status code (no passage of the paper: error convention of the boundary). */
 const char *fsv_strerror(int status);
 /* Last failure's detail message for this context (HOST string owned by the context). */
 const char *fsv_last_error(const fsv_ctx *ctx);
