@@ -20,9 +20,9 @@
  *                   normalised positive part of p - q, bonus token from p when
  *                   every draft is accepted), which keeps the output law equal
  *                   to the target model's (Sec. II, Regime B of Sec. V).  With
- *                   top_p < 1 the target law is first cut to its nucleus (Regime B
- *                   samples with top-p 0.9): the rule then keeps the output law
- *                   equal to the nucleus-cut target law.
+ *                   top_p < 1 and / or top_k > 0 the target law is first cut to its
+ *                   most probable tokens (Regime B samples with top-p 0.9): the rule
+ *                   then keeps the output law equal to the cut target law.
  *   - orc_rollback: the KV rollback of Sec. IV-C (positions from the first
  *                   rejected draft onward are discarded).
  *   - orc_forward_stored : the same forward with chosen intermediate tensors ROUNDED TO
@@ -263,10 +263,14 @@ static void softmax_row(const double *lg, int V, double T, double *p) {
 }
 
 /*
- * Nucleus (top-p) cut of a probability row: order the tokens by probability, keep the most probable ones up to and
- * including the one with which the kept mass first reaches top_p, keep every token tied with that last one as well
- * (so the set does not depend on how ties are ordered), zero the rest and renormalise.  top_p >= 1 keeps the row.
- * *margin (may be NULL) gets min(top_p - mass strictly above the last kept value, mass at or above it - top_p).
+ * Cut of a probability row to its most probable tokens, as Regime B of Sec. V samples (top-p 0.9; top-k is the other
+ * common form of the same cut).  Order the tokens by probability.
+ *   top_k > 0 : keep the top_k most probable tokens and every token tied with the last of them; renormalise.
+ *   top_p < 1 : of what is left, keep the most probable tokens up to and including the one with which the kept mass
+ *               first reaches top_p (of the renormalised row), and every token tied with that last one; renormalise.
+ * Ties are always kept together, so the set never depends on an order among equal probabilities.  top_k <= 0 or >= V
+ * and top_p >= 1 keep the row.  *margin (may be NULL) gets, for the top-p step, min(top_p - mass strictly above the
+ * last kept value, mass at or above it - top_p) in units of the row the step works on.
  */
 typedef struct { double p; int x; } orc_px;
 static int px_desc(const void *a, const void *b) {
@@ -274,21 +278,32 @@ static int px_desc(const void *a, const void *b) {
   if (u->p != v->p) return (u->p < v->p) ? 1 : -1;
   return (u->x > v->x) - (u->x < v->x);
 }
-static int nucleus_row(double *p, int V, double top_p, double *margin) {
+static int cut_row(double *p, int V, int top_k, double top_p, double *margin) {
   if (margin) *margin = INFINITY;
-  if (!(top_p < 1.0)) return 0;
+  const int use_k = top_k > 0 && top_k < V, use_p = top_p < 1.0;
+  if (!use_k && !use_p) return 0;
   orc_px *s = malloc(sizeof(orc_px) * V);
   if (!s) return -1;
-  for (int x = 0; x < V; ++x) { s[x].p = p[x]; s[x].x = x; }
-  qsort(s, V, sizeof(orc_px), px_desc);
-  double cum = 0.0;
-  int k = V - 1;
-  for (int i = 0; i < V; ++i) { cum += s[i].p; if (cum >= top_p) { k = i; break; } }
-  const double cut = s[k].p;
-  double gt = 0.0, ge = 0.0;
-  for (int i = 0; i < V; ++i) { if (s[i].p > cut) gt += s[i].p; if (s[i].p >= cut) ge += s[i].p; }
-  if (margin) { double a = top_p - gt, b = ge - top_p; *margin = (a < b) ? a : b; }
-  for (int x = 0; x < V; ++x) p[x] = (p[x] >= cut) ? p[x] / ge : 0.0;
+  if (use_k) {
+    for (int x = 0; x < V; ++x) { s[x].p = p[x]; s[x].x = x; }
+    qsort(s, V, sizeof(orc_px), px_desc);
+    const double cut = s[top_k - 1].p;
+    double ge = 0.0;
+    for (int x = 0; x < V; ++x) if (p[x] >= cut) ge += p[x];
+    for (int x = 0; x < V; ++x) p[x] = (p[x] >= cut) ? p[x] / ge : 0.0;
+  }
+  if (use_p) {
+    for (int x = 0; x < V; ++x) { s[x].p = p[x]; s[x].x = x; }
+    qsort(s, V, sizeof(orc_px), px_desc);
+    double cum = 0.0;
+    int k = V - 1;
+    for (int i = 0; i < V; ++i) { cum += s[i].p; if (cum >= top_p) { k = i; break; } }
+    const double cut = s[k].p;
+    double gt = 0.0, ge = 0.0;
+    for (int i = 0; i < V; ++i) { if (s[i].p > cut) gt += s[i].p; if (s[i].p >= cut) ge += s[i].p; }
+    if (margin) { double a = top_p - gt, b = ge - top_p; *margin = (a < b) ? a : b; }
+    for (int x = 0; x < V; ++x) p[x] = (p[x] >= cut) ? p[x] / ge : 0.0;
+  }
   free(s);
   return 0;
 }
@@ -331,9 +346,10 @@ static int inverse_cdf(const double *mass, int V, double u, double *margin) {
  *   a_out  : optional [gamma], acceptance probabilities of the drafts that were tested.
  * T == 0 is greedy decoding (Alg. 2): accept while draft == argmax, emit argmax.
  */
-int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
-                    const float *u_acc, float u_smp, double T, double top_p, orc_sample_out *out, double *a_out) {
-  if (V <= 0 || gamma < 0 || T < 0.0 || !(top_p > 0.0)) return -1;
+int orc_sample_cut(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
+                   const float *u_acc, float u_smp, double T, int top_k, double top_p, orc_sample_out *out,
+                   double *a_out) {
+  if (V <= 0 || gamma < 0 || T < 0.0 || !(top_p > 0.0) || top_k < 0) return -1;
   out->tau = 0; out->used_residual = 0; out->accept_margin = INFINITY; out->cdf_margin = INFINITY;
   out->nucleus_margin = INFINITY;
   double nm;
@@ -351,7 +367,7 @@ int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft
     int dtok = draft[i - 1];
     if (dtok < 0 || dtok >= V) { free(p); free(r); return -1; }
     softmax_row(logits + (size_t)(i - 1) * V, V, T, p);
-    if (nucleus_row(p, V, top_p, &nm)) { free(p); free(r); return -1; }
+    if (cut_row(p, V, top_k, top_p, &nm)) { free(p); free(r); return -1; }
     if (nm < out->nucleus_margin) out->nucleus_margin = nm;
     double qd = (double)q[(size_t)(i - 1) * V + dtok];
     double ratio = p[dtok] / qd;              /* qd == 0 gives +inf (or NaN for 0/0) */
@@ -364,7 +380,7 @@ int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft
   }
   out->tau = tau;
   softmax_row(logits + (size_t)tau * V, V, T, p);
-  if (nucleus_row(p, V, top_p, &nm)) { free(p); free(r); return -1; }
+  if (cut_row(p, V, top_k, top_p, &nm)) { free(p); free(r); return -1; }
   if (nm < out->nucleus_margin) out->nucleus_margin = nm;
   if (tau < gamma) {
     double Z = 0.0;
@@ -385,9 +401,14 @@ int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft
   return 0;
 }
 
+int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
+                    const float *u_acc, float u_smp, double T, double top_p, orc_sample_out *out, double *a_out) {
+  return orc_sample_cut(logits, V, gamma, draft, q, u_acc, u_smp, T, 0, top_p, out, a_out);
+}
+
 int orc_sample(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
                const float *u_acc, float u_smp, double T, orc_sample_out *out, double *a_out) {
-  return orc_sample_warp(logits, V, gamma, draft, q, u_acc, u_smp, T, 1.0, out, a_out);
+  return orc_sample_cut(logits, V, gamma, draft, q, u_acc, u_smp, T, 0, 1.0, out, a_out);
 }
 
 /*

@@ -56,6 +56,7 @@ def lib():
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_sample.restype = C.c_int
         _lib.orc_sample_warp.restype = C.c_int
+        _lib.orc_sample_cut.restype = C.c_int
         _lib.orc_rollback.restype = C.c_int
         _lib.orc_linear.restype = None
         _lib.orc_attention.restype = None
@@ -170,10 +171,11 @@ def attention(q, kl, vl, L: int):
     return out
 
 
-def sample(logits, draft, q, u_acc, u_smp: float, T: float, top_p: float = 1.0) -> SampleResult:
+def sample(logits, draft, q, u_acc, u_smp: float, T: float, top_p: float = 1.0, top_k: int = 0) -> SampleResult:
     """Acceptance loop + correction/bonus token for one request (Alg. 2 step 2; speculative sampling for T>0).
 
-    top_p < 1 cuts the target law of every row to its nucleus first (Regime B of Sec. V samples with top-p)."""
+    top_k > 0 and / or top_p < 1 cut the target law of every row to its most probable tokens first (Regime B of Sec. V
+    samples with top-p): top-k, then top-p on what is left, ties kept together."""
     logits = np.ascontiguousarray(logits, np.float64)
     gamma = int(len(draft))
     V = int(logits.shape[1])
@@ -188,11 +190,11 @@ def sample(logits, draft, q, u_acc, u_smp: float, T: float, top_p: float = 1.0) 
         qp = C.c_void_p(0)
     out = _SampleOut()
     a = np.full(gamma, np.nan, np.float64)
-    rc = lib().orc_sample_warp(C.c_void_p(logits.ctypes.data), C.c_int(V), C.c_int(gamma), C.c_void_p(draft.ctypes.data),
-                               qp, C.c_void_p(u_acc.ctypes.data), C.c_float(float(u_smp)), C.c_double(float(T)),
-                               C.c_double(float(top_p)), C.byref(out), C.c_void_p(a.ctypes.data))
+    rc = lib().orc_sample_cut(C.c_void_p(logits.ctypes.data), C.c_int(V), C.c_int(gamma), C.c_void_p(draft.ctypes.data),
+                              qp, C.c_void_p(u_acc.ctypes.data), C.c_float(float(u_smp)), C.c_double(float(T)),
+                              C.c_int(int(top_k)), C.c_double(float(top_p)), C.byref(out), C.c_void_p(a.ctypes.data))
     if rc != 0:
-        raise ValueError("orc_sample_warp rejected its arguments")
+        raise ValueError("orc_sample_cut rejected its arguments")
     return SampleResult(out.tau, out.next_token, bool(out.used_residual), out.accept_margin, out.cdf_margin, a,
                         out.nucleus_margin)
 

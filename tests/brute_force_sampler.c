@@ -18,8 +18,8 @@ typedef struct {
   int32_t tau, next_token, used_residual, pad_;
   double accept_margin, cdf_margin, nucleus_margin;
 } orc_sample_out;
-int orc_sample_warp(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
-                    const float *u_acc, float u_smp, double T, double top_p, orc_sample_out *out, double *a_out);
+int orc_sample_cut(const double *logits, int V, int gamma, const int32_t *draft, const float *q,
+                   const float *u_acc, float u_smp, double T, int top_k, double top_p, orc_sample_out *out, double *a_out);
 
 static int level_offset(int V, int n) { int off = 0, p = 1; for (int k = 0; k < n; ++k) { off += p; p *= V; } return off; }
 
@@ -30,14 +30,18 @@ static int prefix_code(int V, const int32_t *t, int n) {
 }
 
 /* hist is indexed by the code of the emitted sequence (length 1..gamma+1). */
-int brute_force_warp(int V, int gamma, int N, double T, double top_p, const double *target_logits, const float *q_table,
-                     double *hist);
+int brute_force_cut(int V, int gamma, int N, double T, int top_k, double top_p, const double *target_logits,
+                    const float *q_table, double *hist);
 int brute_force(int V, int gamma, int N, double T, const double *target_logits, const float *q_table, double *hist) {
-  return brute_force_warp(V, gamma, N, T, 1.0, target_logits, q_table, hist);
+  return brute_force_cut(V, gamma, N, T, 0, 1.0, target_logits, q_table, hist);
 }
-
 int brute_force_warp(int V, int gamma, int N, double T, double top_p, const double *target_logits, const float *q_table,
                      double *hist) {
+  return brute_force_cut(V, gamma, N, T, 0, top_p, target_logits, q_table, hist);
+}
+
+int brute_force_cut(int V, int gamma, int N, double T, int top_k, double top_p, const double *target_logits,
+                    const float *q_table, double *hist) {
   int nseq = 1;
   for (int k = 0; k < gamma; ++k) nseq *= V;
   double *logits = malloc(sizeof(double) * (gamma + 1) * V);
@@ -65,7 +69,7 @@ int brute_force_warp(int V, int gamma, int N, double T, double top_p, const doub
       for (int k = 0; k < gamma; ++k) { u[k] = (float)(((gg % N) + 0.5) / N); gg /= N; }
       for (int ks = 0; ks < N; ++ks) {
         orc_sample_out out;
-        if (orc_sample_warp(logits, V, gamma, d, q, u, (float)((ks + 0.5) / N), T, top_p, &out, 0) != 0) return -2;
+        if (orc_sample_cut(logits, V, gamma, d, q, u, (float)((ks + 0.5) / N), T, top_k, top_p, &out, 0) != 0) return -2;
         for (int k = 0; k < out.tau; ++k) emit[k] = d[k];
         emit[out.tau] = out.next_token;
         hist[prefix_code(V, emit, out.tau + 1)] += wseq / ((double)ngrid * N);

@@ -339,3 +339,71 @@ def test_accepts_everything_when_draft_equals_the_cut_target():
         u = rng.random(gamma).astype(np.float32) * 0.999
         s = oracle.sample(lg, d, q, u, 0.5, 1.0, top_p=top_p)
         assert s.tau == gamma      # fp32 storage of q can only make q slightly smaller or larger than p'; u < 0.999
+
+
+# ---- top-k cut, alone and followed by top-p ------------------------------------------------------------------
+
+def _topk_cases():
+    path = os.path.join(HERE, "golden", "topk_worked_cases.txt")
+    for line in open(path):
+        if line.startswith("#") or not line.strip():
+            continue
+        name, p, tk, tp, kept, pp = [f.strip() for f in line.split("|")]
+        yield name, np.array([float(x) for x in p.split(",")]), int(tk), float(tp), [int(x) for x in kept.split(",")], \
+            np.array([float(x) for x in pp.split(",")])
+
+
+@pytest.mark.parametrize("case", list(_topk_cases()), ids=lambda c: c[0])
+def test_topk_hand_worked_cases(case):
+    name, p, top_k, top_p, kept, want = case
+    V, N = len(p), 4000
+    lg = np.log(p)[None, :]
+    counts = np.zeros(V)
+    for k in range(N):    # the law of the emitted token of a request without drafts, read off a fine uniform grid
+        s = oracle.sample(lg, np.zeros(0, np.int32), None, np.zeros(0, np.float32), (k + 0.5) / N, 1.0, top_p=top_p, top_k=top_k)
+        counts[s.next_token] += 1
+    law = counts / N
+    assert sorted(np.nonzero(law)[0].tolist()) == kept
+    assert np.abs(law - want).max() < 1.0 / N + 1e-12
+
+
+def _cut_definition(row, top_k, top_p):
+    """The cut written with numpy sorting (a library routine), independent of the oracle's code."""
+    V = len(row)
+    out = row.copy()
+    if 0 < top_k < V:
+        thr = np.sort(out)[::-1][top_k - 1]
+        out = np.where(out >= thr, out, 0.0)
+        out = out / out.sum()
+    if top_p < 1.0:
+        order = np.argsort(-out, kind="stable")
+        k = int(np.searchsorted(np.cumsum(out[order]), top_p, side="left"))
+        thr = out[order[min(k, V - 1)]]
+        out = np.where(out >= thr, out, 0.0)
+        out = out / out.sum()
+    return out
+
+
+@pytest.mark.parametrize("V,gamma,N,top_k,top_p", [(5, 1, 400, 3, 1.0), (4, 2, 128, 2, 1.0), (6, 1, 300, 4, 0.7), (6, 0, 4000, 3, 0.6)])
+def test_output_law_equals_cut_target_bruteforce_topk(V, gamma, N, top_k, top_p):
+    """Speculative sampling on the top-k (and top-p) cut law: the first emitted token follows the cut target law whatever
+    the draft law is, and nothing outside the kept set is ever emitted (brute force over all drafts and uniforms)."""
+    p, q = _random_tables(V, gamma, seed=200 * V + gamma, peaky=1.0)
+    logits = np.log(p)
+    hist = np.zeros(_level_offset(V, gamma + 2), np.float64)
+    drv = _driver()
+    drv.brute_force_cut.restype = C.c_int
+    rc = drv.brute_force_cut(C.c_int(V), C.c_int(gamma), C.c_int(N), C.c_double(1.0), C.c_int(top_k), C.c_double(top_p),
+                             C.c_void_p(logits.ctypes.data), C.c_void_p(q.ctypes.data), C.c_void_p(hist.ctypes.data))
+    assert rc == 0
+    tol = 0.5 * (gamma + 1) / N
+    first = np.zeros(V)
+    for b in range(V):
+        first[b] = hist[1 + b]
+        for m in range(2, gamma + 2):
+            ext = V ** (m - 1)
+            first[b] += hist[_level_offset(V, m) + b * ext: _level_offset(V, m) + (b + 1) * ext].sum()
+    want = _cut_definition(p[0], top_k, top_p)
+    assert np.abs(first - want).max() < 2 * tol + 1e-9, (first, want)
+    assert (first[want == 0] == 0).all()
+    assert int((want > 0).sum()) <= max(top_k, 1) or top_k == 0      # random tables have no ties: at most top_k tokens survive
