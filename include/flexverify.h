@@ -121,6 +121,11 @@ typedef struct {
                                                      tokens whose mass first reaches top_p, with every token tied
                                                      with the last one kept; ignored where T_b = 0                */
   const float *top_p_host;           /* HOST   [B]   same values (NULL with top_p NULL)                           */
+  const int32_t *top_k;              /* DEVICE [B]   top-k cut of the target law (0 or >= vocab = off), or NULL: the k most
+                                                     probable tokens with every token tied with the last of them; applied
+                                                     before top_p, which then works on the renormalised rest (the other
+                                                     common form of Regime B's cut target law); ignored where T_b = 0     */
+  const int32_t *top_k_host;         /* HOST   [B]   same values (NULL with top_k NULL)                           */
 } fsv_batch;
 
 typedef struct {

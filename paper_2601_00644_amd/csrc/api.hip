@@ -55,6 +55,11 @@ int fsv_check_batch(fsv_ctx *c, const fsv_batch *b, bool need_kv, bool need_samp
       for (int i = 0; i < b->batch; ++i)
         if (!(b->top_p_host[i] > 0.f) || !(b->top_p_host[i] <= 1.f))
           FSV_FAIL(c, FSV_E_INVALID_ARG, "top_p of request %d is not in (0, 1]", i);
+    if ((b->top_k != nullptr) != (b->top_k_host != nullptr))
+      FSV_FAIL(c, FSV_E_INVALID_ARG, "top_k needs both its device and its host copy (or neither)");
+    if (b->top_k_host)
+      for (int i = 0; i < b->batch; ++i)
+        if (b->top_k_host[i] < 0) FSV_FAIL(c, FSV_E_INVALID_ARG, "top_k of request %d is negative", i);
   }
   if (need_kv) {
     if (!b->seq_lens || !b->seq_lens_host || !b->page_table || !b->k_pool || !b->v_pool)
@@ -94,7 +99,7 @@ void fsv_destroy(fsv_ctx *c) {
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->rowkey, c->nuc_prefix,
-                  c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->x, c->logits,
+                  c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
                   c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
@@ -146,6 +151,7 @@ int fsv_create(const fsv_model_desc *desc, const fsv_weights *w, fsv_ctx **out) 
   A(dev_alloc(c, &c->rowkey, B));
   A(dev_alloc(c, &c->nuc_prefix, R)); A(dev_alloc(c, &c->nuc_key, R)); A(dev_alloc(c, &c->nuc_above, R));
   A(dev_alloc(c, &c->nuc_total, R)); A(dev_alloc(c, &c->nuc_S, R)); A(dev_alloc(c, &c->nuc_near, R));
+  A(dev_alloc(c, &c->nuc_cabove, R)); A(dev_alloc(c, &c->nuc_kkey, R)); A(dev_alloc(c, &c->nuc_kmass, R));
   if (rc == FSV_OK && d.n_layers > 0) {
     const size_t rows_pad = (R + 31) / 32 * 32;
     A(dev_alloc(c, &c->x, rows_pad * d.d_model));

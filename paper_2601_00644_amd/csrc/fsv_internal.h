@@ -63,8 +63,8 @@ struct fsv_ctx {
   int32_t *acc_scratch = nullptr;  // [max_batch] accepted_len when the caller passes none
   uint32_t *rowkey = nullptr;      // [max_batch] nucleus cut key of the row the token is drawn from (0 = no cut)
   // nucleus (top-p) selection, per logits row: digit-by-digit state, then the cut key, the kept mass, the near flag
-  uint32_t *nuc_prefix = nullptr, *nuc_key = nullptr;
-  unsigned long long *nuc_above = nullptr, *nuc_total = nullptr;
+  uint32_t *nuc_prefix = nullptr, *nuc_key = nullptr, *nuc_cabove = nullptr, *nuc_kkey = nullptr;
+  unsigned long long *nuc_above = nullptr, *nuc_total = nullptr, *nuc_kmass = nullptr;
   double *nuc_S = nullptr;
   int32_t *nuc_near = nullptr;
 

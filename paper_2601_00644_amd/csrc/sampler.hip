@@ -202,9 +202,10 @@ __global__ __launch_bounds__(256) void k_row_stats(const LT *__restrict__ logits
   }
 }
 
-// ---- nucleus (top-p) cut of the target law ------------------------------------------------------------------
-// The cut keeps every token whose logit is at least the cut value: the largest value for which the kept mass reaches
-// top_p (tokens tied at the cut value are all kept, so the set does not depend on an order among ties).  The cut value
+// ---- top-k / nucleus (top-p) cut of the target law ----------------------------------------------------------
+// The cut keeps every token whose logit is at least the cut value: for top-k the value of the top_k-th most probable
+// token, for top-p the largest value for which the kept mass reaches top_p of what the top-k cut left (tokens tied at
+// the cut value are all kept, so the set does not depend on an order among ties).  The cut value
 // is found digit by digit on a monotone 32-bit key of the logit: one pass over the row per digit builds a histogram of
 // the mass per digit value (in LDS, in 2^-40 fixed point, so that the sums do not depend on the order of the atomic
 // adds), and a scan from the top picks the digit at which the kept mass crosses top_p of the total.
@@ -218,26 +219,47 @@ constexpr double kNucScale = 1099511627776.0;  // 2^40
 
 // LEVEL 0: key bits 31..21, LEVEL 1: bits 20..10, LEVEL 2: bits 9..0.  LAST marks the level that fixes the whole key
 // (level 1 for bf16 logits, whose keys have no information below bit 16; level 2 for fp32 logits).  grid = rows.
-template <typename LT, int LEVEL, bool LAST>
+// MODE 1 (top-k) selects the key of the top_k-th most probable token by COUNT (a second, integer histogram) and leaves
+// the cut key and the mass at or above it per row; MODE 0 (top-p) selects by mass among the tokens the top-k cut kept
+// (all of them when the row has none) and writes the row's final cut key and kept mass.  A row that asks for neither
+// gets key 0 (nothing is cut); one that asks for top-k only gets the top-k cut as its final one.
+template <typename LT, int LEVEL, bool LAST, int MODE>
 __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits, int V, int nc,
                                                   const int32_t *__restrict__ row_req,
                                                   const float *__restrict__ temperature, const float *__restrict__ top_p,
-                                                  const float *__restrict__ pmax, uint32_t *__restrict__ st_prefix,
-                                                  unsigned long long *__restrict__ st_above,
-                                                  unsigned long long *__restrict__ st_total, uint32_t *__restrict__ nuc_key,
-                                                  double *__restrict__ nuc_S, int32_t *__restrict__ nuc_near, int vec) {
+                                                  const int32_t *__restrict__ top_k, const float *__restrict__ pmax,
+                                                  uint32_t *__restrict__ st_prefix, unsigned long long *__restrict__ st_above,
+                                                  uint32_t *__restrict__ st_cabove, unsigned long long *__restrict__ st_total,
+                                                  uint32_t *__restrict__ kkey, unsigned long long *__restrict__ kmass,
+                                                  uint32_t *__restrict__ nuc_key, double *__restrict__ nuc_S,
+                                                  int32_t *__restrict__ nuc_near, int vec) {
   constexpr int SHIFT = (LEVEL == 0) ? 21 : (LEVEL == 1 ? 10 : 0), BITS = (LEVEL == 2) ? 10 : 11;
   const int r = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int b = row_req[r];
-  const float T = temperature[b], tp = top_p[b];
-  if (!(T > 0.f) || !(tp < 1.f)) {  // no cut for this row
-    if (LEVEL == 0 && tid == 0) { nuc_key[r] = 0u; nuc_S[r] = -1.0; nuc_near[r] = 0; }
+  const float T = temperature[b], tp = top_p ? top_p[b] : 1.f;
+  const int tk = top_k ? top_k[b] : 0;
+  const bool use_k = T > 0.f && tk > 0 && tk < V, use_p = T > 0.f && tp < 1.f;
+  if (MODE == 1) {
+    if (!use_k) {
+      if (LEVEL == 0 && tid == 0) kkey[r] = 0u;
+      return;
+    }
+  } else if (!use_p) {  // no top-p for this row: its final cut is the top-k one, if any
+    if (LEVEL == 0 && tid == 0) {
+      const uint32_t kk = use_k ? kkey[r] : 0u;
+      nuc_key[r] = kk;
+      nuc_S[r] = kk ? (double)kmass[r] / kNucScale : -1.0;
+      nuc_near[r] = 0;
+    }
     return;
   }
   __shared__ unsigned long long hist[FSV_NUC_BINS];
+  __shared__ uint32_t hcnt[(MODE == 1) ? FSV_NUC_BINS : 1];
   __shared__ float s_m;
-  __shared__ unsigned long long s_sums[64];
-  for (int i = tid; i < FSV_NUC_BINS; i += 1024) hist[i] = 0ull;
+  for (int i = tid; i < FSV_NUC_BINS; i += 1024) {
+    hist[i] = 0ull;
+    if (MODE == 1) hcnt[i] = 0u;
+  }
   if (tid < 64) {
     float mx = -INFINITY;
     for (int c = lane; c < nc; c += 64) mx = fmaxf(mx, pmax[(size_t)r * nc + c]);
@@ -249,6 +271,7 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
   const float m = s_m;
   const exp_scale k = make_exp_scale(kLog2e / (double)T);
   const uint32_t prefix = (LEVEL > 0) ? st_prefix[r] : 0u;
+  const uint32_t lowkey = (MODE == 0 && use_k) ? kkey[r] : 0u;   // top-p works on what the top-k cut kept
   const LT *row = logits + (size_t)r * V;
   for (int i0 = tid * 8; i0 < V; i0 += 1024 * 8) {
     float v[8];
@@ -256,10 +279,14 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
     else loader<LT>::load8(row, i0, V, vec != 0, -INFINITY, v);
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
+      if (i0 + j >= V) continue;   // ids beyond the vocabulary are not tokens (they would count for top-k)
       const uint32_t key = okey(v[j]);
       if (LEVEL > 0 && (key >> (SHIFT + BITS)) != prefix) continue;
+      if (MODE == 0 && key < lowkey) continue;
       const unsigned long long q = (unsigned long long)((double)exp_scaled(v[j] - m, k) * kNucScale + 0.5);
-      if (q) atomicAdd(&hist[(key >> SHIFT) & ((1u << BITS) - 1u)], q);
+      const uint32_t bin = (key >> SHIFT) & ((1u << BITS) - 1u);
+      if (q) atomicAdd(&hist[bin], q);
+      if (MODE == 1) atomicAdd(&hcnt[bin], 1u);
     }
   }
   __syncthreads();
@@ -267,19 +294,51 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
   // lane l owns the 32 digit values below (64 - l) * 32, the highest values in lane 0: masses above each lane's group
   constexpr int PER = FSV_NUC_BINS / 64;
   unsigned long long mine = 0ull;
+  uint32_t minec = 0u;
   const int top = (63 - lane) * PER + PER - 1;
 #pragma unroll
-  for (int i = 0; i < PER; ++i) mine += hist[top - i];
+  for (int i = 0; i < PER; ++i) {
+    mine += hist[top - i];
+    if (MODE == 1) minec += hcnt[top - i];
+  }
   unsigned long long incl = mine;
+  uint32_t inclc = minec;
 #pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const unsigned long long t = __shfl_up(incl, off, 64);
-    if (lane >= off) incl += t;
+    const uint32_t tc = __shfl_up(inclc, off, 64);
+    if (lane >= off) { incl += t; inclc += tc; }
+  }
+  const unsigned long long above0 = (LEVEL == 0) ? 0ull : st_above[r];
+  const unsigned long long before = above0 + (incl - mine);  // mass strictly above this lane's group
+  if (MODE == 1) {
+    const uint32_t cabove0 = (LEVEL == 0) ? 0u : st_cabove[r];
+    const uint32_t beforec = cabove0 + (inclc - minec);     // tokens strictly above this lane's group
+    const unsigned long long ballot = __ballot(beforec + minec >= (uint32_t)tk);
+    // level 0 always has a crossing (tk < V tokens are counted); deeper levels were chosen because they cross
+    const int pick_lane = ballot ? (int)__builtin_ctzll(ballot) : 63;
+    if (lane != pick_lane) return;
+    unsigned long long acc = before;
+    uint32_t accc = beforec;
+    int digit = top - (PER - 1);
+    for (int i = 0; i < PER; ++i) {
+      if (accc + hcnt[top - i] >= (uint32_t)tk || i == PER - 1) { digit = top - i; break; }
+      accc += hcnt[top - i];
+      acc += hist[top - i];
+    }
+    const uint32_t newprefix = (prefix << BITS) | (uint32_t)digit;
+    if (!LAST) {
+      st_prefix[r] = newprefix;
+      st_above[r] = acc;
+      st_cabove[r] = accc;
+    } else {
+      kkey[r] = newprefix << SHIFT;
+      kmass[r] = acc + hist[digit];
+    }
+    return;
   }
   unsigned long long total = (LEVEL == 0) ? __shfl(incl, 63, 64) : st_total[r];
-  const unsigned long long above0 = (LEVEL == 0) ? 0ull : st_above[r];
   const double target = (double)tp * (double)total;
-  const unsigned long long before = above0 + (incl - mine);  // mass strictly above this lane's group
   const bool crosses = (double)(before + mine) >= target;
   const unsigned long long ballot = __ballot(crosses);
   // rounding cannot leave the ballot empty at level 0 (the last lane holds the total); at deeper levels the digit group
@@ -593,22 +652,38 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
     hipLaunchKernelGGL(k_row_stats<LT>, dim3(fsv_ceil_div(nc, 4), M), dim3(256), 0, s, logits, V, nc, c->row_req, b->temperature,
                        c->pmax, c->psum, c->parg, lvec);
   }
-  // Nucleus cut (top-p): only when some request asks for it; one pass over every logits row per key digit.
-  bool nucleus = false;
-  if (b->top_p && b->top_p_host)
-    for (int i = 0; i < B; ++i)
-      nucleus |= b->top_p_host[i] < 1.f && (!b->temperature_host || b->temperature_host[i] > 0.f);
+  // Top-k / top-p cut: only when some request asks for it; one pass over every logits row per key digit and stage.
+  bool any_k = false, any_p = false;
+  for (int i = 0; i < B; ++i) {
+    const bool sampled = !b->temperature_host || b->temperature_host[i] > 0.f;
+    any_p |= sampled && b->top_p && b->top_p_host && b->top_p_host[i] < 1.f;
+    any_k |= sampled && b->top_k && b->top_k_host && b->top_k_host[i] > 0 && b->top_k_host[i] < V;
+  }
+  const bool nucleus = any_k || any_p;
   if (nucleus) {
-    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_STATS, (double)M * V * sizeof(LT) * (sizeof(LT) == 2 ? 2 : 3));
-#define FSV_NUC(LEVEL, LAST)                                                                                          \
-  hipLaunchKernelGGL((k_nucleus<LT, LEVEL, LAST>), dim3(M), dim3(1024), 0, s, logits, V, nc, c->row_req, b->temperature, \
-                     b->top_p, c->pmax, c->nuc_prefix, c->nuc_above, c->nuc_total, c->nuc_key, c->nuc_S, c->nuc_near, lvec)
-    FSV_NUC(0, false);
-    if (sizeof(LT) == 2) {
-      FSV_NUC(1, true);
-    } else {
-      FSV_NUC(1, false);
-      FSV_NUC(2, true);
+    const int levels = (sizeof(LT) == 2) ? 2 : 3;
+    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_STATS, (double)M * V * sizeof(LT) * levels * ((any_k ? 1 : 0) + (any_p ? 1 : 0)));
+#define FSV_NUC(LEVEL, LAST, MODE)                                                                                     \
+  hipLaunchKernelGGL((k_nucleus<LT, LEVEL, LAST, MODE>), dim3(M), dim3(1024), 0, s, logits, V, nc, c->row_req,           \
+                     b->temperature, b->top_p, b->top_k, c->pmax, c->nuc_prefix, c->nuc_above, c->nuc_cabove, c->nuc_total, \
+                     c->nuc_kkey, c->nuc_kmass, c->nuc_key, c->nuc_S, c->nuc_near, lvec)
+    if (any_k) {
+      FSV_NUC(0, false, 1);
+      if (sizeof(LT) == 2) {
+        FSV_NUC(1, true, 1);
+      } else {
+        FSV_NUC(1, false, 1);
+        FSV_NUC(2, true, 1);
+      }
+    }
+    FSV_NUC(0, false, 0);   // also settles the rows that take the top-k cut (or none) as their final one
+    if (any_p) {
+      if (sizeof(LT) == 2) {
+        FSV_NUC(1, true, 0);
+      } else {
+        FSV_NUC(1, false, 0);
+        FSV_NUC(2, true, 0);
+      }
     }
 #undef FSV_NUC
   }
@@ -700,6 +775,8 @@ bool carve_static(fsv_ctx &c, unsigned char *base) {
   c.nuc_prefix = (uint32_t *)take(4 * R); c.nuc_key = (uint32_t *)take(4 * R);
   c.nuc_above = (unsigned long long *)take(8 * R); c.nuc_total = (unsigned long long *)take(8 * R);
   c.nuc_S = (double *)take(8 * R); c.nuc_near = (int32_t *)take(4 * R);
+  c.nuc_cabove = (uint32_t *)take(4 * R); c.nuc_kkey = (uint32_t *)take(4 * R);
+  c.nuc_kmass = (unsigned long long *)take(8 * R);
   return off <= FSV_STATIC_BYTES;
 }
 

@@ -40,7 +40,7 @@ class Batch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_pages", C.c_int32)] + [(n, C.c_void_p) for n in (
         "seq_lens", "seq_lens_host", "last_token", "draft_offsets", "draft_offsets_host", "draft_tokens", "draft_probs",
         "u_accept", "u_sample", "temperature", "temperature_host", "page_table", "k_pool", "v_pool", "top_p",
-        "top_p_host")]
+        "top_p_host", "top_k", "top_k_host")]
 
 
 class Result(C.Structure):
@@ -137,6 +137,8 @@ class DeviceBatch:
     temperature_host: np.ndarray | None = None
     top_p: torch.Tensor | None = None          # [B] nucleus mass per request (None = no cut)
     top_p_host: np.ndarray | None = None
+    top_k: torch.Tensor | None = None          # [B] int32 top-k cut per request (0 = off)
+    top_k_host: np.ndarray | None = None
 
     @property
     def batch(self):
@@ -151,7 +153,7 @@ class DeviceBatch:
                      _ptr(self.last_token), _ptr(self.draft_offsets), _ptr(self.draft_offsets_host),
                      _ptr(self.draft_tokens), _ptr(self.draft_probs), _ptr(self.u_accept), _ptr(self.u_sample),
                      _ptr(self.temperature), _ptr(self.temperature_host), _ptr(self.page_table), _ptr(self.k_pool),
-                     _ptr(self.v_pool), _ptr(self.top_p), _ptr(self.top_p_host))
+                     _ptr(self.v_pool), _ptr(self.top_p), _ptr(self.top_p_host), _ptr(self.top_k), _ptr(self.top_k_host))
 
 
 @dataclass

@@ -249,3 +249,53 @@ def test_many_small_seeded_cases_against_oracle():
     print(f"{total} requests in 80 cases: flagged {flagged_total}, excused {excused_total}")
     for c in ctxs.values():
         c.close()
+
+
+@pytest.mark.parametrize("vocab,batch,gmax,dtype,seed", [
+    (5000, 9, 6, "bf16", 41),        # bf16 logits: the k-th value is usually shared by several tokens (ties kept)
+    (5003, 8, 5, "f32", 42),         # odd vocabulary, fp32 keys (three digits)
+    (152064, 12, 12, "bf16", 43),    # the full vocabulary of the sampling configuration
+])
+def test_top_k_cut_matches_oracle(vocab, batch, gmax, dtype, seed):
+    """top-k per request, alone and followed by top-p, mixed with uncut and greedy requests in one batch."""
+    fv, ctx = _ctx(vocab, batch, 16)
+    case = synth.make_sampler_case(batch, 1, gmax, vocab, 0.5, 0.7, seed, logits_dtype=dtype)
+    top_k = np.array([(0, 50, 5, 1, 2000, vocab + 7)[b % 6] for b in range(batch)], np.int32)
+    top_p = np.array([(1.0, 1.0, 0.8, 1.0, 0.9, 0.9)[b % 6] for b in range(batch)], np.float32)
+    temp = case.temperature.copy()
+    if batch > 7:
+        temp[7] = 0.0                 # a greedy request ignores both cuts
+    t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device="cuda")
+    bt = fv.DeviceBatch(None, None, t(case.draft_offsets), t(case.draft_tokens), case.draft_probs.cuda(),
+                        t(case.u_accept), t(case.u_sample), t(temp), None, None, None, 0, None,
+                        np.ascontiguousarray(case.draft_offsets), np.ascontiguousarray(temp),
+                        t(top_p), top_p, t(top_k), top_k)
+    res = fv.DeviceResult.alloc(batch)
+    ctx.sample(case.logits.cuda(), bt, res)
+    torch.cuda.synchronize()
+    tau, nxt = res.accepted_len.cpu().numpy(), res.next_token.cpu().numpy()
+    lg = case.logits.float().numpy().astype(np.float64)
+    q = case.draft_probs.numpy()
+    exp, near, changed = [], 0, 0
+    for b in range(batch):
+        o, e = int(case.draft_offsets[b]), int(case.draft_offsets[b + 1])
+        args = (lg[o + b: e + b + 1], case.draft_tokens[o:e], q[o:e], case.u_accept[o:e], float(case.u_sample[b]), float(temp[b]))
+        s = oracle.sample(*args, top_p=float(top_p[b]), top_k=int(top_k[b]))
+        if s.nucleus_margin < 1e-6:
+            near += 1
+            exp.append(None)
+            continue
+        exp.append(type("R", (), {"sample": s})())
+        s0 = oracle.sample(*args)
+        changed += (s0.tau, s0.next_token) != (s.tau, s.next_token)
+    bad, excused, flagged = compare_decisions(exp, tau, nxt)
+    print(f"V={vocab}: accepted {tau.sum()}/{case.draft_offsets[-1]}, requests the cut changes {changed}, near {near}, "
+          f"flagged {flagged}, excused {excused}")
+    assert not bad, bad
+    assert changed >= 1
+    # the static entry point takes the same fields
+    res2 = fv.DeviceResult.alloc(batch)
+    fv.sample_static(vocab, case.logits.cuda(), bt, res2)
+    torch.cuda.synchronize()
+    assert torch.equal(res2.accepted_len, res.accepted_len) and torch.equal(res2.next_token, res.next_token)
+    ctx.close()
