@@ -451,10 +451,15 @@ int launch_attention(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, si
                         d.n_kv_heads, group, rows_cap,                                                             \
                      (const uint4 *)c->buf_q, c->q_plane_units, c->attn_part_map, b->page_table, d.max_pages_per_req, b->num_pages,  \
                      kl, vl, layer_bytes, po, pml, out, KBq)
+    const bool deep = c->attn_depth >= 3;   // tiles in flight per wave: 2 (one ahead) or 3 (two ahead)
     if (d.head_dim == 128) {
-      if (pl.rt <= 1) FSV_ATTN_LAUNCH(128, 1, 2); else if (pl.rt == 2) FSV_ATTN_LAUNCH(128, 2, 2); else FSV_ATTN_LAUNCH(128, 3, 2);
+      if (pl.rt <= 1) { if (deep) FSV_ATTN_LAUNCH(128, 1, 3); else FSV_ATTN_LAUNCH(128, 1, 2); }
+      else if (pl.rt == 2) { if (deep) FSV_ATTN_LAUNCH(128, 2, 3); else FSV_ATTN_LAUNCH(128, 2, 2); }
+      else FSV_ATTN_LAUNCH(128, 3, 2);
     } else {
-      if (pl.rt <= 1) FSV_ATTN_LAUNCH(64, 1, 2); else if (pl.rt == 2) FSV_ATTN_LAUNCH(64, 2, 2); else FSV_ATTN_LAUNCH(64, 3, 2);
+      if (pl.rt <= 1) { if (deep) FSV_ATTN_LAUNCH(64, 1, 3); else FSV_ATTN_LAUNCH(64, 1, 2); }
+      else if (pl.rt == 2) { if (deep) FSV_ATTN_LAUNCH(64, 2, 3); else FSV_ATTN_LAUNCH(64, 2, 2); }
+      else { if (deep) FSV_ATTN_LAUNCH(64, 3, 3); else FSV_ATTN_LAUNCH(64, 3, 2); }
     }
 #undef FSV_ATTN_LAUNCH
     FSV_HIP(c, hipGetLastError());
@@ -488,7 +493,13 @@ int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl
 
 int fsv_bf16_attn_create(fsv_ctx *c) {
   const fsv_model_desc &d = c->d;
-  c->attn_wave_target = c->n_cus * kAttnWavesPerCu;
+  int wpc = kAttnWavesPerCu;
+  c->attn_depth = 2;
+  if (const char *e = getenv("FSV_ATTN_TUNE")) {   // "waves per CU,tiles in flight": measurement knob
+    int a = 0, bb = 0;
+    if (sscanf(e, "%d,%d", &a, &bb) == 2 && a >= 1 && a <= 8 && bb >= 2 && bb <= 3) { wpc = a; c->attn_depth = bb; }
+  }
+  c->attn_wave_target = c->n_cus * wpc;
   c->attn_wave_cap = 4 * c->attn_wave_target + 2 * d.max_batch * d.n_kv_heads;  // multi-round schedules: see plan_attention
   const int rows_cap = c->group * (d.max_gamma + 1);
   c->attn_part_bytes = (size_t)c->attn_wave_cap * rows_cap * (d.head_dim + 2) * 4;

@@ -80,6 +80,7 @@ struct fsv_ctx {
   int n_cus = 0;                // compute units of the device the context was created on
   int attn_wave_target = 0;     // waves the attention schedule aims at (resident waves of the device)
   int attn_wave_cap = 0;        // waves the partial buffers hold
+  int attn_depth = 2;           // K/V tiles in flight per attention wave
   int32_t *attn_part_prefix = nullptr, *attn_part_map = nullptr;   // parts before each request; 8-int record per part
 
   // profiling

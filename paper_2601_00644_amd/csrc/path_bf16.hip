@@ -106,9 +106,9 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
     return;
   }
   float *xr = x + (size_t)r * d;
-  float ss = 0.f;
-  for (int k0 = tid * 8; k0 < d; k0 += stride) {
-    float v[8];
+  __shared__ float s_ss[16];
+  // sum of the split slices (in slice order) on top of the residual, or the embedding row
+  auto gather = [&](int k0, float(&v)[8]) {
     if (EMBED) {
       uint4 raw = *reinterpret_cast<const uint4 *>(E + (size_t)row_tok[r] * d + k0);
       uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
@@ -141,22 +141,8 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
         v[0] += pa.x; v[1] += pa.y; v[2] += pa.z; v[3] += pa.w; v[4] += pb.x; v[5] += pb.y; v[6] += pb.z; v[7] += pb.w;
       }
     }
-    *reinterpret_cast<float4 *>(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
-    *reinterpret_cast<float4 *>(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
-  }
-  ss = wave_sum(ss);
-  __shared__ float s_ss[16];
-  if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
-  __syncthreads();
-  float tot = 0.f;
-  for (int i = 0; i < nw; ++i) tot += s_ss[i];  // fixed order
-  const float rinv = 1.0f / sqrtf(tot / (float)d + eps);
-  for (int k0 = tid * 8; k0 < d; k0 += stride) {  // each thread re-reads exactly what it wrote
-    float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
-    float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    uint4 graw = *reinterpret_cast<const uint4 *>(gain + k0);
+  };
+  auto emit = [&](int k0, const float(&v)[8], uint4 graw, float rinv) {
     uint32_t g4[4] = {graw.x, graw.y, graw.z, graw.w};
     uint32_t o[4];
 #pragma unroll
@@ -165,6 +151,47 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
       o[j] = (uint32_t)f2bf(v[2 * j] * rinv * g0) | ((uint32_t)f2bf(v[2 * j + 1] * rinv * g1) << 16);
     }
     a_out[tile_unit(r, k0, KB)] = make_uint4(o[0], o[1], o[2], o[3]);
+  };
+  if (stride == d) {
+    // One 8-wide slice per thread (every shape up to d = 8192): the slice stays in registers across the block-wide sum
+    // of squares, and the gains are fetched together with the inputs, so the kernel is one round of loads, one
+    // reduction and one round of stores.
+    const int k0 = tid * 8;
+    const uint4 graw = *reinterpret_cast<const uint4 *>(gain + k0);
+    float v[8];
+    gather(k0, v);
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
+    *reinterpret_cast<float4 *>(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    __syncthreads();
+    float tot = 0.f;
+    for (int i = 0; i < nw; ++i) tot += s_ss[i];  // fixed order
+    emit(k0, v, graw, 1.0f / sqrtf(tot / (float)d + eps));
+    return;
+  }
+  float ss = 0.f;
+  for (int k0 = tid * 8; k0 < d; k0 += stride) {
+    float v[8];
+    gather(k0, v);
+    *reinterpret_cast<float4 *>(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
+    *reinterpret_cast<float4 *>(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
+  }
+  ss = wave_sum(ss);
+  if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
+  __syncthreads();
+  float tot = 0.f;
+  for (int i = 0; i < nw; ++i) tot += s_ss[i];  // fixed order
+  const float rinv = 1.0f / sqrtf(tot / (float)d + eps);
+  for (int k0 = tid * 8; k0 < d; k0 += stride) {  // each thread re-reads exactly what it wrote
+    float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
+    float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    emit(k0, v, *reinterpret_cast<const uint4 *>(gain + k0), rinv);
   }
 }
 
@@ -213,54 +240,86 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
                                                      int num_pages, size_t layer_off, uint16_t *__restrict__ qp,
                                                      size_t q_plane, uint16_t *__restrict__ kpool,
                                                      uint16_t *__restrict__ vpool) {
-  // grid = (rows, groups of 8 heads of the q|k|v projection)
-  __shared__ float s_cos[64], s_sin[64];
-  const int r = blockIdx.x, half = hd / 2, heads = H + 2 * Hkv, qkvd = heads * hd, group = H / Hkv;
-  const int h0 = blockIdx.y * 8, h1 = min(h0 + 8, heads);
-  const int b = row_req[r], i_row = row_idx[r], pos = row_pos[r];
-  if (threadIdx.x < half) {
-    const float2 cs = reinterpret_cast<const float2 *>(rope_tab)[(size_t)r * half + threadIdx.x];
-    s_cos[threadIdx.x] = cs.x;
-    s_sin[threadIdx.x] = cs.y;
-  }
-  __syncthreads();
-  const int page = min(max(page_table[(size_t)b * max_pages + (pos >> 4)], 0), num_pages - 1), t = pos & 15;
+  // grid = (rows, blocks of 256 threads over the heads of the q|k|v projection); a thread owns four consecutive
+  // rotation pairs (i .. i+3, i+half .. i+half+3) of one head.  The partial sums and the rotation table only need the
+  // row index, so their loads are issued first, next to the row's request / position / page lookups.
+  const int r = blockIdx.x, half = hd / 2, qpt = half / 4, heads = H + 2 * Hkv, qkvd = heads * hd, group = H / Hkv;
+  const int item = blockIdx.y * blockDim.x + threadIdx.x;
+  if (item >= heads * qpt) return;
+  const int hh = item / qpt, i = (item % qpt) * 4;
+  const float *p = part + (size_t)r * qkvd + hh * hd + i;
   const size_t sstr = (size_t)Mpad * qkvd;
-  for (int idx = threadIdx.x; idx < (h1 - h0) * half; idx += blockDim.x) {
-    const int hh = h0 + idx / half, i = idx % half;
-    const float *p = part + (size_t)r * qkvd + hh * hd + i;
-    float a = 0.f, c = 0.f;
+  float4 a = make_float4(0.f, 0.f, 0.f, 0.f), c = a;
+  {
     int s = 0;
     for (; s + 4 <= S; s += 4) {  // four slices in flight; summed in slice order
-      float pa[4], pc[4];
+      float4 pa[4], pc[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { pa[u] = p[(s + u) * sstr]; pc[u] = p[(s + u) * sstr + half]; }
+      for (int u = 0; u < 4; ++u) {
+        pa[u] = *reinterpret_cast<const float4 *>(p + (s + u) * sstr);
+        pc[u] = *reinterpret_cast<const float4 *>(p + (s + u) * sstr + half);
+      }
 #pragma unroll
-      for (int u = 0; u < 4; ++u) { a += pa[u]; c += pc[u]; }
+      for (int u = 0; u < 4; ++u) {
+        a.x += pa[u].x; a.y += pa[u].y; a.z += pa[u].z; a.w += pa[u].w;
+        c.x += pc[u].x; c.y += pc[u].y; c.z += pc[u].z; c.w += pc[u].w;
+      }
     }
-    for (; s < S; ++s) { a += p[s * sstr]; c += p[s * sstr + half]; }
-    if (hh < H + Hkv) {
-      const float ra = a * s_cos[i] - c * s_sin[i], rb = a * s_sin[i] + c * s_cos[i];
-      a = ra;
-      c = rb;
+    for (; s < S; ++s) {
+      const float4 pa = *reinterpret_cast<const float4 *>(p + s * sstr), pc = *reinterpret_cast<const float4 *>(p + s * sstr + half);
+      a.x += pa.x; a.y += pa.y; a.z += pa.z; a.w += pa.w;
+      c.x += pc.x; c.y += pc.y; c.z += pc.z; c.w += pc.w;
     }
-    if (hh < H) {
-      const int kvh = hh / group, rr = i_row * group + hh % group;
-      // the query operand keeps 16 significant bits: plane 0 the nearest bf16, plane 1 the nearest bf16 of the rest
-      const size_t o0 = q_elem_off(b, kvh, rr, i, Hkv, hd), o1 = q_elem_off(b, kvh, rr, i + half, Hkv, hd);
-      const uint16_t ah = f2bf(a), ch = f2bf(c);
-      qp[o0] = ah;
-      qp[o1] = ch;
-      qp[q_plane + o0] = f2bf(a - bf2f(ah));
-      qp[q_plane + o1] = f2bf(c - bf2f(ch));
-    } else if (hh < H + Hkv) {
-      uint16_t *tile = kpool + layer_off + ((size_t)page * Hkv + (hh - H)) * (16 * hd);
-      tile[k_tile_off(t, i)] = f2bf(a);
-      tile[k_tile_off(t, i + half)] = f2bf(c);
-    } else {
-      uint16_t *tile = vpool + layer_off + ((size_t)page * Hkv + (hh - H - Hkv)) * (16 * hd);
-      tile[v_tile_off(t, i)] = f2bf(a);
-      tile[v_tile_off(t, i + half)] = f2bf(c);
+  }
+  const int b = row_req[r], i_row = row_idx[r], pos = row_pos[r];
+  float av[4] = {a.x, a.y, a.z, a.w}, cv[4] = {c.x, c.y, c.z, c.w};
+  if (hh < H + Hkv) {
+    const float4 t0 = *reinterpret_cast<const float4 *>(rope_tab + ((size_t)r * half + i) * 2);      // cos, sin, cos, sin
+    const float4 t1 = *reinterpret_cast<const float4 *>(rope_tab + ((size_t)r * half + i) * 2 + 4);
+    const float cs[4] = {t0.x, t0.z, t1.x, t1.z}, sn[4] = {t0.y, t0.w, t1.y, t1.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float ra = av[j] * cs[j] - cv[j] * sn[j], rb = av[j] * sn[j] + cv[j] * cs[j];
+      av[j] = ra;
+      cv[j] = rb;
+    }
+  }
+  auto pack4 = [](const uint16_t(&h)[4]) { return make_uint2((uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)); };
+  if (hh < H) {
+    // the query operand keeps 16 significant bits: plane 0 the nearest bf16, plane 1 the nearest bf16 of the rest
+    const int kvh = hh / group, rr = i_row * group + hh % group;
+    const size_t o0 = q_elem_off(b, kvh, rr, i, Hkv, hd), o1 = q_elem_off(b, kvh, rr, i + half, Hkv, hd);
+    uint16_t ah[4], ch[4], al[4], cl[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      ah[j] = f2bf(av[j]);
+      ch[j] = f2bf(cv[j]);
+      al[j] = f2bf(av[j] - bf2f(ah[j]));
+      cl[j] = f2bf(cv[j] - bf2f(ch[j]));
+    }
+    *reinterpret_cast<uint2 *>(qp + o0) = pack4(ah);
+    *reinterpret_cast<uint2 *>(qp + o1) = pack4(ch);
+    *reinterpret_cast<uint2 *>(qp + q_plane + o0) = pack4(al);
+    *reinterpret_cast<uint2 *>(qp + q_plane + o1) = pack4(cl);
+    return;
+  }
+  const int page = min(max(page_table[(size_t)b * max_pages + (pos >> 4)], 0), num_pages - 1), t = pos & 15;
+  uint16_t ab[4], cb[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    ab[j] = f2bf(av[j]);
+    cb[j] = f2bf(cv[j]);
+  }
+  if (hh < H + Hkv) {
+    uint16_t *tile = kpool + layer_off + ((size_t)page * Hkv + (hh - H)) * (16 * hd);
+    *reinterpret_cast<uint2 *>(tile + k_tile_off(t, i)) = pack4(ab);          // four consecutive features sit together
+    *reinterpret_cast<uint2 *>(tile + k_tile_off(t, i + half)) = pack4(cb);
+  } else {
+    uint16_t *tile = vpool + layer_off + ((size_t)page * Hkv + (hh - H - Hkv)) * (16 * hd);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      tile[v_tile_off(t, i + j)] = ab[j];
+      tile[v_tile_off(t, i + half + j)] = cb[j];
     }
   }
 }
@@ -428,7 +487,8 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
-      hipLaunchKernelGGL(k_rope_append, dim3(M, fsv_ceil_div(d.n_heads + 2 * d.n_kv_heads, 8)), dim3(256), 0, s, d.n_heads, d.n_kv_heads, d.head_dim,
+      hipLaunchKernelGGL(k_rope_append, dim3(M, fsv_ceil_div((d.n_heads + 2 * d.n_kv_heads) * (d.head_dim / 8), 256)), dim3(256), 0, s,
+                         d.n_heads, d.n_kv_heads, d.head_dim,
                          (const float *)c->rope_tab, part, spq, Mpad, c->row_req, c->row_idx, c->row_pos, b->page_table,
                          d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, c->q_plane_units * 8,
                          (uint16_t *)b->k_pool, (uint16_t *)b->v_pool);
