@@ -33,6 +33,11 @@
  *                   are rounded (round to nearest, ties to even).  With mask 0 it IS
  *                   orc_forward.  The difference between the two is the error that
  *                   bf16 storage alone causes, whatever computes the steps.
+ *   - orc_forward_lora : the same forward for an EVOLVED target (Sec. IV-A: the target's parameters are the frozen
+ *                   backbone plus PEFT adapters injected into the transformer layers; the head -- the last
+ *                   transformer block and the LM head -- stays invariant).  The adapters are LoRA pairs on the
+ *                   attention projections of every layer but the last: y = W x + s B (A x).  Without
+ *                   adapters it IS orc_forward_stored.
  *
  * Parity pins for every function live in tests/test_oracle_*.py.
  */
@@ -184,8 +189,32 @@ void orc_attention(const double *q, int q_stride, const double *kl, const double
  * Query i attends to keys 0 .. L+i (context plus the block up to itself).
  * Returns 0, or -1 on bad arguments / out of memory.
  */
-int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
-                       const int32_t *tokens, int n, double *logits, double *hidden, int stored) {
+/*
+ * One request's LoRA adapter (Sec. IV-A, PEFT parameterisation of the evolving target): for every layer l but the last,
+ * low-rank pairs on the fused q|k|v projection and on the output projection,
+ *   qkv = W_qkv a + scale * B_qkv (A_qkv a),    o_proj = W_o att + scale * B_o (A_o att).
+ * Matrices are [out][in] row-major in the model's weight storage type: A_qkv [rank][d_model], B_qkv [(H+2Hkv)hd][rank],
+ * A_o [rank][H hd], B_o [d_model][rank]; the arrays hold n_layers - 1 pointers each.  The low-rank product is never
+ * rounded (it is not a stored tensor); its input is the same (possibly stored) activation the main projection reads.
+ */
+typedef struct {
+  int rank;
+  double scale;
+  const void *const *a_qkv, *const *b_qkv, *const *a_o, *const *b_o;
+} orc_lora;
+
+/* y[m][:] += scale * B (A x[m][:]) */
+static void lora_add(const void *A, const void *B, int bf16, int out, int in, int rank, double scale, const double *x, int n,
+                     double *y) {
+  double *t = malloc(sizeof(double) * n * rank), *u = malloc(sizeof(double) * n * out);
+  orc_linear(A, bf16, rank, in, x, n, t);
+  orc_linear(B, bf16, out, rank, t, n, u);
+  for (size_t i = 0; i < (size_t)n * out; ++i) y[i] += scale * u[i];
+  free(t); free(u);
+}
+
+int orc_forward_lora(const orc_model *mo, const orc_weights *w, const orc_lora *lora, double *kc, double *vc, int cap, int L,
+                     const int32_t *tokens, int n, double *logits, double *hidden, int stored) {
   const int d = mo->d_model, H = mo->n_heads, Hkv = mo->n_kv_heads, hd = mo->head_dim;
   const int F = mo->d_ffn, V = mo->vocab, bf = mo->weights_bf16;
   if (n <= 0 || L < 0 || L + n > cap || H % Hkv != 0 || hd % 2 != 0) return -1;
@@ -206,6 +235,8 @@ int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, do
     rmsnorm(h, w->attn_norm[l], bf, d, mo->rms_eps, n, a);
     if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
     orc_linear(w->w_qkv[l], bf, qkvdim, d, a, n, qkv);
+    const int adapted = lora && lora->rank > 0 && l < mo->n_layers - 1;   /* the last block is part of the invariant head */
+    if (adapted) lora_add(lora->a_qkv[l], lora->b_qkv[l], bf, qkvdim, d, lora->rank, lora->scale, a, n, qkv);
     for (int i = 0; i < n; ++i) {
       double *row = qkv + (size_t)i * qkvdim;
       int pos = L + i;
@@ -219,6 +250,7 @@ int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, do
     attention_impl(qkv, qkvdim, kl, vl, L, n, H, Hkv, hd, att, stored & ORC_ST_P);
     if (stored & ORC_ST_O) round_rows(att, (size_t)n * qdim);
     orc_linear(w->w_o[l], bf, d, qdim, att, n, upd);
+    if (adapted) lora_add(lora->a_o[l], lora->b_o[l], bf, d, qdim, lora->rank, lora->scale, att, n, upd);
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
     rmsnorm(h, w->mlp_norm[l], bf, d, mo->rms_eps, n, a);
     if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
@@ -240,9 +272,14 @@ int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, do
   return 0;
 }
 
+int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
+                       const int32_t *tokens, int n, double *logits, double *hidden, int stored) {
+  return orc_forward_lora(mo, w, (const orc_lora *)0, kc, vc, cap, L, tokens, n, logits, hidden, stored);
+}
+
 int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
                 const int32_t *tokens, int n, double *logits, double *hidden) {
-  return orc_forward_stored(mo, w, kc, vc, cap, L, tokens, n, logits, hidden, 0);
+  return orc_forward_lora(mo, w, (const orc_lora *)0, kc, vc, cap, L, tokens, n, logits, hidden, 0);
 }
 
 typedef struct {

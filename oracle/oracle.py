@@ -38,6 +38,11 @@ class _Weights(C.Structure):
         (n, C.POINTER(C.c_void_p)) for n in ("attn_norm", "w_qkv", "w_o", "mlp_norm", "w_gate_up", "w_down")]
 
 
+class _Lora(C.Structure):
+    _fields_ = [("rank", C.c_int), ("scale", C.c_double)] + [
+        (n, C.POINTER(C.c_void_p)) for n in ("a_qkv", "b_qkv", "a_o", "b_o")]
+
+
 class _SampleOut(C.Structure):
     _fields_ = [("tau", C.c_int32), ("next_token", C.c_int32), ("used_residual", C.c_int32), ("pad_", C.c_int32),
                 ("accept_margin", C.c_double), ("cdf_margin", C.c_double), ("nucleus_margin", C.c_double)]
@@ -52,6 +57,7 @@ def lib():
         _lib = C.CDLL(build())
         _lib.orc_forward.restype = C.c_int
         _lib.orc_forward_stored.restype = C.c_int
+        _lib.orc_forward_lora.restype = C.c_int
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_sample.restype = C.c_int
@@ -121,11 +127,31 @@ def round_bf16(x: float) -> float:
     return float(lib().orc_round_bf16(float(x)))
 
 
-def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False, stored: int = 0):
+def _lora_struct(cfg, lora):
+    """lora: dict(rank, scale, a_qkv=[...], b_qkv=[...], a_o=[...], b_o=[...]) with n_layers - 1 arrays per list, in the
+    model's weight storage type (float32, or uint16 bf16 bits)."""
+    want = np.uint16 if cfg.dtype == "bf16" else np.float32
+    keep = []
+
+    def per_layer(name):
+        arrs = [np.ascontiguousarray(a) for a in lora[name]]
+        assert len(arrs) == cfg.n_layers - 1 and all(a.dtype == want for a in arrs), name
+        keep.extend(arrs)
+        tab = (C.c_void_p * max(len(arrs), 1))(*[a.ctypes.data for a in arrs])
+        keep.append(tab)
+        return C.cast(tab, C.POINTER(C.c_void_p))
+
+    ls = _Lora(int(lora["rank"]), float(lora["scale"]), per_layer("a_qkv"), per_layer("b_qkv"), per_layer("a_o"),
+               per_layer("b_o"))
+    return ls, keep
+
+
+def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False, stored: int = 0, lora=None):
     """Target forward over tokens placed at positions L.. on top of cache (kc, vc); appends their KV.
 
     Returns logits [n][vocab] fp64 (and the pre-norm hidden state if asked).  Alg. 2 step 2.
     stored: mask of ST_* tensors rounded to bf16 (fp64 arithmetic otherwise); 0 = the plain fp64 definition.
+    lora: this request's adapter of the evolved target (Sec. IV-A), see _lora_struct; None = the base target.
     """
     tokens = np.ascontiguousarray(tokens, np.int32)
     n = int(tokens.shape[0])
@@ -135,11 +161,15 @@ def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False, stored: i
     hidden = np.empty((n, cfg.d_model), np.float64) if want_hidden else None
     ms = _model_struct(cfg)
     ws, keep = _weights_struct(cfg, w)
-    rc = lib().orc_forward_stored(C.byref(ms), C.byref(ws), C.c_void_p(kc.ctypes.data), C.c_void_p(vc.ctypes.data),
-                                  C.c_int(cap), C.c_int(L), C.c_void_p(tokens.ctypes.data), C.c_int(n),
-                                  C.c_void_p(logits.ctypes.data),
-                                  C.c_void_p(hidden.ctypes.data) if want_hidden else C.c_void_p(0), C.c_int(int(stored)))
-    del keep
+    lp, keep2 = (None, None)
+    if lora is not None:
+        ls, keep2 = _lora_struct(cfg, lora)
+        lp = C.byref(ls)
+    rc = lib().orc_forward_lora(C.byref(ms), C.byref(ws), lp, C.c_void_p(kc.ctypes.data), C.c_void_p(vc.ctypes.data),
+                                C.c_int(cap), C.c_int(L), C.c_void_p(tokens.ctypes.data), C.c_int(n),
+                                C.c_void_p(logits.ctypes.data),
+                                C.c_void_p(hidden.ctypes.data) if want_hidden else C.c_void_p(0), C.c_int(int(stored)))
+    del keep, keep2
     if rc != 0:
         raise ValueError("orc_forward rejected its arguments")
     return (logits, hidden) if want_hidden else logits
@@ -217,10 +247,10 @@ class VerifyResult:
 
 
 def verify(cfg, w, kc, vc, L: int, last_token: int, draft, q, u_acc, u_smp: float, T: float,
-           stored: int = 0) -> VerifyResult:
+           stored: int = 0, lora=None) -> VerifyResult:
     """One request of the verification step: score [last_token, drafts], accept/reject, roll back."""
     toks = np.concatenate([[last_token], np.asarray(draft, np.int64)]).astype(np.int32)
-    logits = forward(cfg, w, kc, vc, L, toks, stored=stored)
+    logits = forward(cfg, w, kc, vc, L, toks, stored=stored, lora=lora)
     s = sample(logits, draft, q, u_acc, u_smp, T)
     nl, pr = rollback(L, len(draft), s.tau, cfg.page_size)
     return VerifyResult(logits, s, nl, pr)

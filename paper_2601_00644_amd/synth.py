@@ -127,6 +127,27 @@ def make_weights(cfg: ModelCfg, seed: int, device="cpu", std: float = 0.02) -> d
     return w
 
 
+def make_lora(cfg: ModelCfg, rank: int, seed: int, adapter: int, device="cpu", std_a: float = 0.05, std_b: float = 0.05) -> dict:
+    """A seeded LoRA adapter for every layer but the last (the paper's evolving target keeps its last block and LM head
+    frozen): random A ~ N(0, std_a) and B ~ N(0, std_b) on the fused q|k|v projection and the output projection, in the
+    model's storage dtype.  Trained adapters start from B = 0; random B stands in for a fine-tuned one."""
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    qd = cfg.n_heads * cfg.head_dim
+    shapes = {"a_qkv": (rank, cfg.d_model), "b_qkv": (cfg.qkv_dim, rank), "a_o": (rank, qd), "b_o": (cfg.d_model, rank)}
+    out = {"rank": rank, "scale": 2.0}
+    for j, (name, shape) in enumerate(shapes.items()):
+        std = std_a if name.startswith("a_") else std_b
+        out[name] = [(torch.randn(shape, generator=_gen(seed, 50_000 + 1000 * adapter + 10 * l + j, device), device=device,
+                                  dtype=torch.float32) * std).to(tdt) for l in range(cfg.n_layers - 1)]
+    return out
+
+
+def lora_to_numpy(cfg: ModelCfg, lora: dict) -> dict:
+    """Host copy of an adapter in the layout the oracle takes."""
+    conv = (lambda t: t.view(torch.int16).cpu().numpy().view(np.uint16)) if cfg.dtype == "bf16" else (lambda t: t.cpu().numpy())
+    return {k: ([conv(t) for t in v] if isinstance(v, list) else v) for k, v in lora.items()}
+
+
 def weights_to_numpy(cfg: ModelCfg, w: dict) -> dict:
     """Host copies in the layout the oracle takes: float32, or uint16 bf16 bit patterns."""
     if cfg.dtype == "bf16":

@@ -298,3 +298,65 @@ def test_stored_kv_rows_are_bf16_values_and_the_context_is_untouched():
     _, (kc0, _) = run(0)
     new0 = torch.from_numpy(kc0[:, 21:25].copy())
     assert not torch.equal(new0.to(torch.bfloat16).double(), new0)        # without the flag they are not
+
+
+# ---------------------------------------------------------------------------------------------
+# the evolved target: LoRA adapters on the attention projections (orc_forward_lora)
+# ---------------------------------------------------------------------------------------------
+
+def _lora_case(name="minif32", seed=9, L=23, n=5, rank=8):
+    cfg = synth.MODELS[name]
+    w = synth.make_weights(cfg, seed, std=0.08)
+    wn = synth.weights_to_numpy(cfg, w)
+    lora = synth.make_lora(cfg, rank, seed, 0)
+    k, v = synth.make_kv_context(cfg, L, seed, 0)
+    toks = np.random.default_rng(seed).integers(0, cfg.vocab, n).astype(np.int32)
+
+    def run(weights, lo):
+        kc, vc = oracle.new_cache(cfg, L + n)
+        kc[:, :L], vc[:, :L] = synth.kv_to_f64(k), synth.kv_to_f64(v)
+        return oracle.forward(cfg, weights, kc, vc, L, toks, lora=lo), (kc, vc)
+    return cfg, w, wn, lora, run
+
+
+def test_lora_equals_the_dense_forward_with_merged_weights():
+    # y = W x + s B (A x) is the dense projection with W + s B A: merge the adapter into fp32 copies of the weights of
+    # every layer but the last (in fp64, then to fp32) and run the PLAIN forward; logits and appended KV must agree
+    cfg, w, wn, lora, run = _lora_case()
+    ln = synth.lora_to_numpy(cfg, lora)
+    got, (kc, vc) = run(wn, ln)
+    merged = dict(wn)
+    for l in range(cfg.n_layers - 1):
+        for wk, ak, bk in ((f"w_qkv.{l}", "a_qkv", "b_qkv"), (f"w_o.{l}", "a_o", "b_o")):
+            m = wn[wk].astype(np.float64) + lora["scale"] * ln[bk][l].astype(np.float64) @ ln[ak][l].astype(np.float64)
+            merged[wk] = m.astype(np.float32)
+    want, (kc2, vc2) = run(merged, None)
+    plain, _ = run(wn, None)
+    scale = np.abs(want).max()
+    assert np.abs(got - want).max() < 2e-6 * scale                      # fp32 rounding of the merged weights only
+    assert np.abs(kc - kc2).max() < 2e-6 * np.abs(kc2).max() and np.abs(vc - vc2).max() < 2e-6 * np.abs(vc2).max()
+    assert np.abs(got - plain).max() > 1e-2 * scale                     # and the adapter really changes the target
+
+
+def test_lora_special_cases():
+    cfg, w, wn, lora, run = _lora_case()
+    ln = synth.lora_to_numpy(cfg, lora)
+    plain, _ = run(wn, None)
+    # B = 0 (a freshly initialised adapter) and scale = 0 are the base target, bit for bit
+    zero_b = dict(ln, b_qkv=[np.zeros_like(a) for a in ln["b_qkv"]], b_o=[np.zeros_like(a) for a in ln["b_o"]])
+    assert np.array_equal(run(wn, zero_b)[0], plain)
+    assert np.array_equal(run(wn, dict(ln, scale=0.0))[0], plain)
+    # the head is invariant: the last block has no adapter, so a one-layer model ignores the adapter altogether
+    cfg1 = dataclasses.replace(cfg, n_layers=1)
+    w1 = {k: v for k, v in wn.items() if not k.split(".")[-1].isdigit() or int(k.split(".")[-1]) < 1}
+    kc, vc = oracle.new_cache(cfg1, 8)
+    toks = np.arange(3, dtype=np.int32)
+    a = oracle.forward(cfg1, w1, kc.copy(), vc.copy(), 0, toks)
+    b = oracle.forward(cfg1, w1, kc.copy(), vc.copy(), 0, toks, lora=dict(ln, a_qkv=[], b_qkv=[], a_o=[], b_o=[]))
+    assert np.array_equal(a, b)
+    # linearity in the scale: (logits change) is not linear through the network, but the projection itself is -- checked on
+    # the first layer's appended keys, which depend on the adapter only through qkv = W a + s B A a
+    k1 = run(wn, dict(ln, scale=1.0))[1][0][0]
+    k2 = run(wn, dict(ln, scale=2.0))[1][0][0]
+    k0 = run(wn, None)[1][0][0]
+    assert np.allclose(k2 - k0, 2.0 * (k1 - k0), rtol=1e-9, atol=1e-12)
