@@ -250,6 +250,10 @@ def main():
                     help="page-table layout of the KV sessions (default: the workload's own, interleaved)")
     ap.add_argument("--top-p", type=float, default=1.0,
                     help="nucleus mass applied to the target law of every request (1 = off, the configurations' setting)")
+    ap.add_argument("--adapters", type=int, default=0,
+                    help="serve an evolved target: load this many random LoRA adapters (rank --rank) and spread the requests over "
+                         "them and the base target (0 = base target only, the configurations' setting)")
+    ap.add_argument("--rank", type=int, default=16)
     ap.add_argument("--breakdown", action="store_true", help="also time every kernel class (one extra untimed pass)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three plain 1 GiB device copies, the known-size reference the HBM counters are scaled by")
@@ -284,6 +288,10 @@ def main():
     if args.top_p < 1.0:
         w.batch.top_p_host = np.full(B, args.top_p, np.float32)
         w.batch.top_p = torch.as_tensor(w.batch.top_p_host, device="cuda")
+
+    if args.adapters > 0:
+        ctx.lora_load([synth.make_lora(cfg, args.rank, args.seed, a, device="cuda") for a in range(args.adapters)])
+        w.batch.adapter = torch.as_tensor(np.arange(B, dtype=np.int32) % (args.adapters + 1) - 1, device="cuda")
 
     def step():
         ctx.verify(w.batch, res)
@@ -325,6 +333,7 @@ def main():
            "data": "synthetic",
            "config": {"workload": wl.name, "model_shape": cfg.name, "batch": B, "drafts": G, "rows": M,
                       "kv_tokens": int(req.seq_lens.sum()), "temperature": wl.temperature, "top_p": args.top_p, "draft_noise_sigma": wl.sigma,
+                      "adapters": args.adapters, "adapter_rank": args.rank if args.adapters else 0,
                       "accepted_drafts": int(tau.sum()), "emitted_tokens": int(tau.sum()) + B},
            "roofline": roofline,
            "ms_per_step_p10_p50_p90": [float(np.percentile(per_step, p)) for p in (10, 50, 90)],

@@ -126,6 +126,9 @@ typedef struct {
                                                      before top_p, which then works on the renormalised rest (the other
                                                      common form of Regime B's cut target law); ignored where T_b = 0     */
   const int32_t *top_k_host;         /* HOST   [B]   same values (NULL with top_k NULL)                           */
+  const int32_t *adapter;            /* DEVICE [B]   which adapter of fsv_lora_load() the request's target version uses
+                                                     (the evolved target of Sec. IV-A); any value outside 0 .. n_adapters-1
+                                                     (say -1) = the base target; NULL = base target for everyone         */
 } fsv_batch;
 
 typedef struct {
@@ -156,6 +159,25 @@ int fsv_create(const fsv_model_desc *desc, const fsv_weights *weights, fsv_ctx *
 /* Release everything fsv_create allocated (no passage of the paper: lifetime plumbing of the boundary).  The caller's
  * pools, page tables and sessions are untouched: a session outlives the context that served it (Sec. IV-C). */
 void fsv_destroy(fsv_ctx *ctx);
+
+/*
+ * Adapters of the evolving target (Sec. IV-A: the target's parameters are the frozen backbone plus PEFT adapters injected
+ * into the transformer layers; the last transformer block and the LM head stay invariant, which is what keeps a frozen
+ * edge draft compatible).  An adapter is a LoRA pair per layer l < n_layers - 1 on the fused q|k|v projection and on the
+ * output projection:  qkv = W_qkv a + scale B_qkv (A_qkv a),  o = W_o att + scale B_o (A_o att),  with the low-rank
+ * products kept in fp32.  One batch may mix requests of different target versions (fsv_batch.adapter).
+ * All matrices are DEVICE, row-major [out][in], bf16: A_qkv [rank][d_model], B_qkv [(n_heads + 2 n_kv_heads) head_dim][rank],
+ * A_o [rank][n_heads head_dim], B_o [d_model][rank]; the four tables are HOST arrays of (n_layers - 1) * n_adapters DEVICE
+ * pointers, entry l * n_adapters + a.  fsv_lora_load copies everything (the caller may free its matrices afterwards) and
+ * replaces any set loaded before; lora NULL or n_adapters 0 removes the adapters.  FSV_BF16 models, rank 8 / 16 / 32 / 64.
+ * Not to be called while a call on the context is in flight.
+ */
+typedef struct {
+  int32_t n_adapters, rank;
+  const float *scale;                 /* HOST [n_adapters]: the factor s (alpha / rank of the LoRA literature) */
+  const void *const *a_qkv, *const *b_qkv, *const *a_o, *const *b_o;
+} fsv_lora;
+int fsv_lora_load(fsv_ctx *ctx, const fsv_lora *lora);
 
 /*
  * The verification step (Alg. 2 step 2 with the KV append / rollback of Sec. IV-C) for a batch.

@@ -100,7 +100,8 @@ void fsv_destroy(fsv_ctx *c) {
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->rowkey, c->nuc_prefix,
                   c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
-                  c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map};
+                  c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map,
+                  c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   for (auto &L : c->layers) {
@@ -234,6 +235,23 @@ int fsv_kv_import(fsv_ctx *c, void *k_pool, void *v_pool, int32_t num_pages, con
 int fsv_kv_export(fsv_ctx *c, const void *k_pool, const void *v_pool, int32_t num_pages, const int32_t *pt,
                   int32_t pos0, int32_t n_pos, void *dst_k, void *dst_v, void *stream) {
   return kv_copy(c, (void *)k_pool, (void *)v_pool, num_pages, pt, pos0, n_pos, dst_k, dst_v, false, stream);
+}
+
+int fsv_lora_load(fsv_ctx *c, const fsv_lora *lo) {
+  if (!c) return FSV_E_INVALID_ARG;
+  if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "fsv_lora_load on a sampler-only context");
+  if (c->d.dtype != FSV_BF16) FSV_FAIL(c, FSV_E_UNSUPPORTED, "adapters are implemented for FSV_BF16 models");
+  if (lo && lo->n_adapters != 0) {
+    if (lo->n_adapters < 0 || lo->n_adapters > 1024) FSV_FAIL(c, FSV_E_INVALID_ARG, "n_adapters must be in 0..1024");
+    if (lo->rank != 8 && lo->rank != 16 && lo->rank != 32 && lo->rank != 64)
+      FSV_FAIL(c, FSV_E_UNSUPPORTED, "adapter rank %d: 8, 16, 32 and 64 are implemented", lo->rank);
+    if (c->d.d_model > 8192) FSV_FAIL(c, FSV_E_UNSUPPORTED, "adapters need d_model <= 8192");
+    if (!lo->scale || !lo->a_qkv || !lo->b_qkv || !lo->a_o || !lo->b_o) FSV_FAIL(c, FSV_E_INVALID_ARG, "NULL adapter table");
+    const int cnt = (c->d.n_layers - 1) * lo->n_adapters;
+    for (int i = 0; i < cnt; ++i)
+      if (!lo->a_qkv[i] || !lo->b_qkv[i] || !lo->a_o[i] || !lo->b_o[i]) FSV_FAIL(c, FSV_E_INVALID_ARG, "NULL adapter matrix %d", i);
+  }
+  return fsv_bf16_lora_load(c, lo);
 }
 
 int fsv_linear(fsv_ctx *c, int32_t which, int32_t layer, const void *x, int32_t M, float *y, void *stream) {

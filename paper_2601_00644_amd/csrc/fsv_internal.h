@@ -83,6 +83,12 @@ struct fsv_ctx {
   int attn_depth = 2;           // K/V tiles in flight per attention wave
   int32_t *attn_part_prefix = nullptr, *attn_part_map = nullptr;   // parts before each request; 8-int record per part
 
+  // LoRA adapters of the evolved target (bf16 path): tables [layer < n_layers - 1][adapter][...], library-owned
+  int lora_n = 0, lora_rank = 0;
+  uint16_t *lora_aq = nullptr, *lora_bq = nullptr, *lora_ao = nullptr, *lora_bo = nullptr;
+  float *lora_scale = nullptr;   // [lora_n]
+  float *lora_t = nullptr;       // [max_rows][64] A_qkv x of the rows of the current call
+
   // profiling
   uint32_t prof_mask = 0;
   std::vector<fsv_prof_rec> prof;
@@ -167,6 +173,7 @@ int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, 
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
 int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *logits, hipStream_t s);
 int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float *y, hipStream_t s);
+int fsv_bf16_lora_load(fsv_ctx *c, const fsv_lora *lo);
 int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *out,
                        hipStream_t s);
 int fsv_bf16_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,

@@ -95,11 +95,63 @@ enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };  // epilogues of fsv_bf16
 // ---------------------------------------------------------------------------------------------
 // residual stream: x (+)= sum of split partials (or embedding), RMSNorm, emit the next GEMM's operand
 // ---------------------------------------------------------------------------------------------
-template <int EMBED>
+// LoRA adapters of the evolved target (Sec. IV-A: frozen backbone plus adapters; the last block and the LM head carry
+// none): y = W x + s B (A x) on the fused q|k|v projection and on the output projection.  The low-rank side never goes
+// through the big GEMM: "shrink" (t = A x, rank numbers per row) and "expand" (+= s B t) run inside the per-row kernels
+// that produce and consume the projection's operands, where a row has one adapter and its matrices are read
+// contiguously; the products are fp32 and never rounded.
+struct lora_args {
+  const int32_t *row_req = nullptr, *adapter = nullptr;   // adapter id per request (outside [0, n): none)
+  int n = 0, rank = 0;
+  const float *scale = nullptr;                           // [n]
+  const uint16_t *aq = nullptr;                           // LQ: A_qkv of the layer whose projection follows, [n][rank][d]
+  float *t_out = nullptr;                                 // LQ: [rows][64] A_qkv x of every row
+  const uint16_t *ao = nullptr, *bo = nullptr;            // LO: A_o [n][rank][qd], B_o [n][d][rank] of this layer
+  const uint4 *att = nullptr;                             // LO: the attention output (operand order), qd wide
+  int qd = 0;
+};
+
+// t[j] = sum_k A[j][k] x[k] over the block: every thread contributes the slices it holds, eight ranks at a time; the
+// per-wave sums meet in LDS and are added in wave order.  s_part: [16 waves][64].
+template <typename F>
+__device__ inline void lora_shrink(const uint16_t *__restrict__ A, int rank, int K, int tid, int nthreads, F &&slice,
+                                   float (*s_part)[64], float *s_t) {
+  const int w = tid >> 6, nw = nthreads >> 6;
+  for (int j0 = 0; j0 < rank; j0 += 8) {
+    float part[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int k0 = tid * 8; k0 < K; k0 += nthreads * 8) {
+      float xv[8];
+      slice(k0, xv);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(A + (size_t)(j0 + j) * K + k0);
+        const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+          part[j] += __uint_as_float(w4[u] << 16) * xv[2 * u] + __uint_as_float(w4[u] & 0xffff0000u) * xv[2 * u + 1];
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const float t = wave_sum(part[j]);
+      if ((tid & 63) == 0) s_part[w][j0 + j] = t;
+    }
+  }
+  __syncthreads();
+  if (tid < rank) {
+    float t = 0.f;
+    for (int i = 0; i < nw; ++i) t += s_part[i][tid];  // fixed order
+    s_t[tid] = t;
+  }
+  __syncthreads();
+}
+
+template <int EMBED, int LQ, int LO>
 __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, const int32_t *__restrict__ row_tok,
                                                      const uint16_t *__restrict__ E, const float *__restrict__ part,
                                                      int S, int Mpad, float *__restrict__ x,
-                                                     const uint16_t *__restrict__ gain, uint4 *__restrict__ a_out) {
+                                                     const uint16_t *__restrict__ gain, uint4 *__restrict__ a_out,
+                                                     lora_args lo) {
   const int r = blockIdx.x, tid = threadIdx.x, KB = d / 16, stride = blockDim.x * 8, nw = blockDim.x >> 6;
   if (r >= M) {
     for (int k0 = tid * 8; k0 < d; k0 += stride) a_out[tile_unit(r, k0, KB)] = make_uint4(0, 0, 0, 0);
@@ -107,6 +159,12 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
   }
   float *xr = x + (size_t)r * d;
   __shared__ float s_ss[16];
+  __shared__ float s_part[(LQ || LO) ? 16 : 1][64], s_t[64];
+  int ad = -1;
+  if (LQ || LO) {
+    ad = lo.adapter[lo.row_req[r]];
+    if (ad < 0 || ad >= lo.n) ad = -1;   // block-uniform: the row's request has no adapter
+  }
   // sum of the split slices (in slice order) on top of the residual, or the embedding row
   auto gather = [&](int k0, float(&v)[8]) {
     if (EMBED) {
@@ -142,7 +200,7 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
       }
     }
   };
-  auto emit = [&](int k0, const float(&v)[8], uint4 graw, float rinv) {
+  auto pack = [&](const float(&v)[8], uint4 graw, float rinv) {
     uint32_t g4[4] = {graw.x, graw.y, graw.z, graw.w};
     uint32_t o[4];
 #pragma unroll
@@ -150,29 +208,80 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
       float g0 = __uint_as_float(g4[j] << 16), g1 = __uint_as_float(g4[j] & 0xffff0000u);
       o[j] = (uint32_t)f2bf(v[2 * j] * rinv * g0) | ((uint32_t)f2bf(v[2 * j + 1] * rinv * g1) << 16);
     }
-    a_out[tile_unit(r, k0, KB)] = make_uint4(o[0], o[1], o[2], o[3]);
+    return make_uint4(o[0], o[1], o[2], o[3]);
   };
-  if (stride == d) {
-    // One 8-wide slice per thread (every shape up to d = 8192): the slice stays in registers across the block-wide sum
-    // of squares, and the gains are fetched together with the inputs, so the kernel is one round of loads, one
-    // reduction and one round of stores.
+  if (stride >= d) {
+    // At most one 8-wide slice per thread (every shape up to d = 8192): the slice stays in registers across the
+    // block-wide sum of squares, and the gains are fetched together with the inputs, so the kernel is one round of
+    // loads, one reduction and one round of stores.  Threads beyond the row width only take part in the reductions.
     const int k0 = tid * 8;
-    const uint4 graw = *reinterpret_cast<const uint4 *>(gain + k0);
-    float v[8];
-    gather(k0, v);
+    const bool live = k0 < d;
+    uint4 graw = make_uint4(0, 0, 0, 0);
+    float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (live) {
+      graw = *reinterpret_cast<const uint4 *>(gain + k0);
+      gather(k0, v);
+    }
+    if (LO && ad >= 0) {
+      // output projection of an adapted request: v += s B_o (A_o att), att = this row of the attention output
+      const int KBa = lo.qd / 16;
+      auto att_slice = [&](int kk, float(&xv)[8]) {
+        const uint4 raw = lo.att[tile_unit(r, kk, KBa)];
+        const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          xv[2 * u] = __uint_as_float(w4[u] << 16);
+          xv[2 * u + 1] = __uint_as_float(w4[u] & 0xffff0000u);
+        }
+      };
+      lora_shrink(lo.ao + (size_t)ad * lo.rank * lo.qd, lo.rank, lo.qd, tid, (int)blockDim.x, att_slice, s_part, s_t);
+      if (live) {
+        const float sc = lo.scale[ad];
+        const uint16_t *B = lo.bo + ((size_t)ad * d + k0) * lo.rank;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          float acc = 0.f;
+          for (int j = 0; j < lo.rank; j += 8) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(B + (size_t)i * lo.rank + j);
+            const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+              acc += __uint_as_float(w4[u] << 16) * s_t[j + 2 * u] + __uint_as_float(w4[u] & 0xffff0000u) * s_t[j + 2 * u + 1];
+          }
+          v[i] += sc * acc;
+        }
+      }
+    }
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) ss += v[j] * v[j];
     ss = wave_sum(ss);
     if ((tid & 63) == 0) s_ss[tid >> 6] = ss;
-    *reinterpret_cast<float4 *>(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
-    *reinterpret_cast<float4 *>(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    if (live) {
+      *reinterpret_cast<float4 *>(xr + k0) = make_float4(v[0], v[1], v[2], v[3]);
+      *reinterpret_cast<float4 *>(xr + k0 + 4) = make_float4(v[4], v[5], v[6], v[7]);
+    }
     __syncthreads();
     float tot = 0.f;
     for (int i = 0; i < nw; ++i) tot += s_ss[i];  // fixed order
-    emit(k0, v, graw, 1.0f / sqrtf(tot / (float)d + eps));
+    const uint4 packed = pack(v, graw, 1.0f / sqrtf(tot / (float)d + eps));
+    if (live) a_out[tile_unit(r, k0, KB)] = packed;
+    if (LQ && ad >= 0) {
+      // the q|k|v projection that follows is adapted for this row: leave t = A_qkv a (a = the operand just stored)
+      auto own_slice = [&](int kk, float(&xv)[8]) {   // kk == k0: one slice per thread
+        const uint32_t w4[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          xv[2 * u] = __uint_as_float(w4[u] << 16);
+          xv[2 * u + 1] = __uint_as_float(w4[u] & 0xffff0000u);
+        }
+      };
+      lora_shrink(lo.aq + (size_t)ad * lo.rank * d, lo.rank, d, tid, (int)blockDim.x, own_slice, s_part, s_t);
+      if (tid < lo.rank) lo.t_out[(size_t)r * 64 + tid] = s_t[tid];
+    }
     return;
   }
+  // rows wider than 8192 (no adapters there: fsv_lora_load refuses such a model)
   float ss = 0.f;
   for (int k0 = tid * 8; k0 < d; k0 += stride) {
     float v[8];
@@ -191,7 +300,7 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
   for (int k0 = tid * 8; k0 < d; k0 += stride) {  // each thread re-reads exactly what it wrote
     float4 a = *reinterpret_cast<const float4 *>(xr + k0), b = *reinterpret_cast<const float4 *>(xr + k0 + 4);
     float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-    emit(k0, v, *reinterpret_cast<const uint4 *>(gain + k0), rinv);
+    a_out[tile_unit(r, k0, KB)] = pack(v, *reinterpret_cast<const uint4 *>(gain + k0), rinv);
   }
 }
 
@@ -231,6 +340,7 @@ __global__ void k_rope_table(int M, int half, const double *__restrict__ inv_fre
   reinterpret_cast<float2 *>(tab)[t] = make_float2((float)cs, (float)sn);
 }
 
+template <int LORA>
 __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, const float *__restrict__ rope_tab,
                                                      const float *__restrict__ part, int S, int Mpad,
                                                      const int32_t *__restrict__ row_req,
@@ -239,7 +349,9 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
                                                      const int32_t *__restrict__ page_table, int max_pages,
                                                      int num_pages, size_t layer_off, uint16_t *__restrict__ qp,
                                                      size_t q_plane, uint16_t *__restrict__ kpool,
-                                                     uint16_t *__restrict__ vpool) {
+                                                     uint16_t *__restrict__ vpool, const int32_t *__restrict__ adapter,
+                                                     int n_adapters, int rank, const float *__restrict__ lscale,
+                                                     const uint16_t *__restrict__ bq, const float *__restrict__ tq) {
   // grid = (rows, blocks of 256 threads over the heads of the q|k|v projection); a thread owns four consecutive
   // rotation pairs (i .. i+3, i+half .. i+half+3) of one head.  The partial sums and the rotation table only need the
   // row index, so their loads are issued first, next to the row's request / position / page lookups.
@@ -273,6 +385,29 @@ __global__ __launch_bounds__(256) void k_rope_append(int H, int Hkv, int hd, con
   }
   const int b = row_req[r], i_row = row_idx[r], pos = row_pos[r];
   float av[4] = {a.x, a.y, a.z, a.w}, cv[4] = {c.x, c.y, c.z, c.w};
+  if (LORA) {
+    // adapted request: qkv += s B_qkv t, t = A_qkv a left by the norm kernel (before the rotation: it is part of the
+    // projection); bq: [n][qkvd][rank], tq: [rows][64]
+    const int ad = adapter[b];
+    if (ad >= 0 && ad < n_adapters) {
+      const float sc = lscale[ad];
+      const uint16_t *B = bq + ((size_t)ad * qkvd + hh * hd + i) * rank;
+      const float *t = tq + (size_t)r * 64;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint16_t *brow = B + (size_t)((e < 4) ? e : (half + e - 4)) * rank;
+        float acc = 0.f;
+        for (int j = 0; j < rank; j += 8) {
+          const uint4 raw = *reinterpret_cast<const uint4 *>(brow + j);
+          const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+          for (int u = 0; u < 4; ++u)
+            acc += __uint_as_float(w4[u] << 16) * t[j + 2 * u] + __uint_as_float(w4[u] & 0xffff0000u) * t[j + 2 * u + 1];
+        }
+        if (e < 4) av[e] += sc * acc; else cv[e - 4] += sc * acc;
+      }
+    }
+  }
   if (hh < H + Hkv) {
     const float4 t0 = *reinterpret_cast<const float4 *>(rope_tab + ((size_t)r * half + i) * 2);      // cos, sin, cos, sin
     const float4 t1 = *reinterpret_cast<const float4 *>(rope_tab + ((size_t)r * half + i) * 2 + 4);
@@ -475,42 +610,112 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     hipLaunchKernelGGL(k_rope_table, dim3(fsv_ceil_div(n, 256)), dim3(256), 0, s, M, d.head_dim / 2,
                        (const double *)c->inv_freq, c->row_pos, (float *)c->rope_tab);
   }
+  // adapters of the evolved target: per-request LoRA pairs on q|k|v and o of every layer but the last
+  const bool lora = c->lora_n > 0 && b->adapter != nullptr;
+  const size_t qd = (size_t)d.n_heads * d.head_dim, qkvd = qd + 2 * (size_t)d.n_kv_heads * d.head_dim;
+  auto lora_for = [&](int layer, bool lq, bool lo_) {
+    lora_args la;
+    la.row_req = c->row_req; la.adapter = b->adapter; la.n = c->lora_n; la.rank = c->lora_rank; la.scale = c->lora_scale;
+    if (lq) { la.aq = c->lora_aq + (size_t)layer * c->lora_n * c->lora_rank * d.d_model; la.t_out = c->lora_t; }
+    if (lo_) {
+      la.ao = c->lora_ao + (size_t)layer * c->lora_n * c->lora_rank * qd;
+      la.bo = c->lora_bo + (size_t)layer * c->lora_n * d.d_model * c->lora_rank;
+      la.att = (const uint4 *)c->buf_att; la.qd = (int)qd;
+    }
+    return la;
+  };
+  const bool lq0 = lora && d.n_layers > 1;
   {
     fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
-    hipLaunchKernelGGL(k_resid_norm<1>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
-                       (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
-                       (uint4 *)c->buf_a);
+    if (lq0)
+      hipLaunchKernelGGL((k_resid_norm<1, 1, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
+                         (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
+                         (uint4 *)c->buf_a, lora_for(0, true, false));
+    else
+      hipLaunchKernelGGL((k_resid_norm<1, 0, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
+                         (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
+                         (uint4 *)c->buf_a, lora_args{});
   }
   for (int l = 0; l < d.n_layers; ++l) {
     const fsv_layer_w &L = c->layers[l];
     const size_t lo = (size_t)l * layer_stride(c, b->num_pages);
+    const bool adapted = lora && l < d.n_layers - 1;         // the last block belongs to the invariant head
+    const bool next_adapted = lora && l + 1 < d.n_layers - 1;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
-      hipLaunchKernelGGL(k_rope_append, dim3(M, fsv_ceil_div((d.n_heads + 2 * d.n_kv_heads) * (d.head_dim / 8), 256)), dim3(256), 0, s,
-                         d.n_heads, d.n_kv_heads, d.head_dim,
-                         (const float *)c->rope_tab, part, spq, Mpad, c->row_req, c->row_idx, c->row_pos, b->page_table,
-                         d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q, c->q_plane_units * 8,
-                         (uint16_t *)b->k_pool, (uint16_t *)b->v_pool);
+      const dim3 rg(M, fsv_ceil_div((d.n_heads + 2 * d.n_kv_heads) * (d.head_dim / 8), 256));
+#define FSV_ROPE_ARGS d.n_heads, d.n_kv_heads, d.head_dim, (const float *)c->rope_tab, part, spq, Mpad, c->row_req, c->row_idx, \
+                      c->row_pos, b->page_table, d.max_pages_per_req, b->num_pages, lo, (uint16_t *)c->buf_q,                  \
+                      c->q_plane_units * 8, (uint16_t *)b->k_pool, (uint16_t *)b->v_pool
+      if (adapted)
+        hipLaunchKernelGGL(k_rope_append<1>, rg, dim3(256), 0, s, FSV_ROPE_ARGS, b->adapter, c->lora_n, c->lora_rank,
+                           (const float *)c->lora_scale, c->lora_bq + (size_t)l * c->lora_n * qkvd * c->lora_rank,
+                           (const float *)c->lora_t);
+      else
+        hipLaunchKernelGGL(k_rope_append<0>, rg, dim3(256), 0, s, FSV_ROPE_ARGS, nullptr, 0, 0, nullptr, nullptr, nullptr);
+#undef FSV_ROPE_ARGS
     }
     if ((rc = fsv_bf16_attn_launch(c, b, &pl, lo, s))) return rc;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
-      hipLaunchKernelGGL(k_resid_norm<0>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr, part,
-                         spo, Mpad, c->x, (const uint16_t *)L.mlp_norm, (uint4 *)c->buf_a);
+      if (adapted)
+        hipLaunchKernelGGL((k_resid_norm<0, 0, 1>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
+                           part, spo, Mpad, c->x, (const uint16_t *)L.mlp_norm, (uint4 *)c->buf_a, lora_for(l, false, true));
+      else
+        hipLaunchKernelGGL((k_resid_norm<0, 0, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
+                           part, spo, Mpad, c->x, (const uint16_t *)L.mlp_norm, (uint4 *)c->buf_a, lora_args{});
     }
     if ((rc = launch_gemm<EPI_SWIGLU>(c, FSV_K_GEMM_GATE_UP, L.w_gate_up, c->buf_a, c->buf_act, sg, M, 1, s))) return rc;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_DOWN, L.w_down, c->buf_act, part, sd, M, spd, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
       const void *gain = (l + 1 < d.n_layers) ? c->layers[l + 1].attn_norm : c->final_norm;
-      hipLaunchKernelGGL(k_resid_norm<0>, dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr, part,
-                         spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a);
+      if (next_adapted)
+        hipLaunchKernelGGL((k_resid_norm<0, 1, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
+                           part, spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a, lora_for(l + 1, true, false));
+      else
+        hipLaunchKernelGGL((k_resid_norm<0, 0, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
+                           part, spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a, lora_args{});
     }
   }
   if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->lm_head, c->buf_a, logits, sl, M, 1, s))) return rc;
   FSV_HIP(c, hipGetLastError());
+  return FSV_OK;
+}
+
+// Copy a set of adapters into library-owned tables [layer][adapter][...] (replacing any earlier set).
+int fsv_bf16_lora_load(fsv_ctx *c, const fsv_lora *lo) {
+  const fsv_model_desc &d = c->d;
+  void *old[] = {c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t};
+  for (void *p : old)
+    if (p) (void)hipFree(p);
+  c->lora_aq = c->lora_bq = c->lora_ao = c->lora_bo = nullptr;
+  c->lora_scale = nullptr;
+  c->lora_t = nullptr;
+  c->lora_n = c->lora_rank = 0;
+  if (!lo || lo->n_adapters == 0 || d.n_layers < 2) return FSV_OK;
+  const int n = lo->n_adapters, r = lo->rank, NLa = d.n_layers - 1;
+  const size_t qd = (size_t)d.n_heads * d.head_dim, qkvd = qd + 2 * (size_t)d.n_kv_heads * d.head_dim, dm = d.d_model;
+  FSV_HIP(c, hipMalloc((void **)&c->lora_aq, 2 * (size_t)NLa * n * r * dm));
+  FSV_HIP(c, hipMalloc((void **)&c->lora_bq, 2 * (size_t)NLa * n * qkvd * r));
+  FSV_HIP(c, hipMalloc((void **)&c->lora_ao, 2 * (size_t)NLa * n * r * qd));
+  FSV_HIP(c, hipMalloc((void **)&c->lora_bo, 2 * (size_t)NLa * n * dm * r));
+  FSV_HIP(c, hipMalloc((void **)&c->lora_scale, sizeof(float) * n));
+  FSV_HIP(c, hipMalloc((void **)&c->lora_t, sizeof(float) * 64 * (size_t)c->max_rows));
+  FSV_HIP(c, hipMemcpy(c->lora_scale, lo->scale, sizeof(float) * n, hipMemcpyHostToDevice));
+  for (int l = 0; l < NLa; ++l)
+    for (int a = 0; a < n; ++a) {
+      const size_t i = (size_t)l * n + a;
+      FSV_HIP(c, hipMemcpy(c->lora_aq + i * r * dm, lo->a_qkv[i], 2 * (size_t)r * dm, hipMemcpyDeviceToDevice));
+      FSV_HIP(c, hipMemcpy(c->lora_bq + i * qkvd * r, lo->b_qkv[i], 2 * qkvd * r, hipMemcpyDeviceToDevice));
+      FSV_HIP(c, hipMemcpy(c->lora_ao + i * r * qd, lo->a_o[i], 2 * (size_t)r * qd, hipMemcpyDeviceToDevice));
+      FSV_HIP(c, hipMemcpy(c->lora_bo + i * dm * r, lo->b_o[i], 2 * dm * r, hipMemcpyDeviceToDevice));
+    }
+  FSV_HIP(c, hipDeviceSynchronize());
+  c->lora_n = n;
+  c->lora_rank = r;
   return FSV_OK;
 }
 

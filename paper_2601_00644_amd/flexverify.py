@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, os.environ.get("FSV_LIB_NAME", "libflexverify.so"
 F32, BF16 = 0, 1
 W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
-EXPORTS = ["fsv_create", "fsv_destroy", "fsv_verify", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
+EXPORTS = ["fsv_create", "fsv_destroy", "fsv_lora_load", "fsv_verify", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
            "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
            "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_policy_step_time", "fsv_pager_create",
            "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
@@ -40,7 +40,12 @@ class Batch(C.Structure):
     _fields_ = [("batch", C.c_int32), ("num_pages", C.c_int32)] + [(n, C.c_void_p) for n in (
         "seq_lens", "seq_lens_host", "last_token", "draft_offsets", "draft_offsets_host", "draft_tokens", "draft_probs",
         "u_accept", "u_sample", "temperature", "temperature_host", "page_table", "k_pool", "v_pool", "top_p",
-        "top_p_host", "top_k", "top_k_host")]
+        "top_p_host", "top_k", "top_k_host", "adapter")]
+
+
+class Lora(C.Structure):
+    _fields_ = [("n_adapters", C.c_int32), ("rank", C.c_int32), ("scale", C.c_void_p)] + \
+               [(n, C.POINTER(C.c_void_p)) for n in ("a_qkv", "b_qkv", "a_o", "b_o")]
 
 
 class Result(C.Structure):
@@ -139,6 +144,7 @@ class DeviceBatch:
     top_p_host: np.ndarray | None = None
     top_k: torch.Tensor | None = None          # [B] int32 top-k cut per request (0 = off)
     top_k_host: np.ndarray | None = None
+    adapter: torch.Tensor | None = None        # [B] int32 adapter id of the request's target version (-1 = base)
 
     @property
     def batch(self):
@@ -153,7 +159,7 @@ class DeviceBatch:
                      _ptr(self.last_token), _ptr(self.draft_offsets), _ptr(self.draft_offsets_host),
                      _ptr(self.draft_tokens), _ptr(self.draft_probs), _ptr(self.u_accept), _ptr(self.u_sample),
                      _ptr(self.temperature), _ptr(self.temperature_host), _ptr(self.page_table), _ptr(self.k_pool),
-                     _ptr(self.v_pool), _ptr(self.top_p), _ptr(self.top_p_host), _ptr(self.top_k), _ptr(self.top_k_host))
+                     _ptr(self.v_pool), _ptr(self.top_p), _ptr(self.top_p_host), _ptr(self.top_k), _ptr(self.top_k_host), _ptr(self.adapter))
 
 
 @dataclass
@@ -218,6 +224,23 @@ class Context:
             self.close()
         except Exception:
             pass
+
+    def lora_load(self, adapters: list | None):
+        """adapters: list of dicts as synth.make_lora returns them (device tensors), all of one rank; None removes them."""
+        if not adapters:
+            self._check(lib().fsv_lora_load(self._h, None), "fsv_lora_load")
+            return
+        n, nl = len(adapters), self.cfg.n_layers - 1
+        scale = np.ascontiguousarray([a["scale"] for a in adapters], np.float32)
+        keep = []
+
+        def table(name):
+            arr = (C.c_void_p * max(nl * n, 1))(*[adapters[a][name][l].data_ptr() for l in range(nl) for a in range(n)])
+            keep.append(arr)
+            return C.cast(arr, C.POINTER(C.c_void_p))
+
+        lo = Lora(n, int(adapters[0]["rank"]), scale.ctypes.data, table("a_qkv"), table("b_qkv"), table("a_o"), table("b_o"))
+        self._check(lib().fsv_lora_load(self._h, C.byref(lo)), "fsv_lora_load")
 
     def verify(self, batch: DeviceBatch, result: DeviceResult):
         b, r = batch.struct(), result.struct()
