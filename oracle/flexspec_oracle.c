@@ -38,6 +38,10 @@
  *                   transformer block and the LM head -- stays invariant).  The adapters are LoRA pairs on the
  *                   attention projections of every layer but the last: y = W x + s B (A x).  Without
  *                   adapters it IS orc_forward_stored.
+ *   - orc_draft_forward : the edge draft model of Sec. IV-A, M_d(x) = H_small(B_shared(x)): a frozen copy of the
+ *                   anchor block (the target's last transformer block) followed by a two-layer MLP and a
+ *                   vocabulary projection.  The cloud holds all of it, so it can recompute the draft's law
+ *                   for the tokens it receives instead of having it sent over the uplink.
  *
  * Parity pins for every function live in tests/test_oracle_*.py.
  */
@@ -265,9 +269,11 @@ int orc_forward_lora(const orc_model *mo, const orc_weights *w, const orc_lora *
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
   }
   if (hidden) memcpy(hidden, h, sizeof(double) * n * d);
-  rmsnorm(h, w->final_norm, bf, d, mo->rms_eps, n, a);
-  if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
-  orc_linear(w->lm_head, bf, V, d, a, n, logits);
+  if (logits) {
+    rmsnorm(h, w->final_norm, bf, d, mo->rms_eps, n, a);
+    if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
+    orc_linear(w->lm_head, bf, V, d, a, n, logits);
+  }
   free(h); free(a); free(qkv); free(att); free(gu); free(act); free(upd);
   return 0;
 }
@@ -280,6 +286,48 @@ int orc_forward_stored(const orc_model *mo, const orc_weights *w, double *kc, do
 int orc_forward(const orc_model *mo, const orc_weights *w, double *kc, double *vc, int cap, int L,
                 const int32_t *tokens, int n, double *logits, double *hidden) {
   return orc_forward_lora(mo, w, (const orc_lora *)0, kc, vc, cap, L, tokens, n, logits, hidden, 0);
+}
+
+/*
+ * The draft model of Sec. IV-A (structural definition): M_d(x) = H_small(B_shared(x)).
+ *   B_shared : a frozen copy of the anchor block, i.e. the LAST transformer block of the base target (weights taken from
+ *              layer n_layers - 1 of `w`), applied to the embeddings of the tokens (the base model's embedding table)
+ *              with a KV session of its own (kc, vc: ONE layer, [cap][n_kv_heads][head_dim]);
+ *   H_small  : a two-layer MLP followed by a vocabulary projection, on the block's output h (the residual stream):
+ *              z = W_v ( W_2 silu( W_1 h ) ),  W_1 [d_hidden][d_model], W_2 [d_proj][d_hidden], W_v [vocab][d_proj].
+ * logits: [n][vocab], row i = the draft's logits for the token following tokens[i]; its law is softmax(z / T).
+ * With `stored` != 0 the block rounds its storage points as the target forward does, and the three inputs of the head's
+ * projections (h, the activation, the second layer's output) are rounded to bf16 as well.
+ */
+typedef struct {
+  int d_hidden, d_proj;
+  const void *w1, *w2, *wv;   /* weight storage type of the model */
+} orc_draft_head;
+
+int orc_draft_forward(const orc_model *mo, const orc_weights *w, const orc_draft_head *head, double *kc, double *vc, int cap,
+                      int L, const int32_t *tokens, int n, double *logits, int stored) {
+  if (mo->n_layers < 1 || !head || head->d_hidden <= 0 || head->d_proj <= 0) return -1;
+  const int last = mo->n_layers - 1, d = mo->d_model, bf = mo->weights_bf16, dh = head->d_hidden, dp = head->d_proj;
+  orc_model m1 = *mo;
+  m1.n_layers = 1;
+  orc_weights w1 = *w;   /* the one-layer model whose only block is the anchor block */
+  const void *an = w->attn_norm[last], *qkv = w->w_qkv[last], *wo = w->w_o[last], *mn = w->mlp_norm[last],
+             *gu = w->w_gate_up[last], *dn = w->w_down[last];
+  w1.attn_norm = &an; w1.w_qkv = &qkv; w1.w_o = &wo; w1.mlp_norm = &mn; w1.w_gate_up = &gu; w1.w_down = &dn;
+  double *h = malloc(sizeof(double) * n * d), *t1 = malloc(sizeof(double) * n * dh), *t2 = malloc(sizeof(double) * n * dp);
+  if (!h || !t1 || !t2) return -1;
+  int rc = orc_forward_lora(&m1, &w1, (const orc_lora *)0, kc, vc, cap, L, tokens, n, (double *)0, h, stored);
+  if (rc == 0) {
+    if (stored) round_rows(h, (size_t)n * d);
+    orc_linear(head->w1, bf, dh, d, h, n, t1);
+    for (size_t i = 0; i < (size_t)n * dh; ++i) t1[i] = t1[i] / (1.0 + exp(-t1[i]));   /* silu */
+    if (stored) round_rows(t1, (size_t)n * dh);
+    orc_linear(head->w2, bf, dp, dh, t1, n, t2);
+    if (stored) round_rows(t2, (size_t)n * dp);
+    orc_linear(head->wv, bf, mo->vocab, dp, t2, n, logits);
+  }
+  free(h); free(t1); free(t2);
+  return rc;
 }
 
 typedef struct {

@@ -43,6 +43,10 @@ class _Lora(C.Structure):
         (n, C.POINTER(C.c_void_p)) for n in ("a_qkv", "b_qkv", "a_o", "b_o")]
 
 
+class _DraftHead(C.Structure):
+    _fields_ = [("d_hidden", C.c_int), ("d_proj", C.c_int), ("w1", C.c_void_p), ("w2", C.c_void_p), ("wv", C.c_void_p)]
+
+
 class _SampleOut(C.Structure):
     _fields_ = [("tau", C.c_int32), ("next_token", C.c_int32), ("used_residual", C.c_int32), ("pad_", C.c_int32),
                 ("accept_margin", C.c_double), ("cdf_margin", C.c_double), ("nucleus_margin", C.c_double)]
@@ -58,6 +62,7 @@ def lib():
         _lib.orc_forward.restype = C.c_int
         _lib.orc_forward_stored.restype = C.c_int
         _lib.orc_forward_lora.restype = C.c_int
+        _lib.orc_draft_forward.restype = C.c_int
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
         _lib.orc_sample.restype = C.c_int
@@ -173,6 +178,31 @@ def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False, stored: i
     if rc != 0:
         raise ValueError("orc_forward rejected its arguments")
     return (logits, hidden) if want_hidden else logits
+
+
+def draft_forward(cfg, w, head, kc, vc, L: int, tokens, stored: int = 0):
+    """The edge draft model of Sec. IV-A over tokens placed at positions L.. of ITS one-layer KV session (kc, vc:
+    [1][cap][n_kv_heads][head_dim]): anchor block (the target's last block, from w) + two-layer MLP + vocabulary projection.
+
+    head: dict(w1 [d_hidden][d_model], w2 [d_proj][d_hidden], wv [vocab][d_proj]) in the model's weight storage type.
+    Returns the draft's logits [n][vocab] fp64; its law is softmax(logits / T)."""
+    tokens = np.ascontiguousarray(tokens, np.int32)
+    n = int(tokens.shape[0])
+    assert kc.shape[0] == 1 and kc.dtype == np.float64 and kc.flags.c_contiguous and vc.flags.c_contiguous
+    want = np.uint16 if cfg.dtype == "bf16" else np.float32
+    mats = [np.ascontiguousarray(head[k]) for k in ("w1", "w2", "wv")]
+    assert all(m.dtype == want for m in mats)
+    hs = _DraftHead(int(mats[0].shape[0]), int(mats[1].shape[0]), mats[0].ctypes.data, mats[1].ctypes.data, mats[2].ctypes.data)
+    logits = np.empty((n, cfg.vocab), np.float64)
+    ms = _model_struct(cfg)
+    ws, keep = _weights_struct(cfg, w)
+    rc = lib().orc_draft_forward(C.byref(ms), C.byref(ws), C.byref(hs), C.c_void_p(kc.ctypes.data), C.c_void_p(vc.ctypes.data),
+                                 C.c_int(kc.shape[1]), C.c_int(L), C.c_void_p(tokens.ctypes.data), C.c_int(n),
+                                 C.c_void_p(logits.ctypes.data), C.c_int(int(stored)))
+    del keep, mats
+    if rc != 0:
+        raise ValueError("orc_draft_forward rejected its arguments")
+    return logits
 
 
 def linear(W, x, bf16: bool):

@@ -148,6 +148,15 @@ def lora_to_numpy(cfg: ModelCfg, lora: dict) -> dict:
     return {k: ([conv(t) for t in v] if isinstance(v, list) else v) for k, v in lora.items()}
 
 
+def make_draft_head(cfg: ModelCfg, d_hidden: int, d_proj: int, seed: int, device="cpu", std: float = 0.05) -> dict:
+    """A seeded head of the edge draft model (two-layer MLP + vocabulary projection); a trained one is distilled from
+    the base target (Alg. 1), random matrices stand in for it."""
+    tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    shapes = {"w1": (d_hidden, cfg.d_model), "w2": (d_proj, d_hidden), "wv": (cfg.vocab, d_proj)}
+    return {k: (torch.randn(sh, generator=_gen(seed, 60_000 + j, device), device=device, dtype=torch.float32) * std).to(tdt)
+            for j, (k, sh) in enumerate(shapes.items())}
+
+
 def weights_to_numpy(cfg: ModelCfg, w: dict) -> dict:
     """Host copies in the layout the oracle takes: float32, or uint16 bf16 bit patterns."""
     if cfg.dtype == "bf16":

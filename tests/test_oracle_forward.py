@@ -360,3 +360,65 @@ def test_lora_special_cases():
     k2 = run(wn, dict(ln, scale=2.0))[1][0][0]
     k0 = run(wn, None)[1][0][0]
     assert np.allclose(k2 - k0, 2.0 * (k1 - k0), rtol=1e-9, atol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# the edge draft model: anchor block + two-layer MLP + vocabulary projection (orc_draft_forward)
+# ---------------------------------------------------------------------------------------------
+
+def _anchor_only(cfg, wn):
+    """The one-layer model whose only block is the target's last block (the anchor block)."""
+    last = cfg.n_layers - 1
+    cfg1 = dataclasses.replace(cfg, n_layers=1)
+    w1 = {k: v for k, v in wn.items() if "." not in k}
+    for k, v in wn.items():
+        if k.endswith(f".{last}"):
+            w1[k.rsplit(".", 1)[0] + ".0"] = v
+    return cfg1, w1
+
+
+@pytest.mark.parametrize("name", ["minif32", "mini64"])
+def test_draft_forward_is_the_anchor_block_followed_by_the_head(name):
+    # anchor part: the hidden state of the already pinned forward on the one-layer model made of the LAST block;
+    # head part: three matrix products and a silu with numpy (library routines)
+    cfg, wn = _cfg_and_weights(name, seed=7)
+    head_t = synth.make_draft_head(cfg, 96, 64, 7, std=0.1)
+    head = synth.weights_to_numpy(cfg, head_t)
+    L, n = 19, 6
+    k, v = synth.make_kv_context(dataclasses.replace(cfg, n_layers=1), L, 7, 0)
+    toks = np.random.default_rng(2).integers(0, cfg.vocab, n).astype(np.int32)
+    cfg1, w1 = _anchor_only(cfg, wn)
+
+    def cache():
+        kc, vc = oracle.new_cache(cfg1, L + n)
+        kc[:, :L], vc[:, :L] = synth.kv_to_f64(k), synth.kv_to_f64(v)
+        return kc, vc
+
+    kc, vc = cache()
+    got = oracle.draft_forward(cfg, wn, head, kc, vc, L, toks)
+    kc2, vc2 = cache()
+    _, hid = oracle.forward(cfg1, w1, kc2, vc2, L, toks, want_hidden=True)
+    W = {kk: (synth.bits_to_f32(a).astype(np.float64) if cfg.dtype == "bf16" else a.astype(np.float64)) for kk, a in head.items()}
+    t1 = hid @ W["w1"].T
+    t2 = (t1 / (1.0 + np.exp(-t1))) @ W["w2"].T
+    want = t2 @ W["wv"].T
+    assert np.abs(got - want).max() < 1e-10 * max(1.0, np.abs(want).max())
+    assert np.array_equal(kc, kc2) and np.array_equal(vc, vc2)     # the draft's own KV session got the block's rows
+    # it is the LAST block that is shared, not the first: with the first block the result differs
+    cfg_f, w_f = dataclasses.replace(cfg, n_layers=1), {kk: vv for kk, vv in wn.items() if "." not in kk or kk.endswith(".0")}
+    kc3, vc3 = cache()
+    _, hid_first = oracle.forward(cfg_f, w_f, kc3, vc3, L, toks, want_hidden=True)
+    assert np.abs(hid_first - hid).max() > 1e-3
+
+
+def test_draft_forward_stored_mode_rounds_the_head_inputs():
+    cfg, wn = _cfg_and_weights("mini64", seed=8)
+    head = synth.weights_to_numpy(cfg, synth.make_draft_head(cfg, 256, 256, 8, std=0.1))
+    cfg1 = dataclasses.replace(cfg, n_layers=1)
+    toks = np.arange(5, dtype=np.int32)
+    outs = []
+    for mode in (0, 1 | 4 | 16 | 32):
+        kc, vc = oracle.new_cache(cfg1, 8)
+        outs.append(oracle.draft_forward(cfg, wn, head, kc, vc, 0, toks, stored=mode))
+    rel = np.linalg.norm(outs[1] - outs[0]) / np.linalg.norm(outs[0])
+    assert 1e-4 < rel < 2e-2, rel
