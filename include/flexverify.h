@@ -180,6 +180,39 @@ typedef struct {
 int fsv_lora_load(fsv_ctx *ctx, const fsv_lora *lora);
 
 /*
+ * The edge draft model on the cloud (Sec. IV-A, structural definition): M_d(x) = H_small(B_shared(x)), where B_shared is
+ * a frozen copy of the anchor block -- the base target's LAST transformer block, which the context already holds -- and
+ * H_small is a two-layer MLP followed by a vocabulary projection, z = W_v (W_2 silu(W_1 h)) on the block's output h.
+ * The uplink carries token ids only (Sec. IV-B); with the draft model the cloud recomputes the law q_i(.) each received
+ * draft was drawn from, which the acceptance test of fsv_verify needs when T_b > 0, instead of receiving it.
+ *
+ * fsv_draft_attach: give the context the head (DEVICE, bf16, row-major [out][in]: w1 [d_hidden][d_model],
+ *   w2 [d_proj][d_hidden], w_vocab [vocab][d_proj]; d_hidden and d_proj multiples of 256).  The matrices are re-tiled
+ *   and may be freed afterwards; NULL removes the head.  FSV_BF16 models only.
+ * fsv_draft_probs: run the draft model over the same rows a verification call scores (pending token + drafts of every
+ *   request) on the DRAFT's KV session -- batch->k_pool / v_pool are pools of ONE layer here, same page tables and
+ *   lengths as the target's session, appended to in place -- and write q = softmax(z / T_b), fp32:
+ *     FSV_DRAFT_Q_VERIFY: q_out [G][vocab], row draft_offsets[b] + i = the law of draft i+1 of request b (from its
+ *                         input row i): exactly fsv_batch.draft_probs of the verification call that follows;
+ *     FSV_DRAFT_Q_ALL:    q_out [M][vocab], one law per input row (what an edge device samples its next draft from).
+ *   Rows of requests with T_b = 0 are left untouched.  logits_out (DEVICE [M][vocab] fp32) may be NULL.
+ *   Uses from batch: batch, num_pages, seq_lens(+_host), last_token, draft_offsets(+_host), draft_tokens, temperature,
+ *   page_table, k_pool, v_pool.  After the verification call both sessions hold new_seq_lens valid positions.
+ */
+typedef struct {
+  int32_t d_hidden, d_proj;
+  const void *w1, *w2, *w_vocab;
+} fsv_draft_head;
+enum { FSV_DRAFT_Q_VERIFY = 0, FSV_DRAFT_Q_ALL = 1 };
+int fsv_draft_attach(fsv_ctx *ctx, const fsv_draft_head *head);
+/* fsv_kv_import / fsv_kv_export for the draft's one-layer session: src / dst are [n_pos][n_kv_heads][head_dim]. */
+int fsv_draft_kv_import(fsv_ctx *ctx, void *k_pool, void *v_pool, int32_t num_pages, const int32_t *page_table_row,
+                        int32_t pos0, int32_t n_pos, const void *src_k, const void *src_v, void *stream);
+int fsv_draft_kv_export(fsv_ctx *ctx, const void *k_pool, const void *v_pool, int32_t num_pages,
+                        const int32_t *page_table_row, int32_t pos0, int32_t n_pos, void *dst_k, void *dst_v, void *stream);
+int fsv_draft_probs(fsv_ctx *ctx, const fsv_batch *batch, int32_t rows_mode, float *q_out, float *logits_out, void *stream);
+
+/*
  * The verification step (Alg. 2 step 2 with the KV append / rollback of Sec. IV-C) for a batch.
  * For T_b > 0 the acceptance rule is speculative sampling, which keeps the law of the emitted
  * tokens equal to the target model's (Sec. II; Regime B of Sec. V): draft i is accepted iff

@@ -101,7 +101,8 @@ void fsv_destroy(fsv_ctx *c) {
                   c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->rowkey, c->nuc_prefix,
                   c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
                   c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map,
-                  c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t};
+                  c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t,
+                  c->draft_w1, c->draft_w2, c->draft_wv, c->draft_h1, c->draft_h2};
   for (void *p : ptrs)
     if (p) (void)hipFree(p);
   for (auto &L : c->layers) {
@@ -183,7 +184,7 @@ int fsv_verify(fsv_ctx *c, const fsv_batch *b, const fsv_result *r, void *stream
   int rc = (c->d.dtype == FSV_F32) ? fsv_f32_check(c, b) : fsv_bf16_attn_plan_host(c, b, &pl);
   if (rc) return rc;
   if ((rc = fsv_launch_build_rows(c, b, M, s))) return rc;
-  rc = (c->d.dtype == FSV_F32) ? fsv_f32_forward(c, b, M, logits, s) : fsv_bf16_forward(c, b, &pl, M, logits, s);
+  rc = (c->d.dtype == FSV_F32) ? fsv_f32_forward(c, b, M, logits, s) : fsv_bf16_forward(c, b, &pl, M, logits, 0, s);
   if (rc) return rc;
   return fsv_launch_sampler(c, logits, FSV_F32, b, r, M, true, s);
 }
@@ -214,7 +215,7 @@ int fsv_rollback(fsv_ctx *c, const fsv_batch *b, const int32_t *accepted_len, co
 }
 
 static int kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int32_t num_pages, const int32_t *pt, int32_t pos0,
-                   int32_t n, void *kl, void *vl, bool import, void *stream) {
+                   int32_t n, void *kl, void *vl, bool import, void *stream, bool draft = false) {
   if (!c) return FSV_E_INVALID_ARG;
   if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "KV copy on a sampler-only context");
   if (!k_pool || !v_pool || !pt || !kl || !vl || num_pages <= 0 || pos0 < 0 || n < 0)
@@ -223,8 +224,22 @@ static int kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int32_t num_pages, co
     FSV_FAIL(c, FSV_E_CAPACITY, "positions up to %d exceed the page table", pos0 + n);
   if (n == 0) return FSV_OK;
   hipStream_t s = (hipStream_t)stream;
+  if (draft) {
+    if (c->d.dtype != FSV_BF16) FSV_FAIL(c, FSV_E_UNSUPPORTED, "the draft model is implemented for FSV_BF16 models");
+    return fsv_bf16_kv_copy(c, k_pool, v_pool, num_pages, pt, pos0, n, kl, vl, import, 1, s);
+  }
   return (c->d.dtype == FSV_F32) ? fsv_f32_kv_copy(c, k_pool, v_pool, num_pages, pt, pos0, n, kl, vl, import, s)
-                                 : fsv_bf16_kv_copy(c, k_pool, v_pool, num_pages, pt, pos0, n, kl, vl, import, s);
+                                 : fsv_bf16_kv_copy(c, k_pool, v_pool, num_pages, pt, pos0, n, kl, vl, import, c->d.n_layers, s);
+}
+
+int fsv_draft_kv_import(fsv_ctx *c, void *k_pool, void *v_pool, int32_t num_pages, const int32_t *pt, int32_t pos0,
+                        int32_t n_pos, const void *src_k, const void *src_v, void *stream) {
+  return kv_copy(c, k_pool, v_pool, num_pages, pt, pos0, n_pos, (void *)src_k, (void *)src_v, true, stream, true);
+}
+
+int fsv_draft_kv_export(fsv_ctx *c, const void *k_pool, const void *v_pool, int32_t num_pages, const int32_t *pt,
+                        int32_t pos0, int32_t n_pos, void *dst_k, void *dst_v, void *stream) {
+  return kv_copy(c, (void *)k_pool, (void *)v_pool, num_pages, pt, pos0, n_pos, dst_k, dst_v, false, stream, true);
 }
 
 int fsv_kv_import(fsv_ctx *c, void *k_pool, void *v_pool, int32_t num_pages, const int32_t *pt, int32_t pos0,
@@ -252,6 +267,36 @@ int fsv_lora_load(fsv_ctx *c, const fsv_lora *lo) {
       if (!lo->a_qkv[i] || !lo->b_qkv[i] || !lo->a_o[i] || !lo->b_o[i]) FSV_FAIL(c, FSV_E_INVALID_ARG, "NULL adapter matrix %d", i);
   }
   return fsv_bf16_lora_load(c, lo);
+}
+
+int fsv_draft_attach(fsv_ctx *c, const fsv_draft_head *h) {
+  if (!c) return FSV_E_INVALID_ARG;
+  if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "fsv_draft_attach on a sampler-only context");
+  if (c->d.dtype != FSV_BF16) FSV_FAIL(c, FSV_E_UNSUPPORTED, "the draft model is implemented for FSV_BF16 models");
+  if (h) {
+    if (!h->w1 || !h->w2 || !h->w_vocab) FSV_FAIL(c, FSV_E_INVALID_ARG, "NULL head matrix");
+    if (h->d_hidden <= 0 || h->d_proj <= 0 || h->d_hidden % 256 || h->d_proj % 256)
+      FSV_FAIL(c, FSV_E_UNSUPPORTED, "d_hidden and d_proj must be positive multiples of 256");
+    if (c->d.d_model > 8192) FSV_FAIL(c, FSV_E_UNSUPPORTED, "the draft head needs d_model <= 8192");
+  }
+  return fsv_bf16_draft_attach(c, h);
+}
+
+int fsv_draft_probs(fsv_ctx *c, const fsv_batch *b, int32_t rows_mode, float *q_out, float *logits_out, void *stream) {
+  if (!c) return FSV_E_INVALID_ARG;
+  if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "fsv_draft_probs on a sampler-only context");
+  if (!c->draft_wv) FSV_FAIL(c, FSV_E_INVALID_ARG, "no draft head attached (fsv_draft_attach)");
+  if (!q_out || (rows_mode != FSV_DRAFT_Q_VERIFY && rows_mode != FSV_DRAFT_Q_ALL)) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad argument");
+  const int M = fsv_check_batch(c, b, true, false);
+  if (M <= 0) return M;
+  if (!b->last_token || !b->temperature) FSV_FAIL(c, FSV_E_INVALID_ARG, "last_token and temperature required");
+  if (b->draft_offsets_host[b->batch] > 0 && !b->draft_tokens) FSV_FAIL(c, FSV_E_INVALID_ARG, "draft_tokens required");
+  fsv_attn_plan pl;
+  int rc = fsv_bf16_attn_plan_host(c, b, &pl);
+  if (rc) return rc;
+  hipStream_t s = (hipStream_t)stream;
+  if ((rc = fsv_launch_build_rows(c, b, M, s))) return rc;
+  return fsv_bf16_draft_probs(c, b, &pl, M, rows_mode == FSV_DRAFT_Q_ALL, q_out, logits_out ? logits_out : c->logits, s);
 }
 
 int fsv_linear(fsv_ctx *c, int32_t which, int32_t layer, const void *x, int32_t M, float *y, void *stream) {

@@ -89,6 +89,10 @@ struct fsv_ctx {
   float *lora_scale = nullptr;   // [lora_n]
   float *lora_t = nullptr;       // [max_rows][64] A_qkv x of the rows of the current call
 
+  // head of the edge draft model (bf16 path): re-tiled W_1, W_2, W_v and the operands between them
+  int draft_dh = 0, draft_dp = 0;
+  void *draft_w1 = nullptr, *draft_w2 = nullptr, *draft_wv = nullptr, *draft_h1 = nullptr, *draft_h2 = nullptr;
+
   // profiling
   uint32_t prof_mask = 0;
   std::vector<fsv_prof_rec> prof;
@@ -171,11 +175,14 @@ int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, 
                   int splits, int KBo, hipStream_t st);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
-int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *logits, hipStream_t s);
+int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *logits, int draft, hipStream_t s);
+int fsv_bf16_draft_attach(fsv_ctx *c, const fsv_draft_head *h);
+int fsv_bf16_draft_probs(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, int all_rows, float *q_out, float *logits,
+                         hipStream_t s);
 int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, float *y, hipStream_t s);
 int fsv_bf16_lora_load(fsv_ctx *c, const fsv_lora *lo);
 int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *out,
                        hipStream_t s);
 int fsv_bf16_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,
-                     void *k_lin, void *v_lin, bool import, hipStream_t s);
+                     void *k_lin, void *v_lin, bool import, int layers, hipStream_t s);
 void fsv_free_weights(fsv_ctx *c);

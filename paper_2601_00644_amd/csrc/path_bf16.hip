@@ -146,7 +146,7 @@ __device__ inline void lora_shrink(const uint16_t *__restrict__ A, int rank, int
   __syncthreads();
 }
 
-template <int EMBED, int LQ, int LO>
+template <int EMBED, int LQ, int LO, int RAW = 0>
 __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, const int32_t *__restrict__ row_tok,
                                                      const uint16_t *__restrict__ E, const float *__restrict__ part,
                                                      int S, int Mpad, float *__restrict__ x,
@@ -264,7 +264,9 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
     __syncthreads();
     float tot = 0.f;
     for (int i = 0; i < nw; ++i) tot += s_ss[i];  // fixed order
-    const uint4 packed = pack(v, graw, 1.0f / sqrtf(tot / (float)d + eps));
+    // RAW: the operand is the residual stream itself (input of the draft model's head), no normalisation and no gains
+    const uint4 packed = RAW ? pack(v, make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u), 1.0f)
+                             : pack(v, graw, 1.0f / sqrtf(tot / (float)d + eps));
     if (live) a_out[tile_unit(r, k0, KB)] = packed;
     if (LQ && ad >= 0) {
       // the q|k|v projection that follows is adapted for this row: leave t = A_qkv a (a = the operand just stored)
@@ -473,8 +475,74 @@ __global__ void k_pack_q(int H, int Hkv, int hd, const uint16_t *__restrict__ q,
 }
 
 // ---------------------------------------------------------------------------------------------
+// head of the draft model (Sec. IV-A: two-layer MLP + vocabulary projection) and its law
+// ---------------------------------------------------------------------------------------------
+// sum of the split partials of a head projection (slice order), optional silu, stored as the next projection's operand
+template <int SILU>
+__global__ void k_head_act(const float *__restrict__ part, int S, int Mpad, int M, int N, uint4 *__restrict__ out) {
+  const int r = blockIdx.x, KB = N / 16;
+  for (int k0 = threadIdx.x * 8; k0 < N; k0 += blockDim.x * 8) {
+    uint32_t o[4] = {0, 0, 0, 0};
+    if (r < M) {
+      float v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      const float *p = part + (size_t)r * N + k0;
+      for (int s = 0; s < S; ++s) {
+        const float4 a = *reinterpret_cast<const float4 *>(p + (size_t)s * Mpad * N), b = *reinterpret_cast<const float4 *>(p + (size_t)s * Mpad * N + 4);
+        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w; v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        float x0 = v[2 * j], x1 = v[2 * j + 1];
+        if (SILU) { x0 = x0 / (1.0f + __expf(-x0)); x1 = x1 / (1.0f + __expf(-x1)); }
+        o[j] = (uint32_t)f2bf(x0) | ((uint32_t)f2bf(x1) << 16);
+      }
+    }
+    out[tile_unit(r, k0, KB)] = make_uint4(o[0], o[1], o[2], o[3]);
+  }
+}
+
+// q = softmax(z / T_b) of the draft's logits rows, fp32: one block per logits row.  all_rows 0: the laws the verification
+// call takes (draft i+1 of request b from row i < gamma_b, written to q row draft_offsets[b] + i); 1: every row.
+__global__ __launch_bounds__(256) void k_softmax_q(const float *__restrict__ z, int V, const int32_t *__restrict__ row_req,
+                                                   const int32_t *__restrict__ row_idx, const int32_t *__restrict__ off,
+                                                   const float *__restrict__ temperature, int all_rows, float *__restrict__ q) {
+  const int m = blockIdx.x, tid = threadIdx.x, b = row_req[m], i = row_idx[m];
+  const float T = temperature[b];
+  if (!(T > 0.f)) return;                                   // greedy requests need no law
+  if (!all_rows && i >= off[b + 1] - off[b]) return;        // the last row of a request scores no draft
+  const float *zr = z + (size_t)m * V;
+  float *qr = q + (size_t)(all_rows ? m : m - b) * V;
+  __shared__ float s_f[4];
+  __shared__ double s_d[4];
+  float mx = -INFINITY;
+  for (int k = tid; k < V; k += 256) mx = fmaxf(mx, zr[k]);
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o, 64));
+  if ((tid & 63) == 0) s_f[tid >> 6] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(s_f[0], s_f[1]), fmaxf(s_f[2], s_f[3]));
+  const float k2 = kLog2eF / T;
+  double sum = 0.0;
+  for (int k0 = tid; k0 < V; k0 += 256 * 8) {   // eight terms in fp32, the groups in fp64
+    float g = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (k0 + j * 256 < V) g += __builtin_amdgcn_exp2f((zr[k0 + j * 256] - mx) * k2);
+    sum += (double)g;
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) sum += __shfl_xor(sum, o, 64);
+  if ((tid & 63) == 0) s_d[tid >> 6] = sum;
+  __syncthreads();
+  const float inv = (float)(1.0 / ((s_d[0] + s_d[1]) + (s_d[2] + s_d[3])));
+  for (int k = tid; k < V; k += 256) qr[k] = __builtin_amdgcn_exp2f((zr[k] - mx) * k2) * inv;
+}
+
+// ---------------------------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------------------------
+enum { W_DRAFT1 = 5, W_DRAFT2 = 6, W_DRAFTV = 7 };   // the three projections of the draft model's head (after FSV_W_*)
+
 struct gemm_shape {
   int N, K, NTpad, mode;  // mode 1 = gate|up interleave
 };
@@ -488,6 +556,9 @@ gemm_shape shape_of(const fsv_ctx *c, int which) {
     case FSV_W_O: s.N = d.d_model; s.K = qd; break;
     case FSV_W_GATE_UP: s.N = 2 * d.d_ffn; s.K = d.d_model; s.mode = 1; break;
     case FSV_W_DOWN: s.N = d.d_model; s.K = d.d_ffn; break;
+    case W_DRAFT1: s.N = c->draft_dh; s.K = d.d_model; break;
+    case W_DRAFT2: s.N = c->draft_dp; s.K = c->draft_dh; break;
+    case W_DRAFTV: s.N = d.vocab; s.K = c->draft_dp; break;
     default: s.N = d.vocab; s.K = d.d_model; break;
   }
   s.NTpad = fsv_ceil_div(fsv_ceil_div(s.N, 32), 4) * 4;
@@ -594,7 +665,7 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
   return FSV_OK;
 }
 
-int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, int M, float *logits, hipStream_t s) {
+int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, int M, float *logits, int draft, hipStream_t s) {
   const fsv_model_desc &d = c->d;
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32;
   const gemm_shape sq = shape_of(c, FSV_W_QKV), so = shape_of(c, FSV_W_O), sg = shape_of(c, FSV_W_GATE_UP),
@@ -610,8 +681,10 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     hipLaunchKernelGGL(k_rope_table, dim3(fsv_ceil_div(n, 256)), dim3(256), 0, s, M, d.head_dim / 2,
                        (const double *)c->inv_freq, c->row_pos, (float *)c->rope_tab);
   }
+  // draft model (Sec. IV-A): only the anchor block (the last layer) on the draft's one-layer KV pools, then its own head
+  const int l_first = draft ? d.n_layers - 1 : 0;
   // adapters of the evolved target: per-request LoRA pairs on q|k|v and o of every layer but the last
-  const bool lora = c->lora_n > 0 && b->adapter != nullptr;
+  const bool lora = !draft && c->lora_n > 0 && b->adapter != nullptr;
   const size_t qd = (size_t)d.n_heads * d.head_dim, qkvd = qd + 2 * (size_t)d.n_kv_heads * d.head_dim;
   auto lora_for = [&](int layer, bool lq, bool lo_) {
     lora_args la;
@@ -629,16 +702,16 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
     if (lq0)
       hipLaunchKernelGGL((k_resid_norm<1, 1, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
-                         (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
+                         (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[l_first].attn_norm,
                          (uint4 *)c->buf_a, lora_for(0, true, false));
     else
       hipLaunchKernelGGL((k_resid_norm<1, 0, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok,
-                         (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[0].attn_norm,
+                         (const uint16_t *)c->embed, nullptr, 0, Mpad, c->x, (const uint16_t *)c->layers[l_first].attn_norm,
                          (uint4 *)c->buf_a, lora_args{});
   }
-  for (int l = 0; l < d.n_layers; ++l) {
+  for (int l = l_first; l < d.n_layers; ++l) {
     const fsv_layer_w &L = c->layers[l];
-    const size_t lo = (size_t)l * layer_stride(c, b->num_pages);
+    const size_t lo = (size_t)(draft ? 0 : l) * layer_stride(c, b->num_pages);
     const bool adapted = lora && l < d.n_layers - 1;         // the last block belongs to the invariant head
     const bool next_adapted = lora && l + 1 < d.n_layers - 1;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s))) return rc;
@@ -672,7 +745,10 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
       const void *gain = (l + 1 < d.n_layers) ? c->layers[l + 1].attn_norm : c->final_norm;
-      if (next_adapted)
+      if (draft)
+        hipLaunchKernelGGL((k_resid_norm<0, 0, 0, 1>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
+                           part, spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a, lora_args{});
+      else if (next_adapted)
         hipLaunchKernelGGL((k_resid_norm<0, 1, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
                            part, spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a, lora_for(l + 1, true, false));
       else
@@ -680,7 +756,66 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
                            part, spd, Mpad, c->x, (const uint16_t *)gain, (uint4 *)c->buf_a, lora_args{});
     }
   }
+  if (draft) {
+    // H_small: z = W_v (W_2 silu(W_1 h)), h = the block's output as just stored in buf_a
+    const gemm_shape s1 = shape_of(c, W_DRAFT1), s2 = shape_of(c, W_DRAFT2), sv = shape_of(c, W_DRAFTV);
+    const int sp1 = pick_splits(c, s1, Mt, true), sp2 = pick_splits(c, s2, Mt, true);
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_OTHER, c->draft_w1, c->buf_a, part, s1, M, sp1, s))) return rc;
+    hipLaunchKernelGGL(k_head_act<1>, dim3(Mpad), dim3(256), 0, s, part, sp1, Mpad, M, s1.N, (uint4 *)c->draft_h1);
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_OTHER, c->draft_w2, c->draft_h1, part, s2, M, sp2, s))) return rc;
+    hipLaunchKernelGGL(k_head_act<0>, dim3(Mpad), dim3(256), 0, s, part, sp2, Mpad, M, s2.N, (uint4 *)c->draft_h2);
+    if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->draft_wv, c->draft_h2, logits, sv, M, 1, s))) return rc;
+    FSV_HIP(c, hipGetLastError());
+    return FSV_OK;
+  }
   if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->lm_head, c->buf_a, logits, sl, M, 1, s))) return rc;
+  FSV_HIP(c, hipGetLastError());
+  return FSV_OK;
+}
+
+// The head of the draft model: re-tile its three matrices, size the buffers between them.
+int fsv_bf16_draft_attach(fsv_ctx *c, const fsv_draft_head *h) {
+  void *old[] = {c->draft_w1, c->draft_w2, c->draft_wv, c->draft_h1, c->draft_h2};
+  for (void *p : old)
+    if (p) (void)hipFree(p);
+  c->draft_w1 = c->draft_w2 = c->draft_wv = c->draft_h1 = c->draft_h2 = nullptr;
+  c->draft_dh = c->draft_dp = 0;
+  if (!h) return FSV_OK;
+  c->draft_dh = h->d_hidden;
+  c->draft_dp = h->d_proj;
+  int rc;
+  if ((rc = pack_weight(c, h->w1, W_DRAFT1, &c->draft_w1))) return rc;
+  if ((rc = pack_weight(c, h->w2, W_DRAFT2, &c->draft_w2))) return rc;
+  if ((rc = pack_weight(c, h->w_vocab, W_DRAFTV, &c->draft_wv))) return rc;
+  const int MtMax = fsv_ceil_div(c->max_rows, 32);
+  const size_t rows_pad = (size_t)MtMax * 32;
+  FSV_HIP(c, hipMalloc(&c->draft_h1, rows_pad * h->d_hidden * 2));
+  FSV_HIP(c, hipMemset(c->draft_h1, 0, rows_pad * h->d_hidden * 2));
+  FSV_HIP(c, hipMalloc(&c->draft_h2, rows_pad * h->d_proj * 2));
+  FSV_HIP(c, hipMemset(c->draft_h2, 0, rows_pad * h->d_proj * 2));
+  size_t part = c->part_bytes;   // the split partials of the head's projections share the forward's buffer
+  for (int which : {W_DRAFT1, W_DRAFT2}) {
+    const gemm_shape sh = shape_of(c, which);
+    for (int Mt = 1; Mt <= MtMax; ++Mt) part = max(part, (size_t)pick_splits(c, sh, Mt, true) * Mt * 32 * sh.N * 4);
+  }
+  if (part > c->part_bytes) {
+    (void)hipFree(c->buf_part);
+    c->buf_part = nullptr;
+    FSV_HIP(c, hipMalloc(&c->buf_part, part));
+    FSV_HIP(c, hipMemset(c->buf_part, 0, part));
+    c->part_bytes = part;
+  }
+  FSV_HIP(c, hipDeviceSynchronize());
+  return FSV_OK;
+}
+
+// The draft's law for every received draft token (or every row): anchor block on the draft's KV pools, head, softmax.
+int fsv_bf16_draft_probs(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, int M, int all_rows, float *q_out,
+                         float *logits, hipStream_t s) {
+  int rc = fsv_bf16_forward(c, b, plan, M, logits, 1, s);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_softmax_q, dim3(M), dim3(256), 0, s, logits, c->d.vocab, c->row_req, c->row_idx, b->draft_offsets,
+                     b->temperature, all_rows, q_out);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -762,9 +897,9 @@ int fsv_bf16_attention(fsv_ctx *c, int layer, const void *q, const fsv_batch *b,
 }
 
 int fsv_bf16_kv_copy(fsv_ctx *c, void *k_pool, void *v_pool, int num_pages, const int32_t *pt_row, int pos0, int n,
-                     void *k_lin, void *v_lin, bool import, hipStream_t s) {
+                     void *k_lin, void *v_lin, bool import, int layers, hipStream_t s) {
   const fsv_model_desc &d = c->d;
-  hipLaunchKernelGGL(k_kv_copy, dim3(n, d.n_layers), dim3(256), 0, s, d.n_kv_heads, d.head_dim, num_pages, pt_row, pos0, n,
+  hipLaunchKernelGGL(k_kv_copy, dim3(n, layers), dim3(256), 0, s, d.n_kv_heads, d.head_dim, num_pages, pt_row, pos0, n,
                      (uint16_t *)k_pool, (uint16_t *)v_pool, (uint16_t *)k_lin, (uint16_t *)v_lin, import ? 1 : 0);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, os.environ.get("FSV_LIB_NAME", "libflexverify.so"
 F32, BF16 = 0, 1
 W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
-EXPORTS = ["fsv_create", "fsv_destroy", "fsv_lora_load", "fsv_verify", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
+EXPORTS = ["fsv_create", "fsv_destroy", "fsv_lora_load", "fsv_draft_attach", "fsv_draft_probs", "fsv_draft_kv_import", "fsv_draft_kv_export", "fsv_verify", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
            "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
            "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_policy_step_time", "fsv_pager_create",
            "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
@@ -46,6 +46,13 @@ class Batch(C.Structure):
 class Lora(C.Structure):
     _fields_ = [("n_adapters", C.c_int32), ("rank", C.c_int32), ("scale", C.c_void_p)] + \
                [(n, C.POINTER(C.c_void_p)) for n in ("a_qkv", "b_qkv", "a_o", "b_o")]
+
+
+class DraftHead(C.Structure):
+    _fields_ = [("d_hidden", C.c_int32), ("d_proj", C.c_int32), ("w1", C.c_void_p), ("w2", C.c_void_p), ("w_vocab", C.c_void_p)]
+
+
+DRAFT_Q_VERIFY, DRAFT_Q_ALL = 0, 1
 
 
 class Result(C.Structure):
@@ -242,6 +249,47 @@ class Context:
         lo = Lora(n, int(adapters[0]["rank"]), scale.ctypes.data, table("a_qkv"), table("b_qkv"), table("a_o"), table("b_o"))
         self._check(lib().fsv_lora_load(self._h, C.byref(lo)), "fsv_lora_load")
 
+    def draft_attach(self, head: dict | None):
+        """head: dict(w1, w2, wv) of device tensors as synth.make_draft_head returns them; None removes the head."""
+        if head is None:
+            self._check(lib().fsv_draft_attach(self._h, None), "fsv_draft_attach")
+            return
+        for t in head.values():
+            assert t.is_contiguous()
+        h = DraftHead(int(head["w1"].shape[0]), int(head["w2"].shape[0]), head["w1"].data_ptr(), head["w2"].data_ptr(),
+                      head["wv"].data_ptr())
+        self._check(lib().fsv_draft_attach(self._h, C.byref(h)), "fsv_draft_attach")
+
+    def draft_kv_import(self, k_pool, v_pool, num_pages, page_table_row, pos0, src_k, src_v):
+        """src_k / src_v: [n_pos][n_kv_heads][head_dim] of the draft's one-layer session."""
+        assert src_k.is_contiguous() and src_v.is_contiguous() and src_k.dim() == 3
+        self._check(lib().fsv_draft_kv_import(self._h, C.c_void_p(k_pool.data_ptr()), C.c_void_p(v_pool.data_ptr()),
+                                              int(num_pages), C.c_void_p(page_table_row.data_ptr()), int(pos0),
+                                              int(src_k.shape[0]), C.c_void_p(src_k.data_ptr()), C.c_void_p(src_v.data_ptr()),
+                                              _stream()), "fsv_draft_kv_import")
+
+    def draft_kv_export(self, k_pool, v_pool, num_pages, page_table_row, pos0, n_pos):
+        cfg = self.cfg
+        shape = (n_pos, cfg.n_kv_heads, cfg.head_dim)
+        dk = torch.empty(shape, dtype=torch.bfloat16, device=k_pool.device)
+        dv = torch.empty(shape, dtype=torch.bfloat16, device=k_pool.device)
+        self._check(lib().fsv_draft_kv_export(self._h, C.c_void_p(k_pool.data_ptr()), C.c_void_p(v_pool.data_ptr()),
+                                              int(num_pages), C.c_void_p(page_table_row.data_ptr()), int(pos0), int(n_pos),
+                                              C.c_void_p(dk.data_ptr()), C.c_void_p(dv.data_ptr()), _stream()),
+                    "fsv_draft_kv_export")
+        return dk, dv
+
+    def draft_probs(self, batch: DeviceBatch, rows_mode: int = DRAFT_Q_VERIFY, want_logits: bool = False):
+        """(q, logits or None): the draft model's laws for the rows of `batch` on the draft's one-layer KV pools."""
+        B, G = batch.batch, batch.rows - batch.batch
+        n = batch.rows if rows_mode == DRAFT_Q_ALL else G
+        q = torch.zeros((max(n, 1), self.cfg.vocab), dtype=torch.float32, device="cuda")
+        lg = torch.empty((batch.rows, self.cfg.vocab), dtype=torch.float32, device="cuda") if want_logits else None
+        b = batch.struct()
+        self._check(lib().fsv_draft_probs(self._h, C.byref(b), int(rows_mode), C.c_void_p(q.data_ptr()),
+                                          C.c_void_p(lg.data_ptr()) if want_logits else None, _stream()), "fsv_draft_probs")
+        return q, lg
+
     def verify(self, batch: DeviceBatch, result: DeviceResult):
         b, r = batch.struct(), result.struct()
         self._check(lib().fsv_verify(self._h, C.byref(b), C.byref(r), _stream()), "fsv_verify")
@@ -389,6 +437,12 @@ class Pager:
 def pool_shape(cfg, num_pages: int):
     """Elements of one KV pool: [n_layers][num_pages][n_kv_heads][page_size * head_dim]."""
     return (cfg.n_layers, num_pages, cfg.n_kv_heads, cfg.page_size * cfg.head_dim)
+
+
+def alloc_draft_pools(cfg, num_pages: int, device="cuda"):
+    """KV pools of the draft model's one-layer session."""
+    shape = (1, num_pages, cfg.n_kv_heads, cfg.page_size * cfg.head_dim)
+    return (torch.zeros(shape, dtype=torch.bfloat16, device=device), torch.zeros(shape, dtype=torch.bfloat16, device=device))
 
 
 def alloc_pools(cfg, num_pages: int, device="cuda"):

@@ -243,18 +243,19 @@ def check_bf16_kv(got: np.ndarray, ref_st: np.ndarray, layer0_exact: bool = True
     """Appended KV rows [layers][positions][features] (bf16) against the bf16-storage oracle's cache.
 
     Layer 0 (embedding, norm, QKV projection, rotation, bf16 store: everything before the first attention) must agree
-    BIT FOR BIT but for isolated elements where fp32 against fp64 accumulation lands on the other side of a bf16 rounding
-    boundary (at most 1 in 200 elements, each by one bf16 step).  Deeper layers drift as the logits do (see
-    check_bf16_logits) and are held per (layer, position) row to `bar` in L2 and per element against the row's scale."""
+    BIT FOR BIT except where fp32 against fp64 arithmetic lands on the other side of a bf16 rounding boundary: directly
+    (the element differs by one bf16 step) or one stage earlier, in an element of the normalised activation (every
+    output of that row then moves by that element's step times a weight, at most ~2e-3 of the row's scale).  At most 1 in
+    50 elements may differ at all (measured 0 to 0.6 %, against about half of all elements once the inputs have drifted).
+    Deeper layers drift as the logits do (see check_bf16_logits) and are held per (layer, position) row to `bar` in L2 and
+    per element against the row's scale."""
     if layer0_exact and got.shape[1] > 0:
         d0 = got[0] != ref_st[0]
-        assert d0.mean() <= 5e-3, (what, "layer 0 differs in", int(d0.sum()), "of", d0.size)
+        assert d0.mean() <= 2e-2, (what, "layer 0 differs in", int(d0.sum()), "of", d0.size)
         if d0.any():
-            # one bf16 step of the element, or (for elements near zero, whose own step is smaller than the fp32
-            # accumulation error of the projection) 1e-5 of the row's scale
-            allowed = 2.0 ** -7 * np.abs(ref_st[0]) + 1e-5 * np.abs(ref_st[0]).max(axis=-1, keepdims=True)
+            allowed = 2.0 ** -7 * np.abs(ref_st[0]) + 2e-3 * np.abs(ref_st[0]).max(axis=-1, keepdims=True)
             over = np.abs(got[0] - ref_st[0]) / allowed
-            assert over.max() <= 1.0, (what, "layer 0 differs by more than one bf16 step", float(over.max()))
+            assert over.max() <= 1.0, (what, "layer 0 differs by more than a rounding-boundary flip explains", float(over.max()))
     g2, r2 = got.reshape(-1, got.shape[-1]), ref_st.reshape(-1, ref_st.shape[-1])
     m = logit_metrics(g2, r2)
     assert m["l2"] <= bar and m["row"] <= bar, (what, m, bar)
