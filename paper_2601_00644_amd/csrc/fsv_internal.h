@@ -59,6 +59,7 @@ struct fsv_ctx {
   int32_t *parg = nullptr;  // [max_rows][nc]
   double *bsum = nullptr;   // [max_batch][nsb]
   int32_t *tau_ws = nullptr;   // [max_batch]
+  int32_t *sel_ticket = nullptr;   // [max_batch] blocks of a request that have left their masses; zero between calls
   double *rowstat = nullptr;   // [max_batch][2]: max (as double), 1/S of the row the token is drawn from
   int32_t *acc_scratch = nullptr;  // [max_batch] accepted_len when the caller passes none
   uint32_t *rowkey = nullptr;      // [max_batch] nucleus cut key of the row the token is drawn from (0 = no cut)
