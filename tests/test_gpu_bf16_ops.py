@@ -17,18 +17,18 @@ from tests.helpers import logits_close
 pytestmark = pytest.mark.gpu
 
 
-def _ctx(cfg, seed, max_batch=8, max_gamma=16, max_pages=96, std=0.05):
+def _ctx(cfg, seed, max_batch=8, max_gamma=16, max_pages=96, std=0.05, max_rows=0):
     from paper_2601_00644_amd import flexverify as fv
     w = synth.make_weights(cfg, seed, std=std)
-    ctx = fv.Context(cfg, {k: v.cuda() for k, v in w.items()}, max_batch, max_gamma, max_pages)
+    ctx = fv.Context(cfg, {k: v.cuda() for k, v in w.items()}, max_batch, max_gamma, max_pages, max_rows=max_rows)
     return fv, ctx, w, synth.weights_to_numpy(cfg, w)
 
 
 @pytest.mark.parametrize("name", ["mini128", "mini64"])
-@pytest.mark.parametrize("M", [1, 5, 33, 88, 136])
+@pytest.mark.parametrize("M", [1, 5, 33, 88, 136, 224, 225, 257, 512, 883])   # up to the row counts of the batch-128 workload (several row blocks per weight strip)
 def test_linear_matches_oracle(name, M):
     cfg = synth.MODELS[name]
-    fv, ctx, w, wn = _ctx(cfg, 3, max_batch=8, max_gamma=16)
+    fv, ctx, w, wn = _ctx(cfg, 3, max_batch=8, max_gamma=16, max_rows=max(M, 136))
     g = torch.Generator().manual_seed(M)
     which = [(fv.W_QKV, "w_qkv.1", cfg.d_model), (fv.W_O, "w_o.0", cfg.n_heads * cfg.head_dim),
              (fv.W_GATE_UP, "w_gate_up.1", cfg.d_model), (fv.W_DOWN, "w_down.0", cfg.d_ffn),
