@@ -288,15 +288,14 @@ int fsv_attention(fsv_ctx *ctx, int32_t layer, const void *q, const fsv_batch *b
  * of the kernel classes whose bit (1u << FSV_K_*) is set in mask (0 = off, 0xffffffff = all; at most
  * 8192 launches are kept, later ones are not recorded).  For the GEMM and attention classes the pair
  * rides on the dispatch itself (start and stop of the kernel); for the other classes it is recorded on
- * the stream before and after the launches and so includes the dispatch gaps.  A class whose step takes
- * several launches (FSV_K_SAMPLE_ACCEPT: acceptance + masses; FSV_K_SAMPLE_STATS with a nucleus cut:
- * statistics, then the cut passes) reports them as they were bracketed.  fsv_profile_read() waits for the recorded
+ * the stream before and after the launches and so includes the dispatch gaps.  FSV_K_SAMPLE_NUCLEUS brackets
+ * all the cut passes of one call (one per key digit and per kind of cut) as one record.  fsv_profile_read() waits for the recorded
  * events and returns, per class, the number of launches, their summed duration and the algorithmic
  * bytes the host computed for them (weights for a GEMM, K and V for attention, logits and draft law
  * for the sampling kernels), then clears the records.  Returns the number of classes written (<= cap).
  */
 enum { FSV_K_GEMM_QKV = 0, FSV_K_GEMM_O, FSV_K_GEMM_GATE_UP, FSV_K_GEMM_DOWN, FSV_K_GEMM_LM_HEAD,
-       FSV_K_ATTENTION, FSV_K_ATTN_COMBINE, FSV_K_SAMPLE_STATS, FSV_K_SAMPLE_ACCEPT, FSV_K_SAMPLE_SELECT,
+       FSV_K_ATTENTION, FSV_K_ATTN_COMBINE, FSV_K_SAMPLE_STATS, FSV_K_SAMPLE_DECIDE, FSV_K_SAMPLE_NUCLEUS,
        FSV_K_NORM, FSV_K_ROPE_APPEND, FSV_K_OTHER, FSV_K_COUNT };
 typedef struct {
   int32_t kernel_class; /* FSV_K_*                       */

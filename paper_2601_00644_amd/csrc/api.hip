@@ -8,8 +8,8 @@
 namespace {
 
 const char *kClassNames[FSV_K_COUNT] = {"gemm_qkv",     "gemm_o",        "gemm_gate_up",  "gemm_down",  "gemm_lm_head",
-                                        "attention",    "attn_combine",  "sample_stats",  "sample_accept",
-                                        "sample_select", "norm",         "rope_append",   "other"};
+                                        "attention",    "attn_combine",  "sample_stats",  "sample_decide",
+                                        "sample_nucleus", "norm",         "rope_append",   "other"};
 
 template <typename T>
 int dev_alloc(fsv_ctx *c, T **p, size_t n) {

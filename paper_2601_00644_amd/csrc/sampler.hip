@@ -695,7 +695,8 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
   const bool nucleus = any_k || any_p;
   if (nucleus) {
     const int levels = (sizeof(LT) == 2) ? 2 : 3;
-    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_STATS, (double)M * V * sizeof(LT) * levels * ((any_k ? 1 : 0) + (any_p ? 1 : 0)));
+    const int passes = (any_k ? levels : 0) + 1 + (any_p ? levels - 1 : 0);
+    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_NUCLEUS, (double)M * V * sizeof(LT) * passes);
 #define FSV_NUC(LEVEL, LAST, MODE)                                                                                     \
   hipLaunchKernelGGL((k_nucleus<LT, LEVEL, LAST, MODE>), dim3(gmax + 1, B), dim3(1024), 0, s, logits, V, nc,             \
                      b->draft_offsets, b->temperature, b->top_p, b->top_k, c->pmax, c->nuc_prefix, c->nuc_above,          \
@@ -721,7 +722,7 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
 #undef FSV_NUC
   }
   {
-    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_ACCEPT, (double)B * V * (sizeof(LT) + 4));
+    fsv_prof_scope ps(c, s, FSV_K_SAMPLE_DECIDE, (double)B * V * (sizeof(LT) + 4));
     hipLaunchKernelGGL(k_decide<LT>, dim3(fsv_ceil_div(nsb, 4), B), dim3(256), 0, s, logits, V, nc, nsb, b->draft_offsets,
                        b->draft_tokens, b->draft_probs, b->u_accept, b->u_sample, b->temperature, c->pmax, c->psum, c->parg,
                        nucleus ? c->nuc_key : nullptr, nucleus ? c->nuc_S : nullptr, nucleus ? c->nuc_near : nullptr, c->bsum,
