@@ -42,33 +42,53 @@ namespace {
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
 
-// parts of a request with n key tiles when parts should hold about tpw tiles; *tp = tiles per part
-__device__ __host__ inline int attn_parts(int n, int tpw, int *tp) {
+// parts of a request with n key tiles when a part of a request with ONE query-row tile should hold about tpw tiles;
+// *tp = tiles per part.  A key tile costs a wave more when the request has more query rows (every further row tile
+// repeats the score and value products and the softmax arithmetic on the same K/V registers), so such a request is
+// cut into shorter parts, by the measured cost ratio w16 / 16: all waves then finish at about the same time.
+__device__ __host__ inline int attn_parts(int n, int tpw, int w16, int *tp) {
+  tpw = max(1, tpw * 16 / w16);
   const int s0 = (n + tpw - 1) / tpw;
   *tp = (n + s0 - 1) / s0;
   return (n + *tp - 1) / *tp;
 }
 
 // part_prefix[b] = parts of requests before b (the merge kernel's index); part_desc[global part] = everything a wave of
-// the attention kernel needs to start, in one 32-byte record: request, first tile, tiles, parts of the request, cached
-// length, drafts, first row, (pad) -- a wave fetches it with a single scalar load instead of a chain of dependent ones
-__global__ void k_attn_plan(int B, int tpw, const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ off,
-                            int32_t *__restrict__ part_prefix, int32_t *__restrict__ part_desc, int map_cap) {
-  if (blockIdx.x != 0 || threadIdx.x != 0) return;
-  int run = 0;
-  for (int b = 0; b < B; ++b) {
-    const int L = seq_lens[b], gamma = off[b + 1] - off[b], nk = L + gamma + 1, n = (nk + 31) >> 5;
-    int tp;
-    const int s = attn_parts(n, tpw, &tp);
-    part_prefix[b] = run;
-    for (int p = 0; p < s && run + p < map_cap; ++p) {
-      int32_t *d = part_desc + (size_t)(run + p) * 8;
-      d[0] = b; d[1] = p * tp; d[2] = min(n, (p + 1) * tp) - p * tp; d[3] = s;
-      d[4] = L; d[5] = gamma; d[6] = off[b] + b; d[7] = 0;
+// the attention kernel needs to start, in one 48-byte record: request, first tile, tiles, parts of the request, cached
+// length, drafts, first row, (pad), and the physical pages of the part's first two tiles -- a wave fetches it with three
+// scalar loads and can issue its first K/V loads at once, instead of after a chain of dependent ones
+constexpr int kDescInts = 12;
+__global__ void k_attn_plan(int B, int tpw, int group, int w2, int w3, const int32_t *__restrict__ seq_lens,
+                            const int32_t *__restrict__ off, const int32_t *__restrict__ page_table, int max_pages,
+                            int num_pages, int32_t *__restrict__ part_prefix, int32_t *__restrict__ part_desc, int map_cap) {
+  if (blockIdx.x != 0) return;
+  __shared__ int total;
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int b = 0; b < B; ++b) {
+      const int L = seq_lens[b], gamma = off[b + 1] - off[b], nk = L + gamma + 1, n = (nk + 31) >> 5;
+      const int rtc = (group * (gamma + 1) + 31) >> 5;
+      int tp;
+      const int s = attn_parts(n, tpw, rtc <= 1 ? 16 : rtc == 2 ? w2 : w3, &tp);
+      part_prefix[b] = run;
+      for (int p = 0; p < s && run + p < map_cap; ++p) {
+        int32_t *d = part_desc + (size_t)(run + p) * kDescInts;
+        d[0] = b; d[1] = p * tp; d[2] = min(n, (p + 1) * tp) - p * tp; d[3] = s;
+        d[4] = L; d[5] = gamma; d[6] = off[b] + b; d[7] = 0;
+      }
+      run += s;
     }
-    run += s;
+    part_prefix[B] = run;
+    total = min(run, map_cap);
   }
-  part_prefix[B] = run;
+  __syncthreads();   // the records written above are read back below by other threads of this block
+  for (int p = threadIdx.x; p < total; p += blockDim.x) {
+    int32_t *d = part_desc + (size_t)p * kDescInts;
+    const int b = d[0], t0 = d[1], npg = (d[4] + d[5] + 1 + 15) >> 4;
+    const int32_t *pt = page_table + (size_t)b * max_pages;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) d[8 + i] = min(max(pt[min(2 * t0 + i, npg - 1)], 0), num_pages - 1);
+  }
 }
 
 template <int HD, int RT, int NB>
@@ -84,8 +104,9 @@ __global__ __launch_bounds__(64) void k_attention(
   __shared__ uint4 s_q[2][RT * KS * 64];  // hi and lo planes of the query operand
   const int lane = threadIdx.x, h = lane >> 5, r = lane & 31;
   const int gw = blockIdx.x, pp = gw / Hkv, kvh = gw - pp * Hkv;
-  const int4 d0 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * 8);
-  const int4 d1 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * 8 + 4);
+  const int4 d0 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * kDescInts);
+  const int4 d1 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * kDescInts + 4);
+  const int4 d2 = *reinterpret_cast<const int4 *>(part_desc + (size_t)pp * kDescInts + 8);
   const int b = d0.x, t0 = d0.y, myt = d0.z, nparts = d0.w, L = d1.x, gamma = d1.y, rs = d1.z;
   const int nk = L + gamma + 1, R = group * (gamma + 1);
   const int rtc = min(RT, (R + 31) >> 5);
@@ -132,9 +153,10 @@ __global__ __launch_bounds__(64) void k_attention(
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src + q_plane_units),
                                      (__attribute__((address_space(3))) void *)&s_q[1][i * 64], 16, 0, 0);
   }
-  int gp0[NB], gp1[NB];
+  int gp0[NB], gp1[NB];   // pages of the first NB tiles: two tiles' worth came with the record
+  gp0[0] = d2.x; gp1[0] = d2.y; gp0[1] = d2.z; gp1[1] = d2.w;
 #pragma unroll
-  for (int s = 0; s < NB; ++s) pages_of(s, gp0[s], gp1[s]);
+  for (int s = 2; s < NB; ++s) pages_of(s, gp0[s], gp1[s]);
   __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): the queries are in LDS
   __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -387,12 +409,16 @@ constexpr int kAttnWavesPerCu = 3;  // a wave takes most of a SIMD's registers, 
 int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
   const fsv_model_desc &d = c->d;
   int max_rows = 0;
-  long total_tiles = 0;
+  long total_tiles = 0;   // in units of the cost of a tile of a request with one query-row tile
+  auto w16_of = [&](int g) {
+    const int rtc = fsv_ceil_div(c->group * (g + 1), 32);
+    return rtc <= 1 ? 16 : rtc == 2 ? c->attn_w2 : c->attn_w3;
+  };
   for (int i = 0; i < b->batch; ++i) {
     const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
     const int n = fsv_ceil_div(nk, 32);
     max_rows = max(max_rows, c->group * (g + 1));
-    total_tiles += n;
+    total_tiles += ((long)n * w16_of(g) + 15) / 16;
     pl->kv_tokens += nk;
   }
   // One round if it can be had: the smallest part length, up to twice the even share, for which parts x kv heads fit the
@@ -406,7 +432,7 @@ int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
     for (int i = 0; i < b->batch; ++i) {
       const int g = b->draft_offsets_host[i + 1] - b->draft_offsets_host[i], nk = b->seq_lens_host[i] + g + 1;
       int tp;
-      const int s = attn_parts(fsv_ceil_div(nk, 32), tpw, &tp);
+      const int s = attn_parts(fsv_ceil_div(nk, 32), tpw, w16_of(g), &tp);
       parts += s;
       *split |= s > 1;
     }
@@ -429,7 +455,8 @@ int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
 }
 
 int launch_attn_plan(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan &pl, hipStream_t st) {
-  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(64), 0, st, b->batch, pl.tpw, b->seq_lens, b->draft_offsets,
+  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(64), 0, st, b->batch, pl.tpw, c->group, c->attn_w2, c->attn_w3, b->seq_lens, b->draft_offsets,
+                     b->page_table, c->d.max_pages_per_req, b->num_pages,
                      c->attn_part_prefix, c->attn_part_map, c->attn_wave_cap / c->d.n_kv_heads + 1);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
@@ -495,9 +522,11 @@ int fsv_bf16_attn_create(fsv_ctx *c) {
   const fsv_model_desc &d = c->d;
   int wpc = kAttnWavesPerCu;
   c->attn_depth = 2;
-  if (const char *e = getenv("FSV_ATTN_TUNE")) {   // "waves per CU,tiles in flight": measurement knob
-    int a = 0, bb = 0;
-    if (sscanf(e, "%d,%d", &a, &bb) == 2 && a >= 1 && a <= 8 && bb >= 2 && bb <= 3) { wpc = a; c->attn_depth = bb; }
+  if (const char *e = getenv("FSV_ATTN_TUNE")) {   // "waves per CU,tiles in flight[,w2,w3]": measurement knob
+    int a = 0, bb = 0, w2 = c->attn_w2, w3 = c->attn_w3;
+    const int n = sscanf(e, "%d,%d,%d,%d", &a, &bb, &w2, &w3);
+    if (n >= 2 && a >= 1 && a <= 8 && bb >= 2 && bb <= 3) { wpc = a; c->attn_depth = bb; }
+    if (n == 4 && w2 >= 16 && w2 <= 64 && w3 >= w2 && w3 <= 96) { c->attn_w2 = w2; c->attn_w3 = w3; }
   }
   c->attn_wave_target = c->n_cus * wpc;
   c->attn_wave_cap = 4 * c->attn_wave_target + 2 * d.max_batch * d.n_kv_heads;  // multi-round schedules: see plan_attention
@@ -511,6 +540,6 @@ int fsv_bf16_attn_create(fsv_ctx *c) {
   int rc;
   if ((rc = zalloc(&c->attn_part, c->attn_part_bytes))) return rc;
   if ((rc = zalloc((void **)&c->attn_part_prefix, sizeof(int32_t) * (d.max_batch + 1)))) return rc;
-  if ((rc = zalloc((void **)&c->attn_part_map, sizeof(int32_t) * 8 * (c->attn_wave_cap / d.n_kv_heads + 1)))) return rc;
+  if ((rc = zalloc((void **)&c->attn_part_map, sizeof(int32_t) * kDescInts * (c->attn_wave_cap / d.n_kv_heads + 1)))) return rc;
   return FSV_OK;
 }

@@ -82,6 +82,7 @@ struct fsv_ctx {
   int attn_wave_target = 0;     // waves the attention schedule aims at (resident waves of the device)
   int attn_wave_cap = 0;        // waves the partial buffers hold
   int attn_depth = 2;           // K/V tiles in flight per attention wave
+  int attn_w2 = 26, attn_w3 = 36;  // cost of a key tile for a request with two / three query-row tiles, in 1/16 of one with one
   int32_t *attn_part_prefix = nullptr, *attn_part_map = nullptr;   // parts before each request; 8-int record per part
 
   // LoRA adapters of the evolved target (bf16 path): tables [layer < n_layers - 1][adapter][...], library-owned
