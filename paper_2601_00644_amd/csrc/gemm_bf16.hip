@@ -13,6 +13,7 @@
 // stage to the compute waves and a consumed one back to the loader.
 #include <hip/hip_ext.h>
 #include <math.h>
+#include <stdlib.h>
 
 #include "bf16_common.h"
 
@@ -32,6 +33,104 @@ constexpr int KC = 8;     // 16-wide k blocks per chunk (128 contraction element
 constexpr int NST = 3;    // LDS stages of the activation ring
 constexpr int GRAN = 2;   // chunks per 256-element granule of the K cut
 constexpr int NLD = 2;    // loader waves per block: two halve the time of the first fills, which matters for the short split-K blocks
+
+// Stores one wave's result: for row tiles mt < mtc of the block starting at tile mt0, lane holds, for batch row
+// m = tile*32 + lane%32, features nt*32 + 8*(v/4) + 4*h + v%4 of strip nt.
+template <int MT, int EPI>
+__device__ __forceinline__ void store_strip(const f32x16_t (&acc)[MT], void *__restrict__ out, int nt, int mt0, int mtc, int lane,
+                                            int h, int split, int M, int Mpad, int N, int KBo) {
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if (mt >= mtc) continue;
+    const int m = (mt0 + mt) * 32 + (lane & 31);
+    if constexpr (EPI == EPI_PARTIAL) {
+      if (m >= M) continue;  // the consumers read rows below M only
+      float *dst = (float *)out + ((size_t)split * Mpad + m) * N;
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int n0 = nt * 32 + 8 * g + 4 * h;
+        if (n0 + 3 < N) {
+          *reinterpret_cast<float4 *>(dst + n0) =
+              make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
+        } else {
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
+        }
+      }
+    } else if constexpr (EPI == EPI_F32) {
+      if (m < M) {
+        float *dst = (float *)out + (size_t)m * N;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const int n0 = nt * 32 + 8 * g + 4 * h;
+          if (n0 + 3 < N && (N & 3) == 0) {
+            *reinterpret_cast<float4 *>(dst + n0) =
+                make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
+          } else {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
+          }
+        }
+      }
+    } else {  // SwiGLU: regs 0-3 gate / 4-7 up of features 16*nt + 4h + r, regs 8-11 / 12-15 of 16*nt + 8 + 4h + r
+      if (nt < KBo) {
+        uint16_t *base = (uint16_t *)out;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          uint16_t o4[4];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const float gte = acc[mt][8 * j + r], up = acc[mt][8 * j + 4 + r];
+            o4[r] = f2bf(gte / (1.0f + __expf(-gte)) * up);
+          }
+          const size_t unit = ((size_t)(mt0 + mt) * KBo + nt) * 64 + (lane & 31) + 32 * j;
+          uint2 pk = make_uint2((uint32_t)o4[0] | ((uint32_t)o4[1] << 16), (uint32_t)o4[2] | ((uint32_t)o4[3] << 16));
+          *reinterpret_cast<uint2 *>(base + unit * 8 + 4 * h) = pk;
+        }
+      }
+    }
+  }
+}
+
+// Loader wave lw of a block: activation chunk `it` -> LDS stage it % NST, one 1 KiB row of units per instruction; loader
+// wave l takes the rows i with i % NLD == l.  Meets 1 + per barriers, as every compute wave of the block does.
+template <int MT>
+__device__ __forceinline__ void loader_wave(uint4 *lds, const uint4 *__restrict__ Ap, int lw, int lane, int mt0, int mlast,
+                                            int KB, int cb0, int per) {
+  constexpr int CHU = MT * KC * 64;
+  constexpr int PERW = (MT * KC + NLD - 1) / NLD;  // instructions per loader wave and chunk
+  auto fill = [&](int it) {
+    uint4 *dst = lds + (it % NST) * CHU;
+#pragma unroll
+    for (int j = 0; j < PERW; ++j) {
+      const int i = min(j * NLD + lw, MT * KC - 1);  // (a repeated last row when the split is uneven)
+      const int mt = min(i / KC, mlast);
+      const uint4 *src = Ap + ((size_t)(mt0 + mt) * KB + (size_t)(cb0 + it) * KC + i % KC) * 64 + lane;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
+                                       (__attribute__((address_space(3))) void *)(dst + i * 64), 16, 0, 0);
+    }
+  };
+  fill(0);
+  if (per > 1) {
+    fill(1);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PERW) : "memory");  // chunk 0 has landed, chunk 1 may be in flight
+  } else {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  FSV_BARRIER();
+  for (int it = 0; it < per; ++it) {
+    // stage (it + 2) % NST was read during step it - 1, which every compute wave left at the last barrier
+    if (it + 2 < per) {
+      fill(it + 2);
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PERW) : "memory");  // chunk it + 1 has landed
+    } else {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    FSV_BARRIER();
+  }
+}
 
 template <int MT, int EPI, int D>
 __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
@@ -65,39 +164,7 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
   const int cb0 = (split * nchunks / S) * GRAN, per = ((split + 1) * nchunks / S) * GRAN - cb0;
 
   if (w >= 4) {
-    // ---- loader waves: activation chunk `it` -> LDS stage it % NST, one 1 KiB row of units per instruction; loader
-    // wave l takes the rows i with i % NLD == l ----
-    constexpr int PERW = (MT * KC + NLD - 1) / NLD;  // instructions per loader wave and chunk
-    const int lw = w - 4;
-    auto fill = [&](int it) {
-      uint4 *dst = lds + (it % NST) * CHU;
-#pragma unroll
-      for (int j = 0; j < PERW; ++j) {
-        const int i = min(j * NLD + lw, MT * KC - 1);  // (a repeated last row when the split is uneven)
-        const int mt = min(i / KC, mlast);
-        const uint4 *src = Ap + ((size_t)(mt0 + mt) * KB + (size_t)(cb0 + it) * KC + i % KC) * 64 + lane;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)src,
-                                         (__attribute__((address_space(3))) void *)(dst + i * 64), 16, 0, 0);
-      }
-    };
-    fill(0);
-    if (per > 1) {
-      fill(1);
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PERW) : "memory");  // chunk 0 has landed, chunk 1 may be in flight
-    } else {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    FSV_BARRIER();
-    for (int it = 0; it < per; ++it) {
-      // stage (it + 2) % NST was read during step it - 1, which every compute wave left at the last barrier
-      if (it + 2 < per) {
-        fill(it + 2);
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PERW) : "memory");  // chunk it + 1 has landed
-      } else {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      }
-      FSV_BARRIER();
-    }
+    loader_wave<MT>(lds, Ap, w - 4, lane, mt0, mlast, KB, cb0, per);
     return;
   }
 
@@ -164,60 +231,7 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
     }
   }
 
-  // epilogue: lane holds, for batch row m = tile*32 + lane%32, features nt*32 + 8*(v/4) + 4*h + v%4
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    if (mt >= mtc) continue;
-    const int m = (mt0 + mt) * 32 + (lane & 31);
-    if constexpr (EPI == EPI_PARTIAL) {
-      if (m >= M) continue;  // the consumers read rows below M only
-      float *dst = (float *)out + ((size_t)split * Mpad + m) * N;
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const int n0 = nt * 32 + 8 * g + 4 * h;
-        if (n0 + 3 < N) {
-          *reinterpret_cast<float4 *>(dst + n0) =
-              make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
-        } else {
-#pragma unroll
-          for (int r = 0; r < 4; ++r)
-            if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
-        }
-      }
-    } else if constexpr (EPI == EPI_F32) {
-      if (m < M) {
-        float *dst = (float *)out + (size_t)m * N;
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const int n0 = nt * 32 + 8 * g + 4 * h;
-          if (n0 + 3 < N && (N & 3) == 0) {
-            *reinterpret_cast<float4 *>(dst + n0) =
-                make_float4(acc[mt][4 * g], acc[mt][4 * g + 1], acc[mt][4 * g + 2], acc[mt][4 * g + 3]);
-          } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (n0 + r < N) dst[n0 + r] = acc[mt][4 * g + r];
-          }
-        }
-      }
-    } else {  // SwiGLU: regs 0-3 gate / 4-7 up of features 16*nt + 4h + r, regs 8-11 / 12-15 of 16*nt + 8 + 4h + r
-      if (nt < KBo) {
-        uint16_t *base = (uint16_t *)out;
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          uint16_t o4[4];
-#pragma unroll
-          for (int r = 0; r < 4; ++r) {
-            const float gte = acc[mt][8 * j + r], up = acc[mt][8 * j + 4 + r];
-            o4[r] = f2bf(gte / (1.0f + __expf(-gte)) * up);
-          }
-          const size_t unit = ((size_t)(mt0 + mt) * KBo + nt) * 64 + (lane & 31) + 32 * j;
-          uint2 pk = make_uint2((uint32_t)o4[0] | ((uint32_t)o4[1] << 16), (uint32_t)o4[2] | ((uint32_t)o4[3] << 16));
-          *reinterpret_cast<uint2 *>(base + unit * 8 + 4 * h) = pk;
-        }
-      }
-    }
-  }
+  store_strip<MT, EPI>(acc, out, nt, mt0, mtc, lane, h, split, M, Mpad, N, KBo);
 }
 
 template <int MT, int EPI>
