@@ -98,7 +98,7 @@ void fsv_destroy(fsv_ctx *c) {
   if (!c) return;
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
-                  c->pmax, c->psum, c->parg, c->bsum, c->tau_ws, c->rowstat, c->acc_scratch, c->sel_ticket, c->rowkey, c->nuc_prefix,
+                  c->pmax, c->psum, c->parg, c->bsum, c->acc_scratch, c->sel_ticket, c->nuc_prefix,
                   c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
                   c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map,
                   c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t,
@@ -148,11 +148,10 @@ int fsv_create(const fsv_model_desc *desc, const fsv_weights *w, fsv_ctx **out) 
   A(dev_alloc(c, &c->row_req, R)); A(dev_alloc(c, &c->row_idx, R)); A(dev_alloc(c, &c->row_pos, R));
   A(dev_alloc(c, &c->row_tok, R));
   A(dev_alloc(c, &c->pmax, R * c->nc)); A(dev_alloc(c, &c->psum, R * c->nc)); A(dev_alloc(c, &c->parg, R * c->nc));
-  A(dev_alloc(c, &c->bsum, B * c->nsb)); A(dev_alloc(c, &c->tau_ws, B)); A(dev_alloc(c, &c->rowstat, 2 * B));
+  A(dev_alloc(c, &c->bsum, B * c->nsb));
   A(dev_alloc(c, &c->acc_scratch, B));
   A(dev_alloc(c, &c->sel_ticket, B));
   if (rc == FSV_OK && hipMemset(c->sel_ticket, 0, sizeof(int32_t) * B) != hipSuccess) rc = FSV_E_HIP;
-  A(dev_alloc(c, &c->rowkey, B));
   A(dev_alloc(c, &c->nuc_prefix, R)); A(dev_alloc(c, &c->nuc_key, R)); A(dev_alloc(c, &c->nuc_above, R));
   A(dev_alloc(c, &c->nuc_total, R)); A(dev_alloc(c, &c->nuc_S, R)); A(dev_alloc(c, &c->nuc_near, R));
   A(dev_alloc(c, &c->nuc_cabove, R)); A(dev_alloc(c, &c->nuc_kkey, R)); A(dev_alloc(c, &c->nuc_kmass, R));

@@ -58,11 +58,8 @@ struct fsv_ctx {
   double *psum = nullptr;   // [max_rows][nc]
   int32_t *parg = nullptr;  // [max_rows][nc]
   double *bsum = nullptr;   // [max_batch][nsb]
-  int32_t *tau_ws = nullptr;   // [max_batch]
   int32_t *sel_ticket = nullptr;   // [max_batch] blocks of a request that have left their masses; zero between calls
-  double *rowstat = nullptr;   // [max_batch][2]: max (as double), 1/S of the row the token is drawn from
   int32_t *acc_scratch = nullptr;  // [max_batch] accepted_len when the caller passes none
-  uint32_t *rowkey = nullptr;      // [max_batch] nucleus cut key of the row the token is drawn from (0 = no cut)
   // nucleus (top-p) selection, per logits row: digit-by-digit state, then the cut key, the kept mass, the near flag
   uint32_t *nuc_prefix = nullptr, *nuc_key = nullptr, *nuc_cabove = nullptr, *nuc_kkey = nullptr;
   unsigned long long *nuc_above = nullptr, *nuc_total = nullptr, *nuc_kmass = nullptr;

@@ -797,8 +797,8 @@ bool carve_static(fsv_ctx &c, unsigned char *base) {
   c.row_req = (int32_t *)take(4 * R); c.row_idx = (int32_t *)take(4 * R); c.row_pos = (int32_t *)take(4 * R);
   c.row_tok = (int32_t *)take(4 * R);
   c.pmax = (float *)take(4 * R * NC); c.psum = (double *)take(8 * R * NC); c.parg = (int32_t *)take(4 * R * NC);
-  c.bsum = (double *)take(8 * B * NSB); c.tau_ws = (int32_t *)take(4 * B); c.rowstat = (double *)take(16 * B);
-  c.acc_scratch = (int32_t *)take(4 * B); c.rowkey = (uint32_t *)take(4 * B);
+  c.bsum = (double *)take(8 * B * NSB);
+  c.acc_scratch = (int32_t *)take(4 * B);
   c.nuc_prefix = (uint32_t *)take(4 * R); c.nuc_key = (uint32_t *)take(4 * R);
   c.nuc_above = (unsigned long long *)take(8 * R); c.nuc_total = (unsigned long long *)take(8 * R);
   c.nuc_S = (double *)take(8 * R); c.nuc_near = (int32_t *)take(4 * R);
