@@ -99,7 +99,7 @@ void fsv_destroy(fsv_ctx *c) {
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->acc_scratch, c->sel_ticket, c->nuc_prefix,
-                  c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
+                  c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_done, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
                   c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map,
                   c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t,
                   c->draft_w1, c->draft_w2, c->draft_wv, c->draft_h1, c->draft_h2};
@@ -155,6 +155,7 @@ int fsv_create(const fsv_model_desc *desc, const fsv_weights *w, fsv_ctx **out) 
   A(dev_alloc(c, &c->nuc_prefix, R)); A(dev_alloc(c, &c->nuc_key, R)); A(dev_alloc(c, &c->nuc_above, R));
   A(dev_alloc(c, &c->nuc_total, R)); A(dev_alloc(c, &c->nuc_S, R)); A(dev_alloc(c, &c->nuc_near, R));
   A(dev_alloc(c, &c->nuc_cabove, R)); A(dev_alloc(c, &c->nuc_kkey, R)); A(dev_alloc(c, &c->nuc_kmass, R));
+  A(dev_alloc(c, &c->nuc_done, R));
   if (rc == FSV_OK && d.n_layers > 0) {
     const size_t rows_pad = (R + 31) / 32 * 32;
     A(dev_alloc(c, &c->x, rows_pad * d.d_model));

@@ -64,7 +64,7 @@ struct fsv_ctx {
   uint32_t *nuc_prefix = nullptr, *nuc_key = nullptr, *nuc_cabove = nullptr, *nuc_kkey = nullptr;
   unsigned long long *nuc_above = nullptr, *nuc_total = nullptr, *nuc_kmass = nullptr;
   double *nuc_S = nullptr;
-  int32_t *nuc_near = nullptr;
+  int32_t *nuc_near = nullptr, *nuc_done = nullptr;   // nuc_done[row]: the windowed pass has settled the row's cut
 
   // model workspace (both paths)
   float *x = nullptr;       // [rows_pad][d_model] residual stream, fp32

@@ -11,13 +11,16 @@
 //                 through memory), then the blocks of a request stream the one row its token is drawn from (and the
 //                 draft-law row) into the masses of its 2048-id sub-blocks; the block that finishes last (an integer
 //                 ticket per request) locates the sub-block and the id by inverse CDF, emits the outputs and rolls back
-// plus, when a request asks for a top-k / nucleus (top-p) cut of the target law, k_nucleus: one more pass over every
-// logits row per digit of the cut value (two for bf16 logits, three for fp32) and stage, between the two.
+// plus, when a request asks for a top-k / nucleus (top-p) cut of the target law, between the two: for bf16 logits
+// k_nucleus_top, ONE pass per stage that settles every row whose cut lies within one (first try) or two (second try)
+// binades of the row maximum; for the rows it leaves, and for fp32 logits, k_nucleus: one pass over the row per digit
+// of the cut value (two for bf16 logits, three for fp32) and stage.
 // Rows are addressed as (request, row within the request), so the step needs no row map.  Every floating-point sum is
 // taken in a fixed order (the ticket only decides WHICH block adds the sub-block masses up, in sub-block order); the only
 // other atomics are integer adds into the nucleus histograms, whose result does not depend on their order.
 #include <limits.h>
 #include <math.h>
+#include <type_traits>
 #include <mutex>
 
 #include "fsv_internal.h"
@@ -239,11 +242,12 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
                                                   uint32_t *__restrict__ st_cabove, unsigned long long *__restrict__ st_total,
                                                   uint32_t *__restrict__ kkey, unsigned long long *__restrict__ kmass,
                                                   uint32_t *__restrict__ nuc_key, double *__restrict__ nuc_S,
-                                                  int32_t *__restrict__ nuc_near, int vec) {
+                                                  int32_t *__restrict__ nuc_near, const int32_t *__restrict__ done, int vec) {
   constexpr int SHIFT = (LEVEL == 0) ? 21 : (LEVEL == 1 ? 10 : 0), BITS = (LEVEL == 2) ? 10 : 11;
   const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;   // grid = (largest gamma + 1, requests)
   if ((int)blockIdx.x > off[b + 1] - off[b]) return;
   const int r = off[b] + b + blockIdx.x;
+  if (done && done[r]) return;   // k_nucleus_top has settled this row
   const float T = temperature[b], tp = top_p ? top_p[b] : 1.f;
   const int tk = top_k ? top_k[b] : 0;
   const bool use_k = T > 0.f && tk > 0 && tk < V, use_p = T > 0.f && tp < 1.f;
@@ -281,10 +285,7 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
   const uint32_t prefix = (LEVEL > 0) ? st_prefix[r] : 0u;
   const uint32_t lowkey = (MODE == 0 && use_k) ? kkey[r] : 0u;   // top-p works on what the top-k cut kept
   const LT *row = logits + (size_t)r * V;
-  for (int i0 = tid * 8; i0 < V; i0 += 1024 * 8) {
-    float v[8];
-    if (vec && i0 + 8 <= V) loader<LT>::load8_fast(row, i0, v);
-    else loader<LT>::load8(row, i0, V, vec != 0, -INFINITY, v);
+  auto add8 = [&](int i0, const float (&v)[8]) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       if (i0 + j >= V) continue;   // ids beyond the vocabulary are not tokens (they would count for top-k)
@@ -296,6 +297,25 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
       if (q) atomicAdd(&hist[bin], q);
       if (MODE == 1) atomicAdd(&hcnt[bin], 1u);
     }
+  };
+  // Rounds of U loads per thread issued back to back, without a branch between them (a branch per load makes the wave
+  // wait for each load before the next, and the pass then runs at one memory round trip per 8192 ids of the row); the
+  // ragged end of the row takes the guarded loads one by one.
+  constexpr int U = 4, STEP = 1024 * 8;
+  int base = tid * 8;
+  if (vec) {
+    for (; base + (U - 1) * STEP + 8 <= V; base += U * STEP) {
+      float v[U][8];
+#pragma unroll
+      for (int u = 0; u < U; ++u) loader<LT>::load8_fast(row, base + u * STEP, v[u]);
+#pragma unroll
+      for (int u = 0; u < U; ++u) add8(base + u * STEP, v[u]);
+    }
+  }
+  for (; base < V; base += STEP) {
+    float v[8];
+    loader<LT>::load8(row, base, V, vec != 0, -INFINITY, v);
+    add8(base, v);
   }
   __syncthreads();
   if (tid >= 64) return;
@@ -372,6 +392,182 @@ __global__ __launch_bounds__(1024) void k_nucleus(const LT *__restrict__ logits,
     const double lo = target - (double)acc, hi = (double)kept - target;
     nuc_near[r] = (fmin(lo, hi) < 1e-6 * (double)total) ? 1 : 0;
   }
+}
+
+// The same selection for bf16 logits in ONE pass whenever the cut lies near the top of the row, which is where a top-p
+// or top-k cut lies in practice: only the W highest digit values at and below the row maximum's digit (W = 4: one binade
+// of the logit, tried first; W = 8: two binades, for the rows the first try leaves) get histogram bins, 32 each (a bf16 key has five bits below the digit, so a bin is one key: the second
+// level comes for free).  Every other token is dismissed after a look at its key: the pass needs no exponential and no
+// LDS atomic for it, which is what bounds the full pass.  The row's total mass, against which top_p is measured, is not
+// summed again either: it is the normaliser the statistics pass already left (or, after a top-k cut, the mass that
+// cut kept).  That total differs from the integer sum the full passes form by the rounding of a floating-point sum
+// (1e-7 relative); the rows where that could matter are the ones within 1e-6 of the cut, which are flagged in any case.
+// A row whose cut lies below the window is left to the full passes (done[r] = 0).
+template <int MODE, int W, bool FIRST>
+__global__ __launch_bounds__(1024) void k_nucleus_top(const uint16_t *__restrict__ logits, int V, int nc,
+                                                      const int32_t *__restrict__ off,
+                                                      const float *__restrict__ temperature,
+                                                      const float *__restrict__ top_p, const int32_t *__restrict__ top_k,
+                                                      const float *__restrict__ pmax, const double *__restrict__ psum,
+                                                      uint32_t *__restrict__ kkey, unsigned long long *__restrict__ kmass,
+                                                      uint32_t *__restrict__ nuc_key, double *__restrict__ nuc_S,
+                                                      int32_t *__restrict__ nuc_near, int32_t *__restrict__ done, int vec) {
+  constexpr int FB = 32;
+  const int b = blockIdx.y, tid = threadIdx.x, lane = tid & 63;
+  if ((int)blockIdx.x > off[b + 1] - off[b]) return;
+  const int r = off[b] + b + blockIdx.x;
+  if (!FIRST && done[r]) return;   // settled by the narrower window
+  const float T = temperature[b], tp = top_p ? top_p[b] : 1.f;
+  const int tk = top_k ? top_k[b] : 0;
+  const bool use_k = T > 0.f && tk > 0 && tk < V, use_p = T > 0.f && tp < 1.f;
+  if (MODE == 1) {
+    if (!use_k) {
+      if (tid == 0) { kkey[r] = 0u; done[r] = 1; }
+      return;
+    }
+  } else if (!use_p) {  // no top-p for this row: its final cut is the top-k one, if any
+    if (tid == 0) {
+      const uint32_t kk = use_k ? kkey[r] : 0u;
+      nuc_key[r] = kk;
+      nuc_S[r] = kk ? (double)kmass[r] / kNucScale : -1.0;
+      nuc_near[r] = 0;
+      done[r] = 1;
+    }
+    return;
+  }
+  __shared__ unsigned long long hist[W * FB];
+  __shared__ uint32_t hcnt[(MODE == 1) ? W * FB : 1];
+  __shared__ float s_m;
+  __shared__ double s_total;
+  for (int i = tid; i < W * FB; i += 1024) {
+    hist[i] = 0ull;
+    if (MODE == 1) hcnt[i] = 0u;
+  }
+  if (tid < 64) {   // the row's maximum and normaliser from the per-chunk statistics (chunks in lanes, 64 at a time)
+    float mx = -INFINITY;
+    for (int c = lane; c < nc; c += 64) mx = fmaxf(mx, pmax[(size_t)r * nc + c]);
+#pragma unroll
+    for (int o2 = 32; o2 > 0; o2 >>= 1) mx = fmaxf(mx, __shfl_xor(mx, o2, 64));
+    double term = 0.0;
+    if (MODE == 0 && !use_k) {
+      const double invT = 1.0 / (double)T;
+      for (int c = lane; c < nc; c += 64) {
+        const float pm = pmax[(size_t)r * nc + c];
+        term += psum[(size_t)r * nc + c] * ((pm == mx) ? 1.0 : exp(((double)pm - (double)mx) * invT));
+      }
+#pragma unroll
+      for (int o2 = 32; o2 > 0; o2 >>= 1) term += __shfl_xor(term, o2, 64);
+    }
+    if (lane == 0) {
+      s_m = mx;
+      s_total = (MODE == 0) ? (use_k ? (double)kmass[r] : term * kNucScale) : 0.0;
+    }
+  }
+  __syncthreads();
+  const float m = s_m;
+  const exp_scale k = make_exp_scale(kLog2e / (double)T);
+  const uint32_t d0 = okey(m) >> 21;                              // the row's highest digit
+  const uint32_t lowkey = (MODE == 0 && use_k) ? kkey[r] : 0u;   // top-p works on what the top-k cut kept
+  const uint16_t *row = logits + (size_t)r * V;
+  // the lowest value inside the window (and, after a top-k cut, inside that cut): the value whose key is the window's
+  // lowest key; keys below 2^31 belong to negative values (the key is the complement of their bits)
+  const uint32_t wlow = (d0 >= (uint32_t)(W - 1)) ? ((d0 - (uint32_t)(W - 1)) << 21) : 0u, klow = max(wlow, lowkey);
+  float vlow = __uint_as_float((klow & 0x80000000u) ? (klow & 0x7FFFFFFFu) : ~klow);
+  if (!(vlow == vlow)) vlow = (klow & 0x80000000u) ? INFINITY : -INFINITY;   // (keys of NaN patterns: only when the row holds them)
+  // Eight ids of a thread at a time: a bit per id that falls into the window, then the wave works through the set bits,
+  // every lane on its next one, so that the exponential and the atomics are issued about as often as the busiest lane
+  // has window tokens among its eight, not once per id.
+  auto add8 = [&](int i0, const float (&v)[8], auto in_range) {
+    uint32_t mask = 0u;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      bool ok = v[j] >= vlow;   // the key order is the order of the values: one comparison places a token
+      if (!decltype(in_range)::value) ok = ok && (i0 + j < V);   // ids beyond the vocabulary are not tokens
+      mask |= ok ? (1u << j) : 0u;
+    }
+    while (__any(mask != 0u)) {
+      if (mask) {
+        const int j = __builtin_ctz(mask);
+        mask &= mask - 1u;
+        const float a0 = (j & 1) ? v[1] : v[0], a1 = (j & 1) ? v[3] : v[2], a2 = (j & 1) ? v[5] : v[4], a3 = (j & 1) ? v[7] : v[6];
+        const float b0 = (j & 2) ? a1 : a0, b1 = (j & 2) ? a3 : a2;
+        const float val = (j & 4) ? b1 : b0;
+        const uint32_t key = okey(val);
+        const unsigned long long q = (unsigned long long)((double)exp_scaled(val - m, k) * kNucScale + 0.5);
+        const uint32_t idx = (d0 - (key >> 21)) * FB + ((key >> 16) & (FB - 1));
+        if (q) atomicAdd(&hist[idx], q);
+        if (MODE == 1) atomicAdd(&hcnt[idx], 1u);
+      }
+    }
+  };
+  constexpr int U = 4, STEP = 1024 * 8;
+  int base = tid * 8;
+  if (vec) {
+    for (; base + (U - 1) * STEP + 8 <= V; base += U * STEP) {
+      float v[U][8];
+#pragma unroll
+      for (int u = 0; u < U; ++u) loader<uint16_t>::load8_fast(row, base + u * STEP, v[u]);
+#pragma unroll
+      for (int u = 0; u < U; ++u) add8(base + u * STEP, v[u], std::true_type{});
+    }
+  }
+  for (; base < V; base += STEP) {
+    float v[8];
+    loader<uint16_t>::load8(row, base, V, vec != 0, -INFINITY, v);
+    add8(base, v, std::false_type{});
+  }
+  __syncthreads();
+  if (tid >= 64) return;
+  // lane l < W owns the window's digit d0 - l: the highest keys in lane 0
+  unsigned long long mine = 0ull;
+  uint32_t minec = 0u;
+  if (lane < W) {
+#pragma unroll
+    for (int f = 0; f < FB; ++f) {
+      mine += hist[lane * FB + f];
+      if (MODE == 1) minec += hcnt[lane * FB + f];
+    }
+  }
+  unsigned long long incl = mine;
+  uint32_t inclc = minec;
+#pragma unroll
+  for (int o2 = 1; o2 < W; o2 <<= 1) {
+    const unsigned long long t = __shfl_up(incl, o2, 64);
+    const uint32_t tc = __shfl_up(inclc, o2, 64);
+    if (lane >= o2) { incl += t; inclc += tc; }
+  }
+  const unsigned long long before = incl - mine;   // mass strictly above this lane's digit
+  const uint32_t beforec = inclc - minec;
+  const double total = s_total, target = (double)tp * total;
+  const bool crosses = (MODE == 1) ? (beforec + minec >= (uint32_t)tk) : ((double)(before + mine) >= target);
+  const unsigned long long ballot = __ballot(crosses && lane < W && lane <= (int)d0);   // digits below zero do not exist
+  if (!ballot || (MODE == 0 && !(total > 0.0))) {   // the cut lies below the window: the full passes take the row
+    if (lane == 0) done[r] = 0;
+    return;
+  }
+  if (lane != (int)__builtin_ctzll(ballot)) return;
+  unsigned long long acc = before;
+  uint32_t accc = beforec;
+  int fsel = 0;
+  for (int f = FB - 1; f >= 0; --f) {
+    const unsigned long long hbin = hist[lane * FB + f];
+    const bool hit = (MODE == 1) ? (accc + hcnt[lane * FB + f] >= (uint32_t)tk) : ((double)(acc + hbin) >= target);
+    if (hit || f == 0) { fsel = f; break; }
+    acc += hbin;
+    if (MODE == 1) accc += hcnt[lane * FB + f];
+  }
+  const uint32_t cut = ((d0 - (uint32_t)lane) << 21) | ((uint32_t)fsel << 16);
+  const unsigned long long kept = acc + hist[lane * FB + fsel];
+  if (MODE == 1) {
+    kkey[r] = cut;
+    kmass[r] = kept;
+  } else {
+    nuc_key[r] = cut;
+    nuc_S[r] = (double)kept / kNucScale;
+    const double lo = target - (double)acc, hi = (double)kept - target;
+    nuc_near[r] = (fmin(lo, hi) < 1e-6 * total) ? 1 : 0;
+  }
+  done[r] = 1;
 }
 
 #define FSV_MAX_GAMMA 16
@@ -697,11 +893,24 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
     const int levels = (sizeof(LT) == 2) ? 2 : 3;
     const int passes = (any_k ? levels : 0) + 1 + (any_p ? levels - 1 : 0);
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_NUCLEUS, (double)M * V * sizeof(LT) * passes);
+    // bf16 logits: one windowed pass settles the rows whose cut lies near the top of the row (all of them in practice);
+    // the full passes then find every row done and return at once.  fp32 logits take the full passes.
+    int32_t *done = (sizeof(LT) == 2) ? c->nuc_done : nullptr;
 #define FSV_NUC(LEVEL, LAST, MODE)                                                                                     \
   hipLaunchKernelGGL((k_nucleus<LT, LEVEL, LAST, MODE>), dim3(gmax + 1, B), dim3(1024), 0, s, logits, V, nc,             \
                      b->draft_offsets, b->temperature, b->top_p, b->top_k, c->pmax, c->nuc_prefix, c->nuc_above,          \
-                     c->nuc_cabove, c->nuc_total, c->nuc_kkey, c->nuc_kmass, c->nuc_key, c->nuc_S, c->nuc_near, lvec)
+                     c->nuc_cabove, c->nuc_total, c->nuc_kkey, c->nuc_kmass, c->nuc_key, c->nuc_S, c->nuc_near, done, lvec)
+#define FSV_NUC_TOP1(MODE, WV, FIRSTV)                                                                                 \
+  hipLaunchKernelGGL((k_nucleus_top<MODE, WV, FIRSTV>), dim3(gmax + 1, B), dim3(1024), 0, s, (const uint16_t *)logits,  \
+                     V, nc, b->draft_offsets, b->temperature, b->top_p, b->top_k, c->pmax, c->psum, c->nuc_kkey,        \
+                     c->nuc_kmass, c->nuc_key, c->nuc_S, c->nuc_near, c->nuc_done, lvec)
+#define FSV_NUC_TOP(MODE)                                                                                              \
+  if (sizeof(LT) == 2) {                                                                                               \
+    FSV_NUC_TOP1(MODE, 4, true);                                                                                       \
+    FSV_NUC_TOP1(MODE, 8, false);                                                                                      \
+  }
     if (any_k) {
+      FSV_NUC_TOP(1);
       FSV_NUC(0, false, 1);
       if (sizeof(LT) == 2) {
         FSV_NUC(1, true, 1);
@@ -710,6 +919,7 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
         FSV_NUC(2, true, 1);
       }
     }
+    FSV_NUC_TOP(0);
     FSV_NUC(0, false, 0);   // also settles the rows that take the top-k cut (or none) as their final one
     if (any_p) {
       if (sizeof(LT) == 2) {
@@ -719,6 +929,8 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
         FSV_NUC(2, true, 0);
       }
     }
+#undef FSV_NUC_TOP
+#undef FSV_NUC_TOP1
 #undef FSV_NUC
   }
   {
@@ -802,7 +1014,7 @@ bool carve_static(fsv_ctx &c, unsigned char *base) {
   c.nuc_prefix = (uint32_t *)take(4 * R); c.nuc_key = (uint32_t *)take(4 * R);
   c.nuc_above = (unsigned long long *)take(8 * R); c.nuc_total = (unsigned long long *)take(8 * R);
   c.nuc_S = (double *)take(8 * R); c.nuc_near = (int32_t *)take(4 * R);
-  c.nuc_cabove = (uint32_t *)take(4 * R); c.nuc_kkey = (uint32_t *)take(4 * R);
+  c.nuc_cabove = (uint32_t *)take(4 * R); c.nuc_kkey = (uint32_t *)take(4 * R); c.nuc_done = (int32_t *)take(4 * R);
   c.nuc_kmass = (unsigned long long *)take(8 * R);
   c.sel_ticket = (int32_t *)take(4 * B);   // starts at zero with the array and is left at zero by every call
   return off <= FSV_STATIC_BYTES;

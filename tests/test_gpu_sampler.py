@@ -140,16 +140,20 @@ def test_empty_batch_and_capacity_errors():
     ctx.close()
 
 
-@pytest.mark.parametrize("vocab,batch,gmax,dtype,seed", [
-    (5000, 8, 6, "bf16", 21),        # bf16 logits: many tokens tie at the cut value
-    (5003, 6, 5, "f32", 22),         # odd vocabulary, fp32 keys (three digits)
-    (30000, 6, 8, "f32", 23),
-    (152064, 10, 12, "bf16", 24),    # the full vocabulary of the sampling configuration
+@pytest.mark.parametrize("vocab,batch,gmax,dtype,seed,scale", [
+    (5000, 8, 6, "bf16", 21, 1.0),        # bf16 logits: many tokens tie at the cut value
+    (5003, 6, 5, "f32", 22, 1.0),         # odd vocabulary, fp32 keys (three digits)
+    (30000, 6, 8, "f32", 23, 1.0),
+    (152064, 10, 12, "bf16", 24, 1.0),    # the full vocabulary of the sampling configuration
+    (5000, 9, 6, "bf16", 25, 0.02),       # nearly flat laws: the cut lies among the negative logits, far below the
+    (40000, 6, 8, "bf16", 26, 0.05),      # window of the one-pass kernel, so these rows take the full passes
 ])
-def test_nucleus_cut_matches_oracle(vocab, batch, gmax, dtype, seed):
+def test_nucleus_cut_matches_oracle(vocab, batch, gmax, dtype, seed, scale):
     """top-p per request (Regime B samples with top-p): 1.0 (off), 0.9 and a tight 0.5 mixed in one batch."""
     fv, ctx = _ctx(vocab, batch, 16)
     case = synth.make_sampler_case(batch, 1, gmax, vocab, 0.5, 0.7, seed, logits_dtype=dtype)
+    if scale != 1.0:
+        case.logits = (case.logits.float() * scale).to(case.logits.dtype)
     top_p = np.array([(1.0, 0.9, 0.5)[b % 3] for b in range(batch)], np.float32)
     B = batch
     t = lambda a: torch.as_tensor(np.ascontiguousarray(a), device="cuda")
@@ -255,13 +259,16 @@ def test_many_small_seeded_cases_against_oracle():
     (5000, 9, 6, "bf16", 41),        # bf16 logits: the k-th value is usually shared by several tokens (ties kept)
     (5003, 8, 5, "f32", 42),         # odd vocabulary, fp32 keys (three digits)
     (152064, 12, 12, "bf16", 43),    # the full vocabulary of the sampling configuration
+    (5000, 16, 6, "bf16", 44),       # more requests: every entry of the list below occurs, the deep cuts twice
 ])
 def test_top_k_cut_matches_oracle(vocab, batch, gmax, dtype, seed):
-    """top-k per request, alone and followed by top-p, mixed with uncut and greedy requests in one batch."""
+    """top-k per request, alone and followed by top-p, mixed with uncut and greedy requests in one batch.  The k-th
+    token of the large k lies among the negative logits: below the window of the one-pass kernel for bf16 logits, so
+    those rows take the full passes."""
     fv, ctx = _ctx(vocab, batch, 16)
     case = synth.make_sampler_case(batch, 1, gmax, vocab, 0.5, 0.7, seed, logits_dtype=dtype)
-    top_k = np.array([(0, 50, 5, 1, 2000, vocab + 7)[b % 6] for b in range(batch)], np.int32)
-    top_p = np.array([(1.0, 1.0, 0.8, 1.0, 0.9, 0.9)[b % 6] for b in range(batch)], np.float32)
+    top_k = np.array([(0, 50, 5, 1, 2000, vocab + 7, (vocab * 4) // 5, (vocab * 9) // 10)[b % 8] for b in range(batch)], np.int32)
+    top_p = np.array([(1.0, 1.0, 0.8, 1.0, 0.9, 0.9, 1.0, 0.999)[b % 8] for b in range(batch)], np.float32)
     temp = case.temperature.copy()
     if batch > 7:
         temp[7] = 0.0                 # a greedy request ignores both cuts
