@@ -224,6 +224,21 @@ int fsv_draft_probs(fsv_ctx *ctx, const fsv_batch *batch, int32_t rows_mode, flo
 int fsv_verify(fsv_ctx *ctx, const fsv_batch *batch, const fsv_result *result, void *stream);
 
 /*
+ * The target forward alone: extend KV sessions by rows that need no accept / reject decision -- restoring a user's
+ * context from tokens instead of from a saved cache (Alg. 2 "restore KV cache"; Sec. IV-C: the cloud computes the KV
+ * pairs of the tokens it receives), e.g. a prompt taken in chunks.  Request b contributes the rows last_token[b],
+ * draft_tokens[draft_offsets[b] ..) at positions seq_lens[b] ... exactly as in fsv_verify, their K / V rows are
+ * appended, and the call stops after the LM head.  A chunk longer than max_gamma + 1 rows is passed as several
+ * requests that share ONE page-table row content and continue each other (seq_lens of the next = seq_lens + rows of
+ * the one before): within a layer all rows are appended before any row attends, so a later piece sees the earlier
+ * pieces' keys.  Uses from batch: batch, seq_lens(+_host), last_token, draft_offsets(+_host), draft_tokens,
+ * page_table, k_pool, v_pool, num_pages (and adapter).  logits_out: DEVICE [M][vocab] fp32, row order as in
+ * fsv_verify, or NULL when only the cache is wanted (the logits then stay in the context's own buffer).
+ * Nothing is rolled back: the caller's new length of request b is seq_lens[b] + its rows.
+ */
+int fsv_prefill(fsv_ctx *ctx, const fsv_batch *batch, float *logits_out, void *stream);
+
+/*
  * The accept / resample step alone -- the acceptance loop of Alg. 2 step 2 and its "sample correction token" line, with
  * the speculative-sampling rule of fsv_verify for T_b > 0 -- on caller-provided target logits (DEVICE [M][vocab], row
  * draft_offsets[b] + b + i scores the token after input row i of request b; dtype FSV_BF16 or

@@ -191,6 +191,22 @@ int fsv_verify(fsv_ctx *c, const fsv_batch *b, const fsv_result *r, void *stream
   return fsv_launch_sampler(c, logits, FSV_F32, b, r, M, true, s);
 }
 
+int fsv_prefill(fsv_ctx *c, const fsv_batch *b, float *logits_out, void *stream) {
+  if (!c) return FSV_E_INVALID_ARG;
+  if (c->d.n_layers == 0) FSV_FAIL(c, FSV_E_NO_MODEL, "fsv_prefill on a sampler-only context");
+  const int M = fsv_check_batch(c, b, true, false);
+  if (M <= 0) return M;
+  if (!b->last_token) FSV_FAIL(c, FSV_E_INVALID_ARG, "last_token required");
+  if (b->draft_offsets_host[b->batch] > 0 && !b->draft_tokens) FSV_FAIL(c, FSV_E_INVALID_ARG, "draft_tokens required");
+  hipStream_t s = (hipStream_t)stream;
+  float *logits = logits_out ? logits_out : c->logits;
+  fsv_attn_plan pl;
+  int rc = (c->d.dtype == FSV_F32) ? fsv_f32_check(c, b) : fsv_bf16_attn_plan_host(c, b, &pl);
+  if (rc) return rc;
+  if ((rc = fsv_launch_build_rows(c, b, M, s))) return rc;
+  return (c->d.dtype == FSV_F32) ? fsv_f32_forward(c, b, M, logits, s) : fsv_bf16_forward(c, b, &pl, M, logits, 0, s);
+}
+
 int fsv_sample(fsv_ctx *c, const void *logits, int32_t logits_dtype, const fsv_batch *b, const fsv_result *r,
                void *stream) {
   if (!c) return FSV_E_INVALID_ARG;

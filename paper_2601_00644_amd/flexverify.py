@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, os.environ.get("FSV_LIB_NAME", "libflexverify.so"
 F32, BF16 = 0, 1
 W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
-EXPORTS = ["fsv_create", "fsv_destroy", "fsv_lora_load", "fsv_draft_attach", "fsv_draft_probs", "fsv_draft_kv_import", "fsv_draft_kv_export", "fsv_verify", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
+EXPORTS = ["fsv_create", "fsv_destroy", "fsv_lora_load", "fsv_draft_attach", "fsv_draft_probs", "fsv_draft_kv_import", "fsv_draft_kv_export", "fsv_verify", "fsv_prefill", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
            "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
            "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_policy_step_time", "fsv_pager_create",
            "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
@@ -294,6 +294,18 @@ class Context:
         b, r = batch.struct(), result.struct()
         self._check(lib().fsv_verify(self._h, C.byref(b), C.byref(r), _stream()), "fsv_verify")
 
+    def prefill(self, batch: DeviceBatch, want_logits: bool = False):
+        """The forward alone (fsv_prefill): appends the K / V rows of the batch's rows; returns the [M][vocab] fp32
+        logits when asked for."""
+        b = batch.struct()
+        lg = None
+        if want_logits:
+            rows = batch.rows
+            lg = torch.empty((rows, self.cfg.vocab), dtype=torch.float32, device="cuda")
+        self._check(lib().fsv_prefill(self._h, C.byref(b), C.c_void_p(lg.data_ptr()) if want_logits else None, _stream()),
+                    "fsv_prefill")
+        return lg
+
     def sample(self, logits: torch.Tensor, batch: DeviceBatch, result: DeviceResult):
         dt = BF16 if logits.dtype == torch.bfloat16 else F32
         assert logits.dtype in (torch.bfloat16, torch.float32) and logits.is_contiguous()
@@ -449,6 +461,26 @@ def alloc_pools(cfg, num_pages: int, device="cuda"):
     tdt = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
     return (torch.zeros(pool_shape(cfg, num_pages), dtype=tdt, device=device),
             torch.zeros(pool_shape(cfg, num_pages), dtype=tdt, device=device))
+
+
+def prefill_pieces(chunks, page_rows, k_pool, v_pool, num_pages: int, rows_per_piece: int, device="cuda") -> DeviceBatch:
+    """A DeviceBatch for fsv_prefill from token chunks: chunks = [(session index into page_rows, L0, tokens)], every chunk
+    cut into pieces of at most rows_per_piece rows; the pieces of one chunk are requests that share the session's
+    page-table row and continue each other.  page_rows: host int32 [sessions][max_pages_per_req]."""
+    L, last, off, toks, rows = [], [], [0], [], []
+    for sess, L0, tokens in chunks:
+        tokens = np.asarray(tokens, np.int32)
+        for p0 in range(0, len(tokens), rows_per_piece):
+            piece = tokens[p0:p0 + rows_per_piece]
+            L.append(int(L0) + p0)
+            last.append(int(piece[0]))
+            toks.extend(int(x) for x in piece[1:])
+            off.append(off[-1] + len(piece) - 1)
+            rows.append(np.asarray(page_rows[sess], np.int32))
+    t = lambda a, dt: torch.as_tensor(np.ascontiguousarray(np.asarray(a, dt)), device=device)
+    Lh, offh = np.asarray(L, np.int32), np.asarray(off, np.int32)
+    return DeviceBatch(t(Lh, np.int32), t(last, np.int32), t(offh, np.int32), t(toks if toks else [0], np.int32), None, None,
+                       None, None, t(np.stack(rows), np.int32), k_pool, v_pool, num_pages, Lh, offh)
 
 
 def device_batch(req, draft_tokens=None, draft_probs=None, k_pool=None, v_pool=None, device="cuda") -> DeviceBatch:
