@@ -319,6 +319,9 @@ typedef struct {
   double bytes;         /* algorithmic bytes of those launches as the host computed them at launch  */
 } fsv_kernel_time;
 int fsv_profile_enable(fsv_ctx *ctx, uint32_t class_mask);
+/* Record only every every_n-th launch of each enabled class (1 = all, the default): the event pairs cost a few
+ * microseconds of host and dispatch time each, which a timed region with hundreds of launches need not pay in full. */
+int fsv_profile_sample(fsv_ctx *ctx, int32_t every_n);
 int fsv_profile_read(fsv_ctx *ctx, fsv_kernel_time *out, int32_t cap);
 const char *fsv_kernel_class_name(int32_t kernel_class);
 

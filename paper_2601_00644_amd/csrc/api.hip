@@ -97,6 +97,7 @@ const char *fsv_kernel_class_name(int32_t k) { return (k >= 0 && k < FSV_K_COUNT
 void fsv_destroy(fsv_ctx *c) {
   if (!c) return;
   for (auto &r : c->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+  for (hipEvent_t e : c->prof_pool) (void)hipEventDestroy(e);
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->acc_scratch, c->sel_ticket, c->nuc_prefix,
                   c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_done, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
@@ -342,6 +343,13 @@ int fsv_attention(fsv_ctx *c, int32_t layer, const void *q, const fsv_batch *b, 
 int fsv_profile_enable(fsv_ctx *c, uint32_t class_mask) {
   if (!c) return FSV_E_INVALID_ARG;
   c->prof_mask = class_mask;
+  for (int &n : c->prof_seen) n = 0;
+  return FSV_OK;
+}
+
+int fsv_profile_sample(fsv_ctx *c, int32_t every_n) {
+  if (!c || every_n < 1) return FSV_E_INVALID_ARG;
+  c->prof_every = every_n;
   return FSV_OK;
 }
 
@@ -356,8 +364,8 @@ int fsv_profile_read(fsv_ctx *c, fsv_kernel_time *out, int32_t cap) {
       acc[r.cls].total_ms += ms;
       acc[r.cls].bytes += r.bytes;
     }
-    (void)hipEventDestroy(r.e0);
-    (void)hipEventDestroy(r.e1);
+    c->prof_pool.push_back(r.e0);   // kept for the records to come
+    c->prof_pool.push_back(r.e1);
   }
   c->prof.clear();
   int n = 0;

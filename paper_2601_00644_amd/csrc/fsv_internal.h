@@ -94,7 +94,10 @@ struct fsv_ctx {
 
   // profiling
   uint32_t prof_mask = 0;
+  int prof_every = 1;                     // record every n-th launch of an enabled class (fsv_profile_sample)
+  int prof_seen[16] = {0};                // launches of each class seen since profiling was enabled
   std::vector<fsv_prof_rec> prof;
+  std::vector<hipEvent_t> prof_pool;      // events of records already read, reused by later records
 };
 
 #define FSV_FAIL(ctx, code, ...)                                   \
@@ -122,10 +125,16 @@ struct fsv_prof_scope {
   fsv_prof_scope(fsv_ctx *ctx, hipStream_t st, int cls, double bytes, bool ext_mode = false)
       : c(ctx), s(st), on(ctx && ((ctx->prof_mask >> cls) & 1u)), external(ext_mode) {
     if (!on) return;
+    if (c->prof_every > 1 && (c->prof_seen[cls]++ % c->prof_every) != 0) { on = false; return; }
     if (c->prof.size() >= 8192) { on = false; return; }
     r.cls = cls;
     r.bytes = bytes;
-    if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess) { on = false; return; }
+    auto get = [&](hipEvent_t *e) {
+      if (!c->prof_pool.empty()) { *e = c->prof_pool.back(); c->prof_pool.pop_back(); return true; }
+      return hipEventCreate(e) == hipSuccess;
+    };
+    if (!get(&r.e0)) { on = false; return; }
+    if (!get(&r.e1)) { c->prof_pool.push_back(r.e0); on = false; return; }
     if (!external) (void)hipEventRecord(r.e0, s);
   }
   hipEvent_t start() const { return (on && external) ? r.e0 : nullptr; }

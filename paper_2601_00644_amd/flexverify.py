@@ -20,7 +20,7 @@ F32, BF16 = 0, 1
 W_QKV, W_O, W_GATE_UP, W_DOWN, W_LM_HEAD = range(5)
 
 EXPORTS = ["fsv_create", "fsv_destroy", "fsv_lora_load", "fsv_draft_attach", "fsv_draft_probs", "fsv_draft_kv_import", "fsv_draft_kv_export", "fsv_verify", "fsv_prefill", "fsv_sample", "fsv_sample_static", "fsv_rollback", "fsv_kv_import", "fsv_kv_export",
-           "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_read", "fsv_kernel_class_name",
+           "fsv_linear", "fsv_attention", "fsv_profile_enable", "fsv_profile_sample", "fsv_profile_read", "fsv_kernel_class_name",
            "fsv_strerror", "fsv_last_error", "fsv_policy_stride", "fsv_policy_ema", "fsv_policy_step_time", "fsv_pager_create",
            "fsv_pager_destroy", "fsv_pager_reserve", "fsv_pager_trim", "fsv_pager_free_pages", "fsv_pager_session_pages"]
 
@@ -353,8 +353,10 @@ class Context:
                                         C.c_void_p(out.data_ptr()), _stream()), "fsv_attention")
         return out
 
-    def profile_enable(self, classes=True):
-        """classes: True = all kernel classes, False = off, or an iterable of class names."""
+    def profile_enable(self, classes=True, every: int = 1):
+        """classes: True = all kernel classes, False = off, or an iterable of class names; every: record only every
+        n-th launch of each enabled class."""
+        self._check(lib().fsv_profile_sample(self._h, C.c_int32(max(1, int(every)))), "fsv_profile_sample")
         if classes is True:
             mask = 0xFFFFFFFF
         elif not classes:
