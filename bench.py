@@ -298,9 +298,10 @@ def main():
         step()
     torch.cuda.synchronize()
     ctx.profile_read()
-    # event pairs around the dominant kernel only, every fourth of its 32 launches a step: an event-carrying dispatch
-    # costs a few microseconds, and the step is what is being timed
-    ctx.profile_enable(["gemm_gate_up"], every=4)
+    # event pairs around the dominant kernel only, every eighth of its 32 launches a step: an event-carrying dispatch
+    # leaves the GPU idle for about ten microseconds around it (kernel trace: no gap between the other launches), and
+    # the step is what is being timed
+    ctx.profile_enable(["gemm_gate_up"], every=8)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]   # per-step spread (one event a step)
     torch.cuda.synchronize()
