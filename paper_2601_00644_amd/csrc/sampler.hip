@@ -20,6 +20,7 @@
 // other atomics are integer adds into the nucleus histograms, whose result does not depend on their order.
 #include <limits.h>
 #include <math.h>
+#include <stdlib.h>
 #include <type_traits>
 #include <mutex>
 
@@ -895,7 +896,10 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
     fsv_prof_scope ps(c, s, FSV_K_SAMPLE_NUCLEUS, (double)M * V * sizeof(LT) * passes);
     // bf16 logits: one windowed pass settles the rows whose cut lies near the top of the row (all of them in practice);
     // the full passes then find every row done and return at once.  fp32 logits take the full passes.
-    int32_t *done = (sizeof(LT) == 2) ? c->nuc_done : nullptr;
+    // (FSV_NUCLEUS_FULL=1 in the environment sends every row through the digit-by-digit passes: a test compares the two)
+    const char *full_env = getenv("FSV_NUCLEUS_FULL");
+    const bool windowed = sizeof(LT) == 2 && !(full_env && full_env[0] == '1');
+    int32_t *done = windowed ? c->nuc_done : nullptr;
 #define FSV_NUC(LEVEL, LAST, MODE)                                                                                     \
   hipLaunchKernelGGL((k_nucleus<LT, LEVEL, LAST, MODE>), dim3(gmax + 1, B), dim3(1024), 0, s, logits, V, nc,             \
                      b->draft_offsets, b->temperature, b->top_p, b->top_k, c->pmax, c->nuc_prefix, c->nuc_above,          \
@@ -905,7 +909,7 @@ int launch_sampler_t(fsv_ctx *c, const LT *logits, const fsv_batch *b, const fsv
                      V, nc, b->draft_offsets, b->temperature, b->top_p, b->top_k, c->pmax, c->psum, c->nuc_kkey,        \
                      c->nuc_kmass, c->nuc_key, c->nuc_S, c->nuc_near, c->nuc_done, lvec)
 #define FSV_NUC_TOP(MODE)                                                                                              \
-  if (sizeof(LT) == 2) {                                                                                               \
+  if (windowed) {                                                                                               \
     FSV_NUC_TOP1(MODE, 4, true);                                                                                       \
     FSV_NUC_TOP1(MODE, 8, false);                                                                                      \
   }
