@@ -573,6 +573,12 @@ int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
   int sp = c->n_cus / base;
   sp = max(1, min(sp, nchunks));
   if (sp >= 8) sp &= ~7;  // a multiple of eight keeps each split on one XCD (see k_gemm); the K cut is balanced, not equal
+  else {
+    // the longest block sets the time: the fewest splits whose longest block is no longer than with sp (five splits of
+    // sixteen granules give blocks of 3 and 4, four give blocks of 4: same time, a fifth fewer partial sums)
+    const int longest = fsv_ceil_div(nchunks, sp);
+    while (sp > 1 && fsv_ceil_div(nchunks, sp - 1) == longest) --sp;
+  }
   return sp;
 }
 
