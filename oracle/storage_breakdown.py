@@ -2,7 +2,8 @@
 
 TEST INFRASTRUCTURE (part of the oracle).  Runs the oracle's forward (Alg. 2 step 2) on one synthetic request of a
 named model shape with no rounding, with every storage point rounded, with the set a deployment needs, and with each
-point alone, and prints the worst-row differences of the logits.  The table in the design doc comes from
+point alone, and prints the worst-row differences of the logits.  The per-point figures quoted for the 1B and 8B
+shapes come from
 
     python -m oracle.storage_breakdown llama1b 2048 9
     python -m oracle.storage_breakdown llama8b 1024 9      (needs ~40 GB of host memory and a few minutes)
