@@ -79,14 +79,19 @@ static inline double widen(const void *w, int bf16, size_t idx) {
   return (double)((const float *)w)[idx];
 }
 
-/* Storage points of a bf16 deployment (orc_forward_stored): which tensors are rounded to bf16. */
+/* Storage points of a bf16 deployment (orc_forward_stored): which tensors are rounded to bf16.  The two tensors that
+ * are bounded whatever the model (a normalised activation is at most sqrt(d_model) times its gain, an attention output is a
+ * convex combination of cached values) may instead be kept in fp16, which has the same 16 bits but 11 significant ones:
+ * ORC_ST_A16 / ORC_ST_O16 round them to fp16; where both the bf16 and the fp16 bit of a tensor are set, bf16 wins. */
 enum {
   ORC_ST_A = 1,    /* normalised activations entering the QKV, gate|up and LM-head projections */
   ORC_ST_Q = 2,    /* rotated queries                                                          */
   ORC_ST_KV = 4,   /* rotated keys and values of the new rows, as written to the KV cache       */
   ORC_ST_P = 8,    /* attention probabilities relative to the row maximum, exp(s - max)         */
   ORC_ST_O = 16,   /* attention output entering the O projection                                */
-  ORC_ST_ACT = 32  /* SwiGLU output entering the down projection                                */
+  ORC_ST_ACT = 32, /* SwiGLU output entering the down projection                                */
+  ORC_ST_A16 = 64, /* the tensor of ORC_ST_A, rounded to fp16                                  */
+  ORC_ST_O16 = 128 /* the tensor of ORC_ST_O, rounded to fp16                                  */
 };
 
 /* Nearest bf16 (8 significant bits, fp32 exponent range), ties to even, of a double; returned as a double. */
@@ -102,6 +107,29 @@ double orc_round_bf16(double x) {
 }
 static void round_rows(double *v, size_t n) {
   for (size_t i = 0; i < n; ++i) v[i] = orc_round_bf16(v[i]);
+}
+
+/* Nearest fp16 (11 significant bits, normal range from 2^-14, subnormal quantum 2^-24), ties to even, of a double;
+ * a value that would round beyond the largest finite fp16 number is held at +-65504 (a saturating conversion). */
+double orc_round_f16(double x) {
+  if (x == 0.0 || x != x) return x;
+  if (isinf(x)) return x > 0 ? 65504.0 : -65504.0;
+  int e;
+  (void)frexp(x, &e);                    /* x = m 2^e, 0.5 <= |m| < 1 */
+  int qe = e - 11;                       /* quantum 2^(e-11): 11 significant bits */
+  if (qe < -24) qe = -24;
+  double r = ldexp(nearbyint(ldexp(x, -qe)), qe);
+  if (r > 65504.0) r = 65504.0;
+  if (r < -65504.0) r = -65504.0;
+  return r;
+}
+static void round_rows_f16(double *v, size_t n) {
+  for (size_t i = 0; i < n; ++i) v[i] = orc_round_f16(v[i]);
+}
+/* one storage point: its bf16 bit, else its fp16 bit, else left alone */
+static void store_point(double *v, size_t n, int stored, int bit_bf16, int bit_f16) {
+  if (stored & bit_bf16) round_rows(v, n);
+  else if (stored & bit_f16) round_rows_f16(v, n);
 }
 
 /* Dense projection, the definition: y[m][o] = sum_k x[m][k] * W[o][k]   (x: [n][in], y: [n][out]) */
@@ -237,7 +265,7 @@ int orc_forward_lora(const orc_model *mo, const orc_weights *w, const orc_lora *
   for (int l = 0; l < mo->n_layers; ++l) {
     double *kl = kc + (size_t)l * cap * kvdim, *vl = vc + (size_t)l * cap * kvdim;
     rmsnorm(h, w->attn_norm[l], bf, d, mo->rms_eps, n, a);
-    if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
+    store_point(a, (size_t)n * d, stored, ORC_ST_A, ORC_ST_A16);
     orc_linear(w->w_qkv[l], bf, qkvdim, d, a, n, qkv);
     const int adapted = lora && lora->rank > 0 && l < mo->n_layers - 1;   /* the last block is part of the invariant head */
     if (adapted) lora_add(lora->a_qkv[l], lora->b_qkv[l], bf, qkvdim, d, lora->rank, lora->scale, a, n, qkv);
@@ -252,12 +280,12 @@ int orc_forward_lora(const orc_model *mo, const orc_weights *w, const orc_lora *
       memcpy(vl + (size_t)pos * kvdim, row + qdim + kvdim, sizeof(double) * kvdim);
     }
     attention_impl(qkv, qkvdim, kl, vl, L, n, H, Hkv, hd, att, stored & ORC_ST_P);
-    if (stored & ORC_ST_O) round_rows(att, (size_t)n * qdim);
+    store_point(att, (size_t)n * qdim, stored, ORC_ST_O, ORC_ST_O16);
     orc_linear(w->w_o[l], bf, d, qdim, att, n, upd);
     if (adapted) lora_add(lora->a_o[l], lora->b_o[l], bf, d, qdim, lora->rank, lora->scale, att, n, upd);
     for (size_t t = 0; t < (size_t)n * d; ++t) h[t] += upd[t];
     rmsnorm(h, w->mlp_norm[l], bf, d, mo->rms_eps, n, a);
-    if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
+    store_point(a, (size_t)n * d, stored, ORC_ST_A, ORC_ST_A16);
     orc_linear(w->w_gate_up[l], bf, 2 * F, d, a, n, gu);
     for (int i = 0; i < n; ++i)
       for (int f = 0; f < F; ++f) {
@@ -271,7 +299,7 @@ int orc_forward_lora(const orc_model *mo, const orc_weights *w, const orc_lora *
   if (hidden) memcpy(hidden, h, sizeof(double) * n * d);
   if (logits) {
     rmsnorm(h, w->final_norm, bf, d, mo->rms_eps, n, a);
-    if (stored & ORC_ST_A) round_rows(a, (size_t)n * d);
+    store_point(a, (size_t)n * d, stored, ORC_ST_A, ORC_ST_A16);
     orc_linear(w->lm_head, bf, V, d, a, n, logits);
   }
   free(h); free(a); free(qkv); free(att); free(gu); free(act); free(upd);

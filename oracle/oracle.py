@@ -65,6 +65,8 @@ def lib():
         _lib.orc_draft_forward.restype = C.c_int
         _lib.orc_round_bf16.restype = C.c_double
         _lib.orc_round_bf16.argtypes = [C.c_double]
+        _lib.orc_round_f16.restype = C.c_double
+        _lib.orc_round_f16.argtypes = [C.c_double]
         _lib.orc_sample.restype = C.c_int
         _lib.orc_sample_warp.restype = C.c_int
         _lib.orc_sample_cut.restype = C.c_int
@@ -125,11 +127,19 @@ def new_cache(cfg, cap: int):
 ST_A, ST_Q, ST_KV, ST_P, ST_O, ST_ACT = 1, 2, 4, 8, 16, 32
 ST_BF16 = ST_A | ST_Q | ST_KV | ST_O | ST_ACT
 ST_NAMES = {"a": ST_A, "q": ST_Q, "kv": ST_KV, "p": ST_P, "o": ST_O, "act": ST_ACT}
+# The two tensors that are bounded whatever the model (normalised activations, attention outputs) kept in fp16 instead:
+# the same 16 bits with 11 significant ones.  The bf16 bit of a tensor wins over its fp16 bit.
+ST_A16, ST_O16 = 64, 128
 
 
 def round_bf16(x: float) -> float:
     """Nearest bf16 value (ties to even) of a double."""
     return float(lib().orc_round_bf16(float(x)))
+
+
+def round_f16(x: float) -> float:
+    """Nearest fp16 value (ties to even, held at +-65504 beyond the range) of a double."""
+    return float(lib().orc_round_f16(float(x)))
 
 
 def _lora_struct(cfg, lora):
@@ -155,7 +165,8 @@ def forward(cfg, w, kc, vc, L: int, tokens, want_hidden: bool = False, stored: i
     """Target forward over tokens placed at positions L.. on top of cache (kc, vc); appends their KV.
 
     Returns logits [n][vocab] fp64 (and the pre-norm hidden state if asked).  Alg. 2 step 2.
-    stored: mask of ST_* tensors rounded to bf16 (fp64 arithmetic otherwise); 0 = the plain fp64 definition.
+    stored: mask of ST_* tensors rounded to bf16 (ST_A16 / ST_O16: to fp16), fp64 arithmetic otherwise; 0 = the plain fp64
+    definition.
     lora: this request's adapter of the evolved target (Sec. IV-A), see _lora_struct; None = the base target.
     """
     tokens = np.ascontiguousarray(tokens, np.int32)

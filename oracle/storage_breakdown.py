@@ -38,7 +38,9 @@ def main(name: str, L: int, n: int, seed: int = 1):
 
     ref = run(0)
     rows = [("all six points", 63), ("a + kv + o + act", oracle.ST_A | oracle.ST_KV | oracle.ST_O | oracle.ST_ACT)]
-    rows += [("kv + o + act", oracle.ST_KV | oracle.ST_O | oracle.ST_ACT), ("kv only", oracle.ST_KV)]
+    rows += [("kv + o + act", oracle.ST_KV | oracle.ST_O | oracle.ST_ACT),
+             ("a, o in fp16 + kv + act", oracle.ST_A16 | oracle.ST_O16 | oracle.ST_KV | oracle.ST_ACT),
+             ("a, o in fp16 only", oracle.ST_A16 | oracle.ST_O16), ("kv only", oracle.ST_KV)]
     rows += [(f"only {nm}", bit) for nm, bit in oracle.ST_NAMES.items() if bit != oracle.ST_KV]
     print(f"{name}: context {L}, {n} rows, {cfg.n_layers} layers; difference of the logits from the fp64 forward")
     print(f"{'rounded to bf16':18s} {'worst row L2':>12s} {'elem / row max':>14s} {'elem / max(|ref|, rms)':>22s}")

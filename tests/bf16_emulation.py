@@ -7,23 +7,30 @@ library.
 """
 from __future__ import annotations
 
+import numpy as np
 import torch
 import torch.nn.functional as F
 
 POINTS = ("a", "q", "kv", "p", "o", "act")
+POINTS_F16 = ("a16", "o16")     # the tensors of "a" and "o" rounded to fp16 instead (numpy's conversion: it rounds a
+                                # double once, where torch's goes through fp32 and can round twice)
 
 
-def _rb(t: torch.Tensor, on: bool) -> torch.Tensor:
-    return t.to(torch.bfloat16).double() if on else t
+def _rb(t: torch.Tensor, on: bool, f16: bool = False) -> torch.Tensor:
+    if on:
+        return t.to(torch.bfloat16).double()
+    if f16:
+        return torch.from_numpy(t.clamp(-65504.0, 65504.0).numpy().astype(np.float16).astype(np.float64))
+    return t
 
 
 def forward_stored(cfg, w: dict, k_ctx: torch.Tensor, v_ctx: torch.Tensor, toks: torch.Tensor, points=()):
     """Logits [n][vocab] (fp64) of tokens `toks` placed after a context of L positions.
 
     w: torch tensors as synth.make_weights returns them; k_ctx / v_ctx: [layers][L][Hkv][hd]; points: which of POINTS
-    are rounded to bf16."""
+    are rounded to bf16, which of POINTS_F16 to fp16 (bf16 wins where both are named)."""
     pts = set(points)
-    assert pts <= set(POINTS)
+    assert pts <= set(POINTS) | set(POINTS_F16)
     H, Hkv, hd, n, L = cfg.n_heads, cfg.n_kv_heads, cfg.head_dim, int(toks.shape[0]), int(k_ctx.shape[1])
     x = w["embed"][toks.long()].double()
     pos = torch.arange(L, L + n, dtype=torch.float64)
@@ -39,7 +46,7 @@ def forward_stored(cfg, w: dict, k_ctx: torch.Tensor, v_ctx: torch.Tensor, toks:
 
     mask = torch.arange(L + n)[None, :] <= (L + torch.arange(n))[:, None]
     for l in range(cfg.n_layers):
-        a = _rb(norm(x, w[f"attn_norm.{l}"]), "a" in pts)
+        a = _rb(norm(x, w[f"attn_norm.{l}"]), "a" in pts, "a16" in pts)
         q, k, v = (a @ w[f"w_qkv.{l}"].double().T).split([H * hd, Hkv * hd, Hkv * hd], -1)
         q = _rb(rope(q.reshape(n, H, hd)), "q" in pts)
         k = _rb(rope(k.reshape(n, Hkv, hd)), "kv" in pts)
@@ -51,10 +58,10 @@ def forward_stored(cfg, w: dict, k_ctx: torch.Tensor, v_ctx: torch.Tensor, toks:
         p = torch.exp(s - s.max(-1, keepdim=True).values)
         den = p.sum(-1, keepdim=True)
         o = torch.einsum("hnm,mhd->nhd", _rb(p, "p" in pts) / den, V)
-        o = _rb(o.reshape(n, H * hd), "o" in pts)
+        o = _rb(o.reshape(n, H * hd), "o" in pts, "o16" in pts)
         x = x + o @ w[f"w_o.{l}"].double().T
-        m = _rb(norm(x, w[f"mlp_norm.{l}"]), "a" in pts)
+        m = _rb(norm(x, w[f"mlp_norm.{l}"]), "a" in pts, "a16" in pts)
         g, u = (m @ w[f"w_gate_up.{l}"].double().T).split([cfg.d_ffn, cfg.d_ffn], -1)
         act = _rb(F.silu(g) * u, "act" in pts)
         x = x + act @ w[f"w_down.{l}"].double().T
-    return _rb(norm(x, w["final_norm"]), "a" in pts) @ w["lm_head"].double().T
+    return _rb(norm(x, w["final_norm"]), "a" in pts, "a16" in pts) @ w["lm_head"].double().T

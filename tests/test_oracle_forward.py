@@ -237,6 +237,27 @@ def test_round_bf16_hand_cases_and_library_conversion():
     assert np.array_equal(got, t.to(torch.bfloat16).double().numpy())
 
 
+def test_round_f16_hand_cases_and_library_conversion():
+    # hand-worked: 11 significant bits, ties to even, normal range from 2^-14, subnormal grid 2^-24, held at +-65504
+    cases = [(1.0, 1.0), (1.0 + 2.0 ** -11, 1.0),                    # tie, mantissa even -> down
+             (1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -9),                # tie, mantissa odd -> up
+             (1.0 + 2.0 ** -11 + 2.0 ** -40, 1.0 + 2.0 ** -10),      # just above a tie -> up
+             (-(2.0 + 2.0 ** -9), -2.0 - 2.0 ** -9),                 # representable as is
+             (2049.0, 2048.0), (2051.0, 2052.0),                      # steps of 2 above 2048, ties to even
+             (2.0 ** -24, 2.0 ** -24), (2.0 ** -25, 0.0), (3 * 2.0 ** -25, 2.0 ** -23),   # subnormal grid, ties to even
+             (2.0 ** -14 + 2.0 ** -25, 2.0 ** -14),                   # smallest normal: quantum 2^-24, tie to even
+             (65504.0, 65504.0), (65519.0, 65504.0), (65520.0, 65504.0), (1e9, 65504.0), (-1e9, -65504.0),
+             (float("inf"), 65504.0), (0.0, 0.0)]
+    for x, want in cases:
+        assert oracle.round_f16(x) == want, (x, oracle.round_f16(x), want)
+    # a library routine: numpy's own double -> float16 conversion, on values spread over the binades fp16 covers
+    rng = np.random.default_rng(4)
+    t = rng.standard_normal(20000) * np.exp(4 * rng.standard_normal(20000))
+    t = t[np.abs(t) < 65000.0]
+    got = np.array([oracle.round_f16(float(v)) for v in t])
+    assert np.array_equal(got, t.astype(np.float16).astype(np.float64))
+
+
 def _stored_case(name, seed, L, n, std=0.08):
     cfg = synth.MODELS[name]
     w = synth.make_weights(cfg, seed, std=std)
@@ -269,23 +290,25 @@ def test_stored_mode_matches_an_independent_torch_statement(name):
     cfg, w, k, v, toks, run = _stored_case(name, 5, 50, 6)
     tt = torch.as_tensor(toks)
     ref, _ = run(0)
-    sets = [(p,) for p in POINTS] + [("a", "kv", "o", "act"), POINTS]
+    names = dict(oracle.ST_NAMES, a16=oracle.ST_A16, o16=oracle.ST_O16)
+    sets = [(p,) for p in POINTS] + [("a16",), ("o16",), ("a", "kv", "o", "act"), ("a16", "kv", "o16", "act"),
+                                     ("a", "a16", "o", "o16"), POINTS]       # bf16 wins where both are named
     for pts in sets:
-        mask = sum(oracle.ST_NAMES[p] for p in pts)
+        mask = sum(names[p] for p in pts)
         got, _ = run(mask)
         want = forward_stored(cfg, w, k, v, tt, pts).numpy()
         # both are fp64 and differ by summation order (1e-14).  With several points rounded in a chain that difference
         # can move a value across a bf16 rounding boundary; the one stored element that then differs by one step moves
-        # that row's logits by ~1e-3.  A point alone must agree to rounding; a set on most rows, and nowhere by more
-        # than such a step.
+        # that row's logits by ~1e-3 (and, through the cache, the rows after it).  A point alone must agree to
+        # rounding; a set on at least half of the rows, and nowhere by more than such a step.
         diff = (np.abs(got - want) / np.abs(want).max()).max(axis=1)
         if len(pts) == 1:
             assert diff.max() < 1e-9, (pts, diff)
         else:
-            assert np.median(diff) < 1e-9 and diff.max() < 5e-3, (pts, diff)
+            assert (diff < 1e-9).sum() >= len(diff) // 2 and diff.max() < 5e-3, (pts, diff)
         # and the rounding really happened: the result differs from the plain forward by a bf16-sized amount
         rel = np.linalg.norm(got - ref) / np.linalg.norm(ref)
-        assert 1e-5 < rel < 3e-2, (pts, rel)
+        assert (1e-6 if pts in (("a16",), ("o16",)) else 1e-5) < rel < 3e-2, (pts, rel)
 
 
 def test_stored_kv_rows_are_bf16_values_and_the_context_is_untouched():
