@@ -69,6 +69,13 @@ typedef struct {
  * dtype; the per-layer members are HOST arrays of n_layers DEVICE pointers.  fsv_create() reads
  * them once (it copies fp32 weights and re-tiles bf16 matrices into the operand order of the
  * matrix cores); the caller may free all of them when fsv_create() has returned.
+ * FSV_BF16: the four projections whose input is bounded whatever the model (q|k|v, gate|up and the LM head
+ * take a normalised activation, the output projection a convex combination of cached values) run on fp16
+ * operands, which have three more significant bits than bf16 at the same size and rate; their matrices are
+ * converted once, times a power of two per matrix that puts its largest weight near 2^13, so that every
+ * weight down to 2^-31 of the largest converts exactly (smaller ones round on the fp16 subnormal grid of the
+ * scaled matrix), and the fp32 sums are multiplied by the inverse power.  The down projection (its input,
+ * the SwiGLU output, has no bound) and the KV cache stay bf16.
  */
 typedef struct {
   const void *embed;             /* [vocab][d_model]                                          */

@@ -101,7 +101,7 @@ void fsv_destroy(fsv_ctx *c) {
   void *ptrs[] = {c->embed, c->final_norm, c->lm_head, c->inv_freq, c->rope_tab, c->row_req, c->row_idx, c->row_pos, c->row_tok,
                   c->pmax, c->psum, c->parg, c->bsum, c->acc_scratch, c->sel_ticket, c->nuc_prefix,
                   c->nuc_key, c->nuc_above, c->nuc_total, c->nuc_S, c->nuc_near, c->nuc_done, c->nuc_cabove, c->nuc_kkey, c->nuc_kmass, c->x, c->logits,
-                  c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map,
+                  c->absmax, c->buf_a, c->buf_qkv, c->buf_q, c->buf_att, c->buf_gu, c->buf_act, c->buf_part, c->attn_part, c->attn_part_prefix, c->attn_part_map,
                   c->lora_aq, c->lora_bq, c->lora_ao, c->lora_bo, c->lora_scale, c->lora_t,
                   c->draft_w1, c->draft_w2, c->draft_wv, c->draft_h1, c->draft_h2};
   for (void *p : ptrs)

@@ -310,8 +310,9 @@ __global__ __launch_bounds__(64) void k_attention(
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
           const int e0 = 32 * c + 8 * g;
-          const uint32_t lo = (uint32_t)f2bf(o[rt][c][4 * g] * inv) | ((uint32_t)f2bf(o[rt][c][4 * g + 1] * inv) << 16);
-          const uint32_t hi = (uint32_t)f2bf(o[rt][c][4 * g + 2] * inv) | ((uint32_t)f2bf(o[rt][c][4 * g + 3] * inv) << 16);
+          // the output is a convex combination of cached values: bounded, so it is handed on in fp16
+          const uint32_t lo = f2h2(o[rt][c][4 * g] * inv, o[rt][c][4 * g + 1] * inv);
+          const uint32_t hi = f2h2(o[rt][c][4 * g + 2] * inv, o[rt][c][4 * g + 3] * inv);
           *reinterpret_cast<uint2 *>(out + tile_unit(m, col + e0, KBq) * 8 + 4 * h) = make_uint2(lo, hi);
         }
     } else {
@@ -397,7 +398,7 @@ __global__ __launch_bounds__(256) void k_attn_combine(int Hkv, int group, int ro
   const float inv = 1.0f / ll;
   uint32_t pk[4];
 #pragma unroll
-  for (int j = 0; j < 4; ++j) pk[j] = (uint32_t)f2bf(acc[2 * j] * inv) | ((uint32_t)f2bf(acc[2 * j + 1] * inv) << 16);
+  for (int j = 0; j < 4; ++j) pk[j] = f2h2(acc[2 * j] * inv, acc[2 * j + 1] * inv);
   const int m = rs + rr / group, col = (kvh * group + rr % group) * HD + e0;
   reinterpret_cast<uint4 *>(out)[tile_unit(m, col, KBq)] = make_uint4(pk[0], pk[1], pk[2], pk[3]);
 }

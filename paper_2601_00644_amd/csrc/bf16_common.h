@@ -14,6 +14,16 @@ __device__ inline uint16_t f2bf(float f) {  // round to nearest even (hardware c
   __bf16 b = (__bf16)f;
   return __builtin_bit_cast(uint16_t, b);
 }
+// fp16 (11 significant bits) for the two tensors that are bounded whatever the model: the normalised activations entering
+// a projection and the attention output.  Round to nearest even (hardware conversion), held at +-65504 beyond the range
+// (a NaN stays a NaN).
+__device__ inline uint16_t f2h(float f) {
+  const float g = fminf(fmaxf(f, -65504.0f), 65504.0f);
+  _Float16 hv = (_Float16)(f != f ? f : g);
+  return __builtin_bit_cast(uint16_t, hv);
+}
+__device__ inline float h2f(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+__device__ inline uint32_t f2h2(float lo, float hi) { return (uint32_t)f2h(lo) | ((uint32_t)f2h(hi) << 16); }
 __device__ inline float wave_sum(float v) {
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);

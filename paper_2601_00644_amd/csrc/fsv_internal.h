@@ -34,6 +34,8 @@ struct fsv_layer_w {
   // fp32 path: plain copies [out][in]; bf16 path: re-tiled matrices, plain gains
   void *attn_norm = nullptr, *w_qkv = nullptr, *w_o = nullptr, *mlp_norm = nullptr, *w_gate_up = nullptr,
        *w_down = nullptr;
+  // bf16 path: the matrices stored in fp16 carry a power of two; the projection's sums are multiplied by its inverse
+  float os_qkv = 1.0f, os_o = 1.0f, os_gate_up = 1.0f;
 };
 
 struct fsv_ctx {
@@ -69,6 +71,8 @@ struct fsv_ctx {
   // model workspace (both paths)
   float *x = nullptr;       // [rows_pad][d_model] residual stream, fp32
   float *logits = nullptr;  // [max_rows][vocab] fp32 when the caller passes no logits_out
+  float os_lm_head = 1.0f;      // bf16 path: inverse of the power of two the fp16 LM-head matrix carries
+  uint32_t *absmax = nullptr;   // bf16 path: one word for the largest weight magnitude of the matrix being converted
   void *buf_a = nullptr, *buf_qkv = nullptr, *buf_q = nullptr, *buf_att = nullptr, *buf_gu = nullptr,
        *buf_act = nullptr, *buf_part = nullptr;
   size_t part_bytes = 0;
@@ -180,7 +184,7 @@ int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl
 // 1 = SwiGLU to the bf16 operand order, 2 = fp32 rows [M][N]
 int fsv_bf16_gemm_init(fsv_ctx *c);
 int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
-                  int splits, int KBo, hipStream_t st);
+                  int splits, int KBo, int f16, float oscale, hipStream_t st);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
 int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *logits, int draft, hipStream_t s);

@@ -11,6 +11,12 @@
 // loads are issued by a wave of their own, the compute waves' load counter tracks the weight stream only
 // and a wait for the oldest chunk never drains the younger ones.  One barrier per chunk hands a filled
 // stage to the compute waves and a consumed one back to the loader.
+//
+// F16: both operands are fp16 (the projections whose input is a normalised activation or an attention output, which are
+// bounded whatever the model and gain three significant bits over bf16 that way).  Their weights were converted from bf16
+// at creation, times a power of two per matrix that places the largest weight near 2^13 (the conversion is then exact
+// for every weight down to 2^-31 of the largest); the epilogue multiplies the fp32 sums by the inverse power.  Same
+// instruction rate, same bytes.
 #include <hip/hip_ext.h>
 #include <math.h>
 #include <stdlib.h>
@@ -24,6 +30,7 @@ namespace {
 enum { EPI_PARTIAL = 0, EPI_SWIGLU = 1, EPI_F32 = 2 };
 
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 
 #define FSV_IN_AGPR(x) asm("" : "+a"(x))
 // The barrier as an opaque statement: memory operations do not move across it, and no counter wait is attached.
@@ -36,12 +43,16 @@ constexpr int NLD = 2;    // loader waves per block: two halve the time of the f
 
 // Stores one wave's result: for row tiles mt < mtc of the block starting at tile mt0, lane holds, for batch row
 // m = tile*32 + lane%32, features nt*32 + 8*(v/4) + 4*h + v%4 of strip nt.
-template <int MT, int EPI>
-__device__ __forceinline__ void store_strip(const f32x16_t (&acc)[MT], void *__restrict__ out, int nt, int mt0, int mtc, int lane,
-                                            int h, int split, int M, int Mpad, int N, int KBo) {
+template <int MT, int EPI, bool F16>
+__device__ __forceinline__ void store_strip(f32x16_t (&acc)[MT], void *__restrict__ out, int nt, int mt0, int mtc, int lane,
+                                            int h, int split, int M, int Mpad, int N, int KBo, float oscale) {
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     if (mt >= mtc) continue;
+    if constexpr (F16) {   // undo the power of two the weights carry (exact)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[mt][v] *= oscale;
+    }
     const int m = (mt0 + mt) * 32 + (lane & 31);
     if constexpr (EPI == EPI_PARTIAL) {
       if (m >= M) continue;  // the consumers read rows below M only
@@ -132,10 +143,10 @@ __device__ __forceinline__ void loader_wave(uint4 *lds, const uint4 *__restrict_
   }
 }
 
-template <int MT, int EPI, int D>
+template <int MT, int EPI, int D, bool F16>
 __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
                                               void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                              int S, int nchunks, int KBo, int NBv, int MB) {
+                                              int S, int nchunks, int KBo, int NBv, int MB, float oscale) {
   extern __shared__ uint4 lds[];
   constexpr int CHU = MT * KC * 64;  // 16-byte units of one activation chunk
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5;
@@ -210,8 +221,13 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
       __builtin_amdgcn_sched_barrier(0);
       FSV_IN_AGPR(wuse[kb]);
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], aop[kb % (DL + 1)][mt], acc[mt], 0, 0, 0);
+      for (int mt = 0; mt < MT; ++mt) {
+        if constexpr (F16)
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, wuse[kb]),
+                                                           __builtin_bit_cast(f16x8_t, aop[kb % (DL + 1)][mt]), acc[mt], 0, 0, 0);
+        else
+          acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wuse[kb], aop[kb % (DL + 1)][mt], acc[mt], 0, 0, 0);
+      }
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -231,26 +247,30 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
     }
   }
 
-  store_strip<MT, EPI>(acc, out, nt, mt0, mtc, lane, h, split, M, Mpad, N, KBo);
+  store_strip<MT, EPI, F16>(acc, out, nt, mt0, mtc, lane, h, split, M, Mpad, N, KBo, oscale);
 }
 
 template <int MT, int EPI>
 int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt,
-             int M, int Mpad, int splits, int nchunks, int KBo, int NB, int mblocks, hipStream_t st) {
+             int M, int Mpad, int splits, int nchunks, int KBo, int NB, int mblocks, int f16, float oscale, hipStream_t st) {
   // Weight chunks in flight per wave ahead of the one in use.  Measured on MI355X, one is best: with two to four the
   // bytes in flight across the chip approach the size of the L2s they pass through and the achieved bandwidth drops.
   constexpr int D = 1;
   const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;   // fsv_bf16_gemm_init has raised the kernel's limit to this
   // the profiling events ride on the dispatch itself: they time the kernel, not the gaps around it
   fsv_prof_scope ps(c, st, cls, (double)N * KB * 32.0, true);
-  hipExtLaunchKernelGGL((k_gemm<MT, EPI, D>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
-                        (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks);
+  if (f16)
+    hipExtLaunchKernelGGL((k_gemm<MT, EPI, D, true>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
+                          (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, oscale);
+  else
+    hipExtLaunchKernelGGL((k_gemm<MT, EPI, D, false>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
+                          (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, 1.0f);
   return FSV_OK;
 }
 
 template <int EPI>
 int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits,
-             int KBo, hipStream_t st) {
+             int KBo, int f16, float oscale, hipStream_t st) {
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = K / 256, KB = K / 16;
   // row tiles per block: the fewest row blocks of at most four tiles (more do not fit the 256 registers a wave of a
   // six-wave block may use), the tiles spread evenly over them (five tiles are taken as 3 + 2, not 4 + 1: a block
@@ -262,7 +282,7 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
   // one-dimensional grid, decoded in the kernel; feature blocks padded to a multiple of eight when the splits are not
   const int NB = NTpad / 4, NBg = (splits % 8 == 0) ? NB : (NB + 7) / 8 * 8;
   dim3 grid((unsigned)NBg * splits * mblocks, 1, 1);
-#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, st
+#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, f16, oscale, st
   switch (mt_blk) {
     case 1: return launch_t<1, EPI>(FSV_ARGS);
     case 2: return launch_t<2, EPI>(FSV_ARGS);
@@ -274,7 +294,9 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
 
 template <int MT, int EPI>
 int init_t(fsv_ctx *c) {
-  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1>),
+  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1, false>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, NST * MT * KC * 64 * 16));
+  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1, true>),
                                  hipFuncAttributeMaxDynamicSharedMemorySize, NST * MT * KC * 64 * 16));
   return FSV_OK;
 }
@@ -296,13 +318,14 @@ int fsv_bf16_gemm_init(fsv_ctx *c) {
   return FSV_OK;
 }
 
+// f16: both operands are fp16 and the sums are multiplied by oscale (see the head of this file); else bf16 operands.
 int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
-                  int splits, int KBo, hipStream_t st) {
+                  int splits, int KBo, int f16, float oscale, hipStream_t st) {
   int rc;
   switch (epi) {
-    case EPI_PARTIAL: rc = launch_e<EPI_PARTIAL>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, st); break;
-    case EPI_SWIGLU: rc = launch_e<EPI_SWIGLU>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, st); break;
-    default: rc = launch_e<EPI_F32>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, st); break;
+    case EPI_PARTIAL: rc = launch_e<EPI_PARTIAL>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, st); break;
+    case EPI_SWIGLU: rc = launch_e<EPI_SWIGLU>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, st); break;
+    default: rc = launch_e<EPI_F32>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, st); break;
   }
   if (rc) return rc;
   FSV_HIP(c, hipGetLastError());

@@ -29,7 +29,8 @@ namespace {
 // mode 0: packed row n' = source row n'.  mode 1 (gate|up): every 32-row tile holds 16 hidden features,
 // gate and up interleaved in groups of 8 (rows 0-7 gate f0-7, 8-15 up f0-7, 16-23 gate f8-15, 24-31 up f8-15),
 // so that after the MFMA one lane owns gate and up of the same four features.
-__global__ void k_pack_w(const uint16_t *__restrict__ W, int N, int K, int NTpad, int mode, int F, uint4 *__restrict__ out) {
+__global__ void k_pack_w(const uint16_t *__restrict__ W, int N, int K, int NTpad, int mode, int F, uint4 *__restrict__ out,
+                         int f16, float wscale) {
   const size_t unit = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int KB = K / 16;
   if (unit >= (size_t)NTpad * KB * 64) return;
@@ -44,21 +45,48 @@ __global__ void k_pack_w(const uint16_t *__restrict__ W, int N, int K, int NTpad
   }
   uint4 v = make_uint4(0, 0, 0, 0);
   if (src >= 0) v = *reinterpret_cast<const uint4 *>(W + (size_t)src * K + k0);
+  if (f16) {   // bf16 -> fp16 times a power of two (see pack_weight)
+    uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      w4[j] = f2h2(__uint_as_float(w4[j] << 16) * wscale, __uint_as_float(w4[j] & 0xffff0000u) * wscale);
+    v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+  }
   out[unit] = v;
 }
 
-// row-major bf16 [M][K] -> operand order, zero rows up to Mpad
-__global__ void k_pack_act(const uint16_t *__restrict__ x, int M, int Mpad, int K, uint4 *__restrict__ out) {
+// largest magnitude (as bf16 bits without the sign) of n bf16 values, n a multiple of 8; *out starts at zero
+__global__ void k_absmax_bf16(const uint4 *__restrict__ W, size_t n8, uint32_t *__restrict__ out) {
+  uint32_t m = 0;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+    const uint4 v = W[i];
+    const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) m = max(m, max(w4[j] & 0x7fffu, (w4[j] >> 16) & 0x7fffu));
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) m = max(m, (uint32_t)__shfl_xor((int)m, off, 64));
+  if ((threadIdx.x & 63) == 0 && m) atomicMax(out, m);
+}
+
+// row-major bf16 [M][K] -> operand order (f16: converted to fp16, the operand type of that projection), zero rows up to Mpad
+__global__ void k_pack_act(const uint16_t *__restrict__ x, int M, int Mpad, int K, uint4 *__restrict__ out, int f16) {
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int K8 = K / 8;
   if (t >= (size_t)Mpad * K8) return;
   const int m = t / K8, k0 = (t % K8) * 8;
   uint4 v = make_uint4(0, 0, 0, 0);
   if (m < M) v = *reinterpret_cast<const uint4 *>(x + (size_t)m * K + k0);
+  if (f16) {
+    uint32_t w4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) w4[j] = f2h2(__uint_as_float(w4[j] << 16), __uint_as_float(w4[j] & 0xffff0000u));
+    v = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+  }
   out[tile_unit(m, k0, K / 16)] = v;
 }
 
-// operand order bf16 -> row-major fp32 [M][K]
+// operand order fp16 (the attention output) -> row-major fp32 [M][K]
 __global__ void k_unpack_act(const uint4 *__restrict__ in, int M, int K, float *__restrict__ y) {
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int K8 = K / 8;
@@ -69,8 +97,8 @@ __global__ void k_unpack_act(const uint4 *__restrict__ in, int M, int K, float *
   float *dst = y + (size_t)m * K + k0;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    dst[2 * j] = __uint_as_float(w[j] << 16);
-    dst[2 * j + 1] = __uint_as_float(w[j] & 0xffff0000u);
+    dst[2 * j] = h2f((uint16_t)(w[j] & 0xffffu));
+    dst[2 * j + 1] = h2f((uint16_t)(w[j] >> 16));
   }
 }
 
@@ -206,7 +234,9 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       float g0 = __uint_as_float(g4[j] << 16), g1 = __uint_as_float(g4[j] & 0xffff0000u);
-      o[j] = (uint32_t)f2bf(v[2 * j] * rinv * g0) | ((uint32_t)f2bf(v[2 * j + 1] * rinv * g1) << 16);
+      // a normalised activation is at most sqrt(d) times its gain: fp16; the raw residual stream has no bound: bf16
+      if (RAW) o[j] = (uint32_t)f2bf(v[2 * j] * rinv * g0) | ((uint32_t)f2bf(v[2 * j + 1] * rinv * g1) << 16);
+      else o[j] = f2h2(v[2 * j] * rinv * g0, v[2 * j + 1] * rinv * g1);
     }
     return make_uint4(o[0], o[1], o[2], o[3]);
   };
@@ -226,12 +256,12 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
       // output projection of an adapted request: v += s B_o (A_o att), att = this row of the attention output
       const int KBa = lo.qd / 16;
       auto att_slice = [&](int kk, float(&xv)[8]) {
-        const uint4 raw = lo.att[tile_unit(r, kk, KBa)];
+        const uint4 raw = lo.att[tile_unit(r, kk, KBa)];   // fp16
         const uint32_t w4[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          xv[2 * u] = __uint_as_float(w4[u] << 16);
-          xv[2 * u + 1] = __uint_as_float(w4[u] & 0xffff0000u);
+          xv[2 * u] = h2f((uint16_t)(w4[u] & 0xffffu));
+          xv[2 * u + 1] = h2f((uint16_t)(w4[u] >> 16));
         }
       };
       lora_shrink(lo.ao + (size_t)ad * lo.rank * lo.qd, lo.rank, lo.qd, tid, (int)blockDim.x, att_slice, s_part, s_t);
@@ -271,11 +301,11 @@ __global__ __launch_bounds__(1024) void k_resid_norm(int M, int d, float eps, co
     if (LQ && ad >= 0) {
       // the q|k|v projection that follows is adapted for this row: leave t = A_qkv a (a = the operand just stored)
       auto own_slice = [&](int kk, float(&xv)[8]) {   // kk == k0: one slice per thread
-        const uint32_t w4[4] = {packed.x, packed.y, packed.z, packed.w};
+        const uint32_t w4[4] = {packed.x, packed.y, packed.z, packed.w};   // fp16 (never the RAW form)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-          xv[2 * u] = __uint_as_float(w4[u] << 16);
-          xv[2 * u + 1] = __uint_as_float(w4[u] & 0xffff0000u);
+          xv[2 * u] = h2f((uint16_t)(w4[u] & 0xffffu));
+          xv[2 * u + 1] = h2f((uint16_t)(w4[u] >> 16));
         }
       };
       lora_shrink(lo.aq + (size_t)ad * lo.rank * d, lo.rank, d, tid, (int)blockDim.x, own_slice, s_part, s_t);
@@ -545,6 +575,7 @@ enum { W_DRAFT1 = 5, W_DRAFT2 = 6, W_DRAFTV = 7 };   // the three projections of
 
 struct gemm_shape {
   int N, K, NTpad, mode;  // mode 1 = gate|up interleave
+  int f16;                // operands in fp16: the projections fed by a normalisation or by the attention output
 };
 
 gemm_shape shape_of(const fsv_ctx *c, int which) {
@@ -552,14 +583,14 @@ gemm_shape shape_of(const fsv_ctx *c, int which) {
   const int qd = d.n_heads * d.head_dim, qkvd = (d.n_heads + 2 * d.n_kv_heads) * d.head_dim;
   gemm_shape s{};
   switch (which) {
-    case FSV_W_QKV: s.N = qkvd; s.K = d.d_model; break;
-    case FSV_W_O: s.N = d.d_model; s.K = qd; break;
-    case FSV_W_GATE_UP: s.N = 2 * d.d_ffn; s.K = d.d_model; s.mode = 1; break;
+    case FSV_W_QKV: s.N = qkvd; s.K = d.d_model; s.f16 = 1; break;
+    case FSV_W_O: s.N = d.d_model; s.K = qd; s.f16 = 1; break;
+    case FSV_W_GATE_UP: s.N = 2 * d.d_ffn; s.K = d.d_model; s.mode = 1; s.f16 = 1; break;
     case FSV_W_DOWN: s.N = d.d_model; s.K = d.d_ffn; break;
     case W_DRAFT1: s.N = c->draft_dh; s.K = d.d_model; break;
     case W_DRAFT2: s.N = c->draft_dp; s.K = c->draft_dh; break;
     case W_DRAFTV: s.N = d.vocab; s.K = c->draft_dp; break;
-    default: s.N = d.vocab; s.K = d.d_model; break;
+    default: s.N = d.vocab; s.K = d.d_model; s.f16 = 1; break;   // LM head
   }
   s.NTpad = fsv_ceil_div(fsv_ceil_div(s.N, 32), 4) * 4;
   return s;
@@ -582,13 +613,33 @@ int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
   return sp;
 }
 
-int pack_weight(fsv_ctx *c, const void *src, int which, void **dst) {
+// Re-tile one weight matrix into the operand order of the matrix cores.  A matrix of an fp16 projection (shape_of().f16)
+// is converted from bf16 on the way, times 2^s with s chosen so that its largest weight lands in [2^13, 2^14): every
+// weight down to 2^-31 of the largest is then an exact fp16 number (smaller ones round on the 2^-24 grid of the scaled
+// matrix), and nothing overflows.  *oscale receives 2^-s, which the projection multiplies its fp32 sums by.
+int pack_weight(fsv_ctx *c, const void *src, int which, void **dst, float *oscale = nullptr) {
   gemm_shape s = shape_of(c, which);
   const size_t units = (size_t)s.NTpad * (s.K / 16) * 64;
   if (units * 16 > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
+  float wscale = 1.0f;
+  if (s.f16) {
+    if (!oscale) FSV_FAIL(c, FSV_E_INVALID_ARG, "internal: an fp16 projection needs a place for its scale");
+    if (!c->absmax) FSV_HIP(c, hipMalloc((void **)&c->absmax, sizeof(uint32_t)));
+    FSV_HIP(c, hipMemset(c->absmax, 0, sizeof(uint32_t)));
+    const size_t n8 = (size_t)s.N * s.K / 8;
+    hipLaunchKernelGGL(k_absmax_bf16, dim3((unsigned)min((size_t)4096, (n8 + 255) / 256)), dim3(256), 0, 0, (const uint4 *)src, n8,
+                       c->absmax);
+    uint32_t bits = 0;
+    FSV_HIP(c, hipMemcpy(&bits, c->absmax, sizeof bits, hipMemcpyDeviceToHost));
+    int sh = 0;
+    if (bits >= 0x0080u && bits < 0x7f80u) sh = 13 - ((int)(bits >> 7) - 127);   // a finite, normal largest weight
+    sh = max(-100, min(100, sh));
+    wscale = ldexpf(1.0f, sh);
+    *oscale = ldexpf(1.0f, -sh);
+  }
   FSV_HIP(c, hipMalloc(dst, units * 16));
   hipLaunchKernelGGL(k_pack_w, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, 0, (const uint16_t *)src, s.N, s.K,
-                     s.NTpad, s.mode, c->d.d_ffn, (uint4 *)*dst);
+                     s.NTpad, s.mode, c->d.d_ffn, (uint4 *)*dst, s.f16, wscale);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -601,8 +652,9 @@ int copy_dev(fsv_ctx *c, void **dst, const void *src, size_t bytes) {
 
 template <int EPI>
 int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, int splits,
-                hipStream_t st) {
-  return fsv_bf16_gemm(c, cls, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0, st);
+                hipStream_t st, float oscale = 1.0f) {
+  return fsv_bf16_gemm(c, cls, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0, s.f16,
+                       oscale, st);
 }
 
 size_t layer_stride(const fsv_ctx *c, int num_pages) {
@@ -623,15 +675,15 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
   }
   if ((rc = copy_dev(c, &c->embed, w->embed, (size_t)2 * d.vocab * d.d_model))) return rc;
   if ((rc = copy_dev(c, &c->final_norm, w->final_norm, (size_t)2 * d.d_model))) return rc;
-  if ((rc = pack_weight(c, w->lm_head, FSV_W_LM_HEAD, &c->lm_head))) return rc;
+  if ((rc = pack_weight(c, w->lm_head, FSV_W_LM_HEAD, &c->lm_head, &c->os_lm_head))) return rc;
   c->layers.resize(d.n_layers);
   for (int l = 0; l < d.n_layers; ++l) {
     fsv_layer_w &L = c->layers[l];
     if ((rc = copy_dev(c, &L.attn_norm, w->attn_norm[l], (size_t)2 * d.d_model))) return rc;
     if ((rc = copy_dev(c, &L.mlp_norm, w->mlp_norm[l], (size_t)2 * d.d_model))) return rc;
-    if ((rc = pack_weight(c, w->w_qkv[l], FSV_W_QKV, &L.w_qkv))) return rc;
-    if ((rc = pack_weight(c, w->w_o[l], FSV_W_O, &L.w_o))) return rc;
-    if ((rc = pack_weight(c, w->w_gate_up[l], FSV_W_GATE_UP, &L.w_gate_up))) return rc;
+    if ((rc = pack_weight(c, w->w_qkv[l], FSV_W_QKV, &L.w_qkv, &L.os_qkv))) return rc;
+    if ((rc = pack_weight(c, w->w_o[l], FSV_W_O, &L.w_o, &L.os_o))) return rc;
+    if ((rc = pack_weight(c, w->w_gate_up[l], FSV_W_GATE_UP, &L.w_gate_up, &L.os_gate_up))) return rc;
     if ((rc = pack_weight(c, w->w_down[l], FSV_W_DOWN, &L.w_down))) return rc;
   }
   // rotary frequencies theta^(-2i/hd) in fp64
@@ -720,7 +772,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     const size_t lo = (size_t)(draft ? 0 : l) * layer_stride(c, b->num_pages);
     const bool adapted = lora && l < d.n_layers - 1;         // the last block belongs to the invariant head
     const bool next_adapted = lora && l + 1 < d.n_layers - 1;
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s))) return rc;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s, L.os_qkv))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
       const dim3 rg(M, fsv_ceil_div((d.n_heads + 2 * d.n_kv_heads) * (d.head_dim / 8), 256));
@@ -736,7 +788,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
 #undef FSV_ROPE_ARGS
     }
     if ((rc = fsv_bf16_attn_launch(c, b, &pl, lo, s))) return rc;
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s))) return rc;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s, L.os_o))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
       if (adapted)
@@ -746,7 +798,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
         hipLaunchKernelGGL((k_resid_norm<0, 0, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
                            part, spo, Mpad, c->x, (const uint16_t *)L.mlp_norm, (uint4 *)c->buf_a, lora_args{});
     }
-    if ((rc = launch_gemm<EPI_SWIGLU>(c, FSV_K_GEMM_GATE_UP, L.w_gate_up, c->buf_a, c->buf_act, sg, M, 1, s))) return rc;
+    if ((rc = launch_gemm<EPI_SWIGLU>(c, FSV_K_GEMM_GATE_UP, L.w_gate_up, c->buf_a, c->buf_act, sg, M, 1, s, L.os_gate_up))) return rc;
     if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_DOWN, L.w_down, c->buf_act, part, sd, M, spd, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
@@ -774,7 +826,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     FSV_HIP(c, hipGetLastError());
     return FSV_OK;
   }
-  if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->lm_head, c->buf_a, logits, sl, M, 1, s))) return rc;
+  if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->lm_head, c->buf_a, logits, sl, M, 1, s, c->os_lm_head))) return rc;
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -865,20 +917,21 @@ int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, floa
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32;
   const void *Wp;
   int cls;
+  float os = 1.0f;
   switch (which) {
-    case FSV_W_QKV: Wp = c->layers[layer].w_qkv; cls = FSV_K_GEMM_QKV; break;
-    case FSV_W_O: Wp = c->layers[layer].w_o; cls = FSV_K_GEMM_O; break;
-    case FSV_W_GATE_UP: Wp = c->layers[layer].w_gate_up; cls = FSV_K_GEMM_GATE_UP; break;
+    case FSV_W_QKV: Wp = c->layers[layer].w_qkv; cls = FSV_K_GEMM_QKV; os = c->layers[layer].os_qkv; break;
+    case FSV_W_O: Wp = c->layers[layer].w_o; cls = FSV_K_GEMM_O; os = c->layers[layer].os_o; break;
+    case FSV_W_GATE_UP: Wp = c->layers[layer].w_gate_up; cls = FSV_K_GEMM_GATE_UP; os = c->layers[layer].os_gate_up; break;
     case FSV_W_DOWN: Wp = c->layers[layer].w_down; cls = FSV_K_GEMM_DOWN; break;
-    default: Wp = c->lm_head; cls = FSV_K_GEMM_LM_HEAD; break;
+    default: Wp = c->lm_head; cls = FSV_K_GEMM_LM_HEAD; os = c->os_lm_head; break;
   }
   const size_t nact = (size_t)Mpad * (sh.K / 8);
   hipLaunchKernelGGL(k_pack_act, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, s, (const uint16_t *)x, M, Mpad, sh.K,
-                     (uint4 *)c->buf_a);
+                     (uint4 *)c->buf_a, sh.f16);
   int rc;
-  if (which == FSV_W_LM_HEAD) return launch_gemm<EPI_F32>(c, cls, Wp, c->buf_a, y, sh, M, 1, s);
+  if (which == FSV_W_LM_HEAD) return launch_gemm<EPI_F32>(c, cls, Wp, c->buf_a, y, sh, M, 1, s, os);
   const int sp = pick_splits(c, sh, Mt, which != FSV_W_GATE_UP);
-  if ((rc = launch_gemm<EPI_PARTIAL>(c, cls, Wp, c->buf_a, c->buf_part, sh, M, sp, s))) return rc;
+  if ((rc = launch_gemm<EPI_PARTIAL>(c, cls, Wp, c->buf_a, c->buf_part, sh, M, sp, s, os))) return rc;
   const size_t n = (size_t)M * sh.N;
   hipLaunchKernelGGL(k_reduce_part, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float *)c->buf_part, sp, Mpad,
                      M, sh.N, sh.mode, c->d.d_ffn, y);

@@ -44,6 +44,37 @@ def test_linear_matches_oracle(name, M):
     ctx.close()
 
 
+@pytest.mark.parametrize("scale", [1e-7, 1.0, 2.0e4])
+def test_linear_over_the_range_of_weight_magnitudes(scale):
+    """The projections that keep their operands in fp16 convert their bf16 weights once, times a power of two per matrix:
+    matrices whose largest weight is far below or far above the fp16 range, with entries spread over twelve decades inside
+    one matrix, and an all-zero matrix, against the oracle's definition on the bf16 weights."""
+    from paper_2601_00644_amd import flexverify as fv
+    cfg = synth.MODELS["mini64"]
+    w = synth.make_weights(cfg, 5, std=0.05)
+    g = torch.Generator().manual_seed(17)
+    keys = [(fv.W_QKV, "w_qkv.0", cfg.d_model), (fv.W_O, "w_o.1", cfg.n_heads * cfg.head_dim),
+            (fv.W_GATE_UP, "w_gate_up.0", cfg.d_model), (fv.W_LM_HEAD, "lm_head", cfg.d_model)]
+    for _, key, _ in keys:
+        decades = torch.rand(w[key].shape, generator=g) * 12.0                 # each entry 10^-u of its size, u in [0, 12)
+        w[key] = (w[key].float() * scale * 20.0 * torch.pow(10.0, -decades)).to(torch.bfloat16)
+    w["w_o.0"] = torch.zeros_like(w["w_o.0"])
+    wn = synth.weights_to_numpy(cfg, w)
+    ctx = fv.Context(cfg, {k: v.cuda() for k, v in w.items()}, 4, 8, 8, max_rows=40)
+    for wh, key, K in keys + [(fv.W_O, "w_o.0", cfg.n_heads * cfg.head_dim)]:
+        layer = int(key.split(".")[1]) if "." in key else 0
+        x = torch.randn((37, K), generator=g).to(torch.bfloat16)
+        y = ctx.linear(wh, layer, x.cuda(), wn[key].shape[0]).cpu().numpy().astype(np.float64)
+        ref = oracle.linear(wn[key], x.float().numpy().astype(np.float64), True)
+        if key == "w_o.0":
+            assert not y.any() and not ref.any()
+            continue
+        assert np.isfinite(y).all() and np.abs(ref).max() > 0
+        ok, ratio = logits_close(y, ref, 1e-3)
+        assert ok, (key, scale, ratio)
+    ctx.close()
+
+
 def _attention_case(cfg, seed, seq_lens, gammas, pages):
     B = len(seq_lens)
     seq_lens, gammas = np.asarray(seq_lens, np.int32), np.asarray(gammas, np.int32)

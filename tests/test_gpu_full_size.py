@@ -4,10 +4,10 @@ The oracle cannot score a whole 8B-shape batch in test time, but requests are in
 step of the verification path, so a subset is exact: a few sampled requests are given drafts the
 ORACLE stepped (nothing the oracle consumes comes from the library), the library verifies the full
 batch, and for the sampled requests logits, decisions, rollback and appended KV are compared with
-the oracle.  The logit bar is helpers.check_bf16_logits: against the plain fp64 oracle a flat 2e-2
-for the 16-layer 1B shapes and, at the 32 layers of the 8B shapes, 1.25 times what bf16 storage alone
-costs on the same request (the oracle's two modes compared in the test); the appended cache rows of
-layer 0 equal the bf16-storage oracle's bit for bit, deeper layers within the same bar.
+the oracle.  The logit bar is helpers.check_bf16_logits: a flat 2e-2 against the plain fp64 oracle at
+every size (what 16-bit storage alone costs on the same request is computed beside it, by the oracle
+in its storage mode, and printed); the appended cache rows of layer 0 equal the storage-mode oracle's
+bit for bit, deeper layers within the same bar.
 For every request of the batch the accept / resample arithmetic is compared exactly on identical
 logits: the oracle's sampler is run on the logits the library produced (flagged draws counted), and
 the rollback outputs against their closed form.  The sampling configuration (logits are inputs) is
@@ -132,7 +132,7 @@ def test_c3_8b_batch16_sampled_requests(llama8b):
                 break
             want.add(b)
         return sorted(want)
-    _check_workload("c3_8b_b16", weights, wn, 1, pick, flat=False)
+    _check_workload("c3_8b_b16", weights, wn, 1, pick, flat=True)
 
 
 def test_c5_8b_batch128_sampled_requests(llama8b):
@@ -141,7 +141,7 @@ def test_c5_8b_batch128_sampled_requests(llama8b):
     def pick(req):
         few = np.nonzero(req.gammas <= 4)[0]
         return sorted({int(np.argmin(req.seq_lens)), int(few[np.argmax(req.seq_lens[few])]), int(np.argmax(req.gammas))})
-    _check_workload("c5_8b_b128", weights, wn, 1, pick, flat=False)
+    _check_workload("c5_8b_b128", weights, wn, 1, pick, flat=True)
 
 
 @pytest.fixture(scope="module")
