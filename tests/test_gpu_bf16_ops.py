@@ -75,6 +75,33 @@ def test_linear_over_the_range_of_weight_magnitudes(scale):
     ctx.close()
 
 
+def test_fp16_operand_conversion_saturates_and_keeps_nan():
+    """An operand beyond the fp16 range is held at +-65504 (never turned into an infinity), a NaN stays a NaN, and values
+    on the fp16 subnormal grid survive: the q|k|v projection of hand-placed rows against the oracle's definition applied to
+    the oracle's own fp16 rounding of the same rows."""
+    cfg = synth.MODELS["mini64"]
+    fv, ctx, w, wn = _ctx(cfg, 9, max_batch=4, max_gamma=8, max_rows=40)
+    K = cfg.d_model
+    g = torch.Generator().manual_seed(23)
+    x = torch.randn((6, K), generator=g)
+    x[1, ::7] = 1.0e6
+    x[1, 3::7] = -3.0e5
+    x[2] *= 2.0e-6                       # most of the row below the smallest normal fp16 number
+    x[3, 5] = float("nan")
+    x[4] *= 3.0e4                        # some entries beyond the range, some inside
+    xb = x.to(torch.bfloat16)
+    y = ctx.linear(fv.W_QKV, 0, xb.cuda(), wn["w_qkv.0"].shape[0]).cpu().numpy().astype(np.float64)
+    x16 = np.vectorize(oracle.round_f16)(xb.float().numpy().astype(np.float64))
+    assert np.abs(x16[np.isfinite(x16)]).max() == 65504.0
+    ref = oracle.linear(wn["w_qkv.0"], np.nan_to_num(x16, nan=0.0), True)
+    rows = [0, 1, 2, 4, 5]
+    assert np.isfinite(y[rows]).all()
+    ok, ratio = logits_close(y[rows], ref[rows], 1e-3)
+    assert ok, ratio
+    assert np.isnan(y[3]).all()          # every feature of the row sums over the NaN
+    ctx.close()
+
+
 def _attention_case(cfg, seed, seq_lens, gammas, pages):
     B = len(seq_lens)
     seq_lens, gammas = np.asarray(seq_lens, np.int32), np.asarray(gammas, np.int32)
