@@ -1,4 +1,4 @@
-// Weight-streaming bf16 GEMM of the FSV_BF16 path: the dense projections of the target forward (Alg. 2
+// Weight-streaming 16-bit GEMM (bf16 or fp16 operands, fp32 sums) of the FSV_BF16 path: the dense projections of the target forward (Alg. 2
 // step 2) for a few dozen to a few hundred rows, where streaming the weight matrix from HBM is the bound.
 // Built with -mllvm -amdgpu-mfma-vgpr-form (accumulators in architectural registers, the weight chunks in
 // flight in accumulation registers).
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, wbytes, 0x00020000);
   const uint32_t wbase = ((uint32_t)nt * (uint32_t)KB * 64u + (uint32_t)lane) * 16u;
   constexpr uint32_t OOB = 0xFFFF0000u;  // a chunk beyond the K range: the descriptor returns zeros, no memory traffic
-  bf16x8_t wb[D + 1][KC];
+  bf16x8_t wb[D + 1][KC];   // sixteen bytes of operand per lane; the element type only matters to the MFMA below
   auto issue = [&](int it, bf16x8_t(&dst)[KC]) {
     const uint32_t off = (it < per) ? wbase + (uint32_t)(cb0 + it) * (KC * 1024u) : OOB;
 #pragma unroll

@@ -1,7 +1,8 @@
 // FSV_BF16 instantiation of the target forward (Alg. 2 step 2: the target model scores the pending
 // token and the received draft block on top of the user's restored KV session; Sec. IV-C: KV pairs
-// are computed only for the new tokens).  Written for gfx950: 64-wide waves, bf16 matrix cores
-// (v_mfma_f32_32x32x16_bf16), weights and KV pages stored in the order the matrix cores consume
+// are computed only for the new tokens).  Written for gfx950: 64-wide waves, 16-bit matrix cores
+// (v_mfma_f32_32x32x16_bf16 / _f16: the activations that are bounded by construction, i.e. the output of
+// a normalisation and of the attention, travel in fp16, everything else in bf16), weights and KV pages stored in the order the matrix cores consume
 // them so that every global load of the two dominant streams (weights, KV) is one contiguous
 // 1 KiB request per wave and needs no LDS round trip.
 //
