@@ -439,7 +439,7 @@ int plan_attention(fsv_ctx *c, const fsv_batch *b, fsv_attn_plan *pl) {
     }
     return parts * d.n_kv_heads;
   };
-  const int even = (int)max(2L, (total_tiles * d.n_kv_heads + target - 1) / target);
+  const int even = (int)max((long)c->attn_min_tpw, (total_tiles * d.n_kv_heads + target - 1) / target);
   int tpw = 0;
   for (int t = even; t <= 2 * even; ++t) {
     bool sp;
@@ -523,11 +523,12 @@ int fsv_bf16_attn_create(fsv_ctx *c) {
   const fsv_model_desc &d = c->d;
   int wpc = kAttnWavesPerCu;
   c->attn_depth = 2;
-  if (const char *e = getenv("FSV_ATTN_TUNE")) {   // "waves per CU,tiles in flight[,w2,w3]": measurement knob
-    int a = 0, bb = 0, w2 = c->attn_w2, w3 = c->attn_w3;
-    const int n = sscanf(e, "%d,%d,%d,%d", &a, &bb, &w2, &w3);
+  if (const char *e = getenv("FSV_ATTN_TUNE")) {   // "waves per CU,tiles in flight[,w2,w3[,fewest tiles per part]]": measurement knob
+    int a = 0, bb = 0, w2 = c->attn_w2, w3 = c->attn_w3, mt = c->attn_min_tpw;
+    const int n = sscanf(e, "%d,%d,%d,%d,%d", &a, &bb, &w2, &w3, &mt);
     if (n >= 2 && a >= 1 && a <= 8 && bb >= 2 && bb <= 3) { wpc = a; c->attn_depth = bb; }
-    if (n == 4 && w2 >= 16 && w2 <= 64 && w3 >= w2 && w3 <= 96) { c->attn_w2 = w2; c->attn_w3 = w3; }
+    if (n >= 4 && w2 >= 16 && w2 <= 64 && w3 >= w2 && w3 <= 96) { c->attn_w2 = w2; c->attn_w3 = w3; }
+    if (n == 5 && mt >= 2 && mt <= 64) c->attn_min_tpw = mt;
   }
   c->attn_wave_target = c->n_cus * wpc;
   c->attn_wave_cap = 4 * c->attn_wave_target + 2 * d.max_batch * d.n_kv_heads;  // multi-round schedules: see plan_attention

@@ -71,6 +71,7 @@ struct fsv_ctx {
   // model workspace (both paths)
   float *x = nullptr;       // [rows_pad][d_model] residual stream, fp32
   float *logits = nullptr;  // [max_rows][vocab] fp32 when the caller passes no logits_out
+  int gemm_ncw_force = 0;       // bf16 path: 2..4 = weight strips per GEMM block fixed (FSV_GEMM_NCW, a measurement and test knob)
   float os_lm_head = 1.0f;      // bf16 path: inverse of the power of two the fp16 LM-head matrix carries
   uint32_t *absmax = nullptr;   // bf16 path: one word for the largest weight magnitude of the matrix being converted
   void *buf_a = nullptr, *buf_qkv = nullptr, *buf_q = nullptr, *buf_att = nullptr, *buf_gu = nullptr,
@@ -83,6 +84,8 @@ struct fsv_ctx {
   int attn_wave_target = 0;     // waves the attention schedule aims at (resident waves of the device)
   int attn_wave_cap = 0;        // waves the partial buffers hold
   int attn_depth = 2;           // K/V tiles in flight per attention wave
+  int attn_min_tpw = 5;         // fewest key tiles a part is given: with a single 2048-position request, parts of 5 tiles
+                                // (13 per kv head, merged from one batch of loads) beat parts of 2 (33 per head) by 4 % of the call
   int attn_w2 = 26, attn_w3 = 36;  // cost of a key tile for a request with two / three query-row tiles, in 1/16 of one with one
   int32_t *attn_part_prefix = nullptr, *attn_part_map = nullptr;   // parts before each request; 8-int record per part
 
@@ -184,7 +187,7 @@ int fsv_bf16_attn_launch(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl
 // 1 = SwiGLU to the bf16 operand order, 2 = fp32 rows [M][N]
 int fsv_bf16_gemm_init(fsv_ctx *c);
 int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
-                  int splits, int KBo, int f16, float oscale, hipStream_t st);
+                  int splits, int KBo, int f16, float oscale, int ncw, hipStream_t st);
 // path_bf16.hip
 int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w);
 int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *pl, int M, float *logits, int draft, hipStream_t s);

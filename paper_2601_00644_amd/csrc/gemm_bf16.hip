@@ -3,7 +3,8 @@
 // Built with -mllvm -amdgpu-mfma-vgpr-form (accumulators in architectural registers, the weight chunks in
 // flight in accumulation registers).
 //
-// A block is four compute waves and NLD loader waves.  Compute wave w owns 32 output features (one weight
+// A block is up to four compute waves (the host picks two to four, so that the launch fills the compute units) and NLD
+// loader waves.  Compute wave w owns 32 output features (one weight
 // tile row) for up to MT*32 batch rows over the block's K range and streams that strip of the re-tiled
 // matrix straight from HBM into MFMA operand registers, D chunks of 128 k (D = 1) ahead of its use.  The loader waves
 // copy the activation chunks of the same K range from global memory (L2) directly into a three-stage LDS
@@ -143,10 +144,11 @@ __device__ __forceinline__ void loader_wave(uint4 *lds, const uint4 *__restrict_
   }
 }
 
-template <int MT, int EPI, int D, bool F16>
-__global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
+template <int MT, int EPI, int D, bool F16, int NCW>
+__global__ __launch_bounds__(64 * (NCW + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
                                               void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                              int S, int nchunks, int KBo, int NBv, int MB, float oscale) {
+                                              int S, int nchunks, int KBo, int NBv, int MB, float oscale, int NT) {
+  // NCW: compute waves of the block (the block has NCW + NLD waves); NT: weight strips the matrix holds
   extern __shared__ uint4 lds[];
   constexpr int CHU = MT * KC * 64;  // 16-byte units of one activation chunk
   const int tid = threadIdx.x, w = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63, h = lane >> 5;
@@ -174,13 +176,20 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
   // K range of the split: a balanced cut of the `nchunks` granules into S parts, counted in chunks
   const int cb0 = (split * nchunks / S) * GRAN, per = ((split + 1) * nchunks / S) * GRAN - cb0;
 
-  if (w >= 4) {
-    loader_wave<MT>(lds, Ap, w - 4, lane, mt0, mlast, KB, cb0, per);
+  if (w >= NCW) {
+    loader_wave<MT>(lds, Ap, w - NCW, lane, mt0, mlast, KB, cb0, per);
     return;
   }
 
   // ---- compute waves ----
-  const int nt = nblk * 4 + w;
+  const int nt = nblk * NCW + w;
+  if constexpr (NCW != 4) {   // (the strips are padded to a multiple of four)
+    if (nt >= NT) {  // no strip left for this wave of the last feature block: it only keeps the block's barrier count
+      FSV_BARRIER();
+      for (int it = 0; it < per; ++it) FSV_BARRIER();
+      return;
+    }
+  }
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, wbytes, 0x00020000);
   const uint32_t wbase = ((uint32_t)nt * (uint32_t)KB * 64u + (uint32_t)lane) * 16u;
   constexpr uint32_t OOB = 0xFFFF0000u;  // a chunk beyond the K range: the descriptor returns zeros, no memory traffic
@@ -252,25 +261,34 @@ __global__ __launch_bounds__(64 * (4 + NLD)) void k_gemm(const void *__restrict_
 
 template <int MT, int EPI>
 int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt,
-             int M, int Mpad, int splits, int nchunks, int KBo, int NB, int mblocks, int f16, float oscale, hipStream_t st) {
+             int M, int Mpad, int splits, int nchunks, int KBo, int NB, int mblocks, int f16, float oscale, int ncw, int NT,
+             hipStream_t st) {
   // Weight chunks in flight per wave ahead of the one in use.  Measured on MI355X, one is best: with two to four the
   // bytes in flight across the chip approach the size of the L2s they pass through and the achieved bandwidth drops.
   constexpr int D = 1;
   const size_t ldsb = (size_t)NST * MT * KC * 64 * 16;   // fsv_bf16_gemm_init has raised the kernel's limit to this
   // the profiling events ride on the dispatch itself: they time the kernel, not the gaps around it
   fsv_prof_scope ps(c, st, cls, (double)N * KB * 32.0, true);
-  if (f16)
-    hipExtLaunchKernelGGL((k_gemm<MT, EPI, D, true>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
-                          (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, oscale);
-  else
-    hipExtLaunchKernelGGL((k_gemm<MT, EPI, D, false>), grid, dim3(64 * (4 + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, wbytes,
-                          (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, 1.0f);
+#define FSV_GEMM_GO(F16V, NCWV, OSC)                                                                                          \
+  hipExtLaunchKernelGGL((k_gemm<MT, EPI, D, F16V, NCWV>), grid, dim3(64 * (NCWV + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, \
+                        wbytes, (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, OSC, NT)
+  if (f16) {
+    if (ncw == 4) FSV_GEMM_GO(true, 4, oscale);
+    else if (ncw == 3) FSV_GEMM_GO(true, 3, oscale);
+    else FSV_GEMM_GO(true, 2, oscale);
+  } else {
+    if (ncw == 4) FSV_GEMM_GO(false, 4, 1.0f);
+    else if (ncw == 3) FSV_GEMM_GO(false, 3, 1.0f);
+    else FSV_GEMM_GO(false, 2, 1.0f);
+  }
+#undef FSV_GEMM_GO
   return FSV_OK;
 }
 
 template <int EPI>
 int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M, int splits,
-             int KBo, int f16, float oscale, hipStream_t st) {
+             int KBo, int f16, float oscale, int ncw, hipStream_t st) {
+  if (ncw < 2 || ncw > 4) FSV_FAIL(c, FSV_E_INVALID_ARG, "internal: %d compute waves per block", ncw);
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32, nchunks = K / 256, KB = K / 16;
   // row tiles per block: the fewest row blocks of at most four tiles (more do not fit the 256 registers a wave of a
   // six-wave block may use), the tiles spread evenly over them (five tiles are taken as 3 + 2, not 4 + 1: a block
@@ -280,9 +298,9 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
   if (wbytes > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
   if (splits < 1 || splits > nchunks) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad split count %d for %d granules", splits, nchunks);
   // one-dimensional grid, decoded in the kernel; feature blocks padded to a multiple of eight when the splits are not
-  const int NB = NTpad / 4, NBg = (splits % 8 == 0) ? NB : (NB + 7) / 8 * 8;
+  const int NB = fsv_ceil_div(NTpad, ncw), NBg = (splits % 8 == 0) ? NB : (NB + 7) / 8 * 8;
   dim3 grid((unsigned)NBg * splits * mblocks, 1, 1);
-#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, f16, oscale, st
+#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, f16, oscale, ncw, NTpad, st
   switch (mt_blk) {
     case 1: return launch_t<1, EPI>(FSV_ARGS);
     case 2: return launch_t<2, EPI>(FSV_ARGS);
@@ -294,10 +312,12 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
 
 template <int MT, int EPI>
 int init_t(fsv_ctx *c) {
-  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1, false>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, NST * MT * KC * 64 * 16));
-  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1, true>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, NST * MT * KC * 64 * 16));
+#define FSV_GEMM_ATTR(F16V, NCWV)                                                                          \
+  FSV_HIP(c, hipFuncSetAttribute(reinterpret_cast<const void *>(&k_gemm<MT, EPI, 1, F16V, NCWV>),          \
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, NST * MT * KC * 64 * 16))
+  FSV_GEMM_ATTR(false, 4); FSV_GEMM_ATTR(false, 3); FSV_GEMM_ATTR(false, 2);
+  FSV_GEMM_ATTR(true, 4); FSV_GEMM_ATTR(true, 3); FSV_GEMM_ATTR(true, 2);
+#undef FSV_GEMM_ATTR
   return FSV_OK;
 }
 
@@ -319,13 +339,14 @@ int fsv_bf16_gemm_init(fsv_ctx *c) {
 }
 
 // f16: both operands are fp16 and the sums are multiplied by oscale (see the head of this file); else bf16 operands.
+// ncw: compute waves (weight strips) per block, 2..4.
 int fsv_bf16_gemm(fsv_ctx *c, int cls, int epi, const void *Wp, const void *Ap, void *out, int N, int K, int NTpad, int M,
-                  int splits, int KBo, int f16, float oscale, hipStream_t st) {
+                  int splits, int KBo, int f16, float oscale, int ncw, hipStream_t st) {
   int rc;
   switch (epi) {
-    case EPI_PARTIAL: rc = launch_e<EPI_PARTIAL>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, st); break;
-    case EPI_SWIGLU: rc = launch_e<EPI_SWIGLU>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, st); break;
-    default: rc = launch_e<EPI_F32>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, st); break;
+    case EPI_PARTIAL: rc = launch_e<EPI_PARTIAL>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, ncw, st); break;
+    case EPI_SWIGLU: rc = launch_e<EPI_SWIGLU>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, ncw, st); break;
+    default: rc = launch_e<EPI_F32>(c, cls, Wp, Ap, out, N, K, NTpad, M, splits, KBo, f16, oscale, ncw, st); break;
   }
   if (rc) return rc;
   FSV_HIP(c, hipGetLastError());

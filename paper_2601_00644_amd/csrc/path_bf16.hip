@@ -597,11 +597,16 @@ gemm_shape shape_of(const fsv_ctx *c, int which) {
   return s;
 }
 
-// K splits so that feature tiles x splits x row blocks comes to about one block per compute unit (a block fills
+// How a projection is cut into blocks: compute waves (weight strips of 32 features) per block and K splits.
+struct gemm_launch {
+  int ncw, splits;
+};
+
+// K splits so that feature blocks x splits x row blocks comes to about one block per compute unit (a block fills
 // the unit's LDS with its activation ring; more splits only add partial sums to write and read back)
-int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
+int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow, int ncw) {
   if (!allow) return 1;
-  const int nchunks = s.K / KCHUNK, base = (s.NTpad / 4) * fsv_ceil_div(Mt, 4);
+  const int nchunks = s.K / KCHUNK, base = fsv_ceil_div(s.NTpad, ncw) * fsv_ceil_div(Mt, 4);
   int sp = c->n_cus / base;
   sp = max(1, min(sp, nchunks));
   if (sp >= 8) sp &= ~7;  // a multiple of eight keeps each split on one XCD (see k_gemm); the K cut is balanced, not equal
@@ -612,6 +617,30 @@ int pick_splits(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
     while (sp > 1 && fsv_ceil_div(nchunks, sp - 1) == longest) --sp;
   }
   return sp;
+}
+
+// With one row block (up to 128 rows) a projection is bound by streaming its weights, every wave streams its own strip
+// and what counts is that all compute units take part: among four, three and two strips per block take the one with
+// the least serial work per compute unit, rounds of blocks x strips per block x granules per split (8B shapes: q|k|v
+// goes from 48 x 4 = 192 blocks of four strips to 64 x 4 = 256 blocks of three; 1B shapes: gate|up from 128 blocks to
+// 256 of two strips).  Ties keep the larger block.  With several row blocks the matrix cores are the bound and a
+// block keeps one compute wave per SIMD.
+gemm_launch pick_launch(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allow) {
+  if (c->gemm_ncw_force) return gemm_launch{c->gemm_ncw_force, pick_splits(c, s, Mt, allow, c->gemm_ncw_force)};
+  gemm_launch best{4, pick_splits(c, s, Mt, allow, 4)};
+  if (Mt > 4) return best;
+  const int nchunks = s.K / KCHUNK;
+  long best_cost = -1;
+  for (int ncw = 4; ncw >= 2; --ncw) {
+    const int sp = pick_splits(c, s, Mt, allow, ncw);
+    const long blocks = (long)fsv_ceil_div(s.NTpad, ncw) * sp;
+    const long cost = (long)fsv_ceil_div((int)blocks, c->n_cus) * ncw * fsv_ceil_div(nchunks, sp);
+    if (best_cost < 0 || cost < best_cost) {
+      best = gemm_launch{ncw, sp};
+      best_cost = cost;
+    }
+  }
+  return best;
 }
 
 // Re-tile one weight matrix into the operand order of the matrix cores.  A matrix of an fp16 projection (shape_of().f16)
@@ -652,10 +681,10 @@ int copy_dev(fsv_ctx *c, void **dst, const void *src, size_t bytes) {
 }
 
 template <int EPI>
-int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, int splits,
+int launch_gemm(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, const gemm_shape &s, int M, gemm_launch gl,
                 hipStream_t st, float oscale = 1.0f) {
-  return fsv_bf16_gemm(c, cls, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0, s.f16,
-                       oscale, st);
+  return fsv_bf16_gemm(c, cls, EPI, Wp, Ap, out, s.N, s.K, s.NTpad, M, gl.splits, (EPI == EPI_SWIGLU) ? c->d.d_ffn / 16 : 0,
+                       s.f16, oscale, gl.ncw, st);
 }
 
 size_t layer_stride(const fsv_ctx *c, int num_pages) {
@@ -673,6 +702,10 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
     FSV_HIP(c, hipGetDevice(&dev));
     FSV_HIP(c, hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     if (c->n_cus < 1) c->n_cus = 1;
+  }
+  if (const char *e = getenv("FSV_GEMM_NCW")) {   // read before anything is sized by pick_launch
+    const int v = atoi(e);
+    if (v >= 2 && v <= 4) c->gemm_ncw_force = v;
   }
   if ((rc = copy_dev(c, &c->embed, w->embed, (size_t)2 * d.vocab * d.d_model))) return rc;
   if ((rc = copy_dev(c, &c->final_norm, w->final_norm, (size_t)2 * d.d_model))) return rc;
@@ -714,7 +747,7 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
     gemm_shape s = shape_of(c, which);
     if (which == FSV_W_LM_HEAD) continue;  // written straight to the logits
     for (int Mt = 1; Mt <= MtMax; ++Mt)
-      part = max(part, (size_t)pick_splits(c, s, Mt, which != FSV_W_GATE_UP) * Mt * 32 * s.N * 4);
+      part = max(part, (size_t)pick_launch(c, s, Mt, which != FSV_W_GATE_UP).splits * Mt * 32 * s.N * 4);
   }
   c->part_bytes = part;
   if ((rc = zalloc(&c->buf_part, part))) return rc;
@@ -729,7 +762,9 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
   const int Mt = fsv_ceil_div(M, 32), Mpad = Mt * 32;
   const gemm_shape sq = shape_of(c, FSV_W_QKV), so = shape_of(c, FSV_W_O), sg = shape_of(c, FSV_W_GATE_UP),
                    sd = shape_of(c, FSV_W_DOWN), sl = shape_of(c, FSV_W_LM_HEAD);
-  const int spq = pick_splits(c, sq, Mt, true), spo = pick_splits(c, so, Mt, true), spd = pick_splits(c, sd, Mt, true);
+  const gemm_launch glq = pick_launch(c, sq, Mt, true), glo = pick_launch(c, so, Mt, true), gld = pick_launch(c, sd, Mt, true),
+                    glg = pick_launch(c, sg, Mt, false), gll = pick_launch(c, sl, Mt, false);
+  const int spq = glq.splits, spo = glo.splits, spd = gld.splits;
   float *part = (float *)c->buf_part;
   const int nthr = min(1024, max(64, fsv_ceil_div(d.d_model / 8, 64) * 64));  // one 8-wide slice per thread
   int rc;
@@ -773,7 +808,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
     const size_t lo = (size_t)(draft ? 0 : l) * layer_stride(c, b->num_pages);
     const bool adapted = lora && l < d.n_layers - 1;         // the last block belongs to the invariant head
     const bool next_adapted = lora && l + 1 < d.n_layers - 1;
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, spq, s, L.os_qkv))) return rc;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_QKV, L.w_qkv, c->buf_a, part, sq, M, glq, s, L.os_qkv))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_ROPE_APPEND, 0.0);
       const dim3 rg(M, fsv_ceil_div((d.n_heads + 2 * d.n_kv_heads) * (d.head_dim / 8), 256));
@@ -789,7 +824,7 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
 #undef FSV_ROPE_ARGS
     }
     if ((rc = fsv_bf16_attn_launch(c, b, &pl, lo, s))) return rc;
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, spo, s, L.os_o))) return rc;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_O, L.w_o, c->buf_att, part, so, M, glo, s, L.os_o))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
       if (adapted)
@@ -799,8 +834,8 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
         hipLaunchKernelGGL((k_resid_norm<0, 0, 0>), dim3(Mpad), dim3(nthr), 0, s, M, d.d_model, d.rms_eps, c->row_tok, nullptr,
                            part, spo, Mpad, c->x, (const uint16_t *)L.mlp_norm, (uint4 *)c->buf_a, lora_args{});
     }
-    if ((rc = launch_gemm<EPI_SWIGLU>(c, FSV_K_GEMM_GATE_UP, L.w_gate_up, c->buf_a, c->buf_act, sg, M, 1, s, L.os_gate_up))) return rc;
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_DOWN, L.w_down, c->buf_act, part, sd, M, spd, s))) return rc;
+    if ((rc = launch_gemm<EPI_SWIGLU>(c, FSV_K_GEMM_GATE_UP, L.w_gate_up, c->buf_a, c->buf_act, sg, M, glg, s, L.os_gate_up))) return rc;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_GEMM_DOWN, L.w_down, c->buf_act, part, sd, M, gld, s))) return rc;
     {
       fsv_prof_scope ps(c, s, FSV_K_NORM, 0.0);
       const void *gain = (l + 1 < d.n_layers) ? c->layers[l + 1].attn_norm : c->final_norm;
@@ -818,16 +853,17 @@ int fsv_bf16_forward(fsv_ctx *c, const fsv_batch *b, const fsv_attn_plan *plan, 
   if (draft) {
     // H_small: z = W_v (W_2 silu(W_1 h)), h = the block's output as just stored in buf_a
     const gemm_shape s1 = shape_of(c, W_DRAFT1), s2 = shape_of(c, W_DRAFT2), sv = shape_of(c, W_DRAFTV);
-    const int sp1 = pick_splits(c, s1, Mt, true), sp2 = pick_splits(c, s2, Mt, true);
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_OTHER, c->draft_w1, c->buf_a, part, s1, M, sp1, s))) return rc;
+    const gemm_launch gl1 = pick_launch(c, s1, Mt, true), gl2 = pick_launch(c, s2, Mt, true), glv = pick_launch(c, sv, Mt, false);
+    const int sp1 = gl1.splits, sp2 = gl2.splits;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_OTHER, c->draft_w1, c->buf_a, part, s1, M, gl1, s))) return rc;
     hipLaunchKernelGGL(k_head_act<1>, dim3(Mpad), dim3(256), 0, s, part, sp1, Mpad, M, s1.N, (uint4 *)c->draft_h1);
-    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_OTHER, c->draft_w2, c->draft_h1, part, s2, M, sp2, s))) return rc;
+    if ((rc = launch_gemm<EPI_PARTIAL>(c, FSV_K_OTHER, c->draft_w2, c->draft_h1, part, s2, M, gl2, s))) return rc;
     hipLaunchKernelGGL(k_head_act<0>, dim3(Mpad), dim3(256), 0, s, part, sp2, Mpad, M, s2.N, (uint4 *)c->draft_h2);
-    if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->draft_wv, c->draft_h2, logits, sv, M, 1, s))) return rc;
+    if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->draft_wv, c->draft_h2, logits, sv, M, glv, s))) return rc;
     FSV_HIP(c, hipGetLastError());
     return FSV_OK;
   }
-  if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->lm_head, c->buf_a, logits, sl, M, 1, s, c->os_lm_head))) return rc;
+  if ((rc = launch_gemm<EPI_F32>(c, FSV_K_GEMM_LM_HEAD, c->lm_head, c->buf_a, logits, sl, M, gll, s, c->os_lm_head))) return rc;
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -855,7 +891,7 @@ int fsv_bf16_draft_attach(fsv_ctx *c, const fsv_draft_head *h) {
   size_t part = c->part_bytes;   // the split partials of the head's projections share the forward's buffer
   for (int which : {W_DRAFT1, W_DRAFT2}) {
     const gemm_shape sh = shape_of(c, which);
-    for (int Mt = 1; Mt <= MtMax; ++Mt) part = max(part, (size_t)pick_splits(c, sh, Mt, true) * Mt * 32 * sh.N * 4);
+    for (int Mt = 1; Mt <= MtMax; ++Mt) part = max(part, (size_t)pick_launch(c, sh, Mt, true).splits * Mt * 32 * sh.N * 4);
   }
   if (part > c->part_bytes) {
     (void)hipFree(c->buf_part);
@@ -930,9 +966,10 @@ int fsv_bf16_linear(fsv_ctx *c, int which, int layer, const void *x, int M, floa
   hipLaunchKernelGGL(k_pack_act, dim3((unsigned)((nact + 255) / 256)), dim3(256), 0, s, (const uint16_t *)x, M, Mpad, sh.K,
                      (uint4 *)c->buf_a, sh.f16);
   int rc;
-  if (which == FSV_W_LM_HEAD) return launch_gemm<EPI_F32>(c, cls, Wp, c->buf_a, y, sh, M, 1, s, os);
-  const int sp = pick_splits(c, sh, Mt, which != FSV_W_GATE_UP);
-  if ((rc = launch_gemm<EPI_PARTIAL>(c, cls, Wp, c->buf_a, c->buf_part, sh, M, sp, s, os))) return rc;
+  if (which == FSV_W_LM_HEAD) return launch_gemm<EPI_F32>(c, cls, Wp, c->buf_a, y, sh, M, pick_launch(c, sh, Mt, false), s, os);
+  const gemm_launch gl = pick_launch(c, sh, Mt, which != FSV_W_GATE_UP);
+  const int sp = gl.splits;
+  if ((rc = launch_gemm<EPI_PARTIAL>(c, cls, Wp, c->buf_a, c->buf_part, sh, M, gl, s, os))) return rc;
   const size_t n = (size_t)M * sh.N;
   hipLaunchKernelGGL(k_reduce_part, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, (const float *)c->buf_part, sp, Mpad,
                      M, sh.N, sh.mode, c->d.d_ffn, y);

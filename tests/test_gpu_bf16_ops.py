@@ -44,6 +44,28 @@ def test_linear_matches_oracle(name, M):
     ctx.close()
 
 
+@pytest.mark.parametrize("ncw", [2, 3, 4])
+@pytest.mark.parametrize("M", [7, 97, 128, 300])
+def test_linear_with_every_block_shape(ncw, M, monkeypatch):
+    """The projections choose two, three or four weight strips per block by what fills the machine; here each shape is
+    forced (FSV_GEMM_NCW) on matrices whose strip count is and is not a multiple of it (the last block then has waves
+    without a strip), one row block and several."""
+    monkeypatch.setenv("FSV_GEMM_NCW", str(ncw))
+    cfg = synth.MODELS["mini128"]
+    fv, ctx, w, wn = _ctx(cfg, 11, max_batch=8, max_gamma=16, max_rows=max(M, 136))
+    g = torch.Generator().manual_seed(100 * ncw + M)
+    for wh, key, K in [(fv.W_QKV, "w_qkv.0", cfg.d_model), (fv.W_O, "w_o.1", cfg.n_heads * cfg.head_dim),
+                       (fv.W_GATE_UP, "w_gate_up.0", cfg.d_model), (fv.W_DOWN, "w_down.1", cfg.d_ffn),
+                       (fv.W_LM_HEAD, "lm_head", cfg.d_model)]:
+        layer = int(key.split(".")[1]) if "." in key else 0
+        x = torch.randn((M, K), generator=g).to(torch.bfloat16)
+        y = ctx.linear(wh, layer, x.cuda(), wn[key].shape[0]).cpu().numpy().astype(np.float64)
+        ref = oracle.linear(wn[key], x.float().numpy().astype(np.float64), True)
+        ok, ratio = logits_close(y, ref, 1e-3)
+        assert ok, (key, ncw, M, ratio)
+    ctx.close()
+
+
 @pytest.mark.parametrize("scale", [1e-7, 1.0, 2.0e4])
 def test_linear_over_the_range_of_weight_magnitudes(scale):
     """The projections that keep their operands in fp16 convert their bf16 weights once, times a power of two per matrix:
