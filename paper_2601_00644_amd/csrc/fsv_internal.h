@@ -71,6 +71,7 @@ struct fsv_ctx {
   // model workspace (both paths)
   float *x = nullptr;       // [rows_pad][d_model] residual stream, fp32
   float *logits = nullptr;  // [max_rows][vocab] fp32 when the caller passes no logits_out
+  int strip_pad_bytes = 8192;   // bf16 path: padding between the weight strips of a re-tiled matrix (FSV_STRIP_PAD_KIB overrides)
   int gemm_ncw_force = 0;       // bf16 path: 2..4 = weight strips per GEMM block fixed (FSV_GEMM_NCW, a measurement and test knob)
   float os_lm_head = 1.0f;      // bf16 path: inverse of the power of two the fp16 LM-head matrix carries
   uint32_t *absmax = nullptr;   // bf16 path: one word for the largest weight magnitude of the matrix being converted

@@ -13,6 +13,10 @@
 // and a wait for the oldest chunk never drains the younger ones.  One barrier per chunk hands a filled
 // stage to the compute waves and a consumed one back to the loader.
 //
+// The strips of consecutive feature tiles lie K / 16 KiB plus a padding of 8 KiB apart: all waves advance through their
+// strips in step, and with the strips a power of two apart (256 KiB at K = 4096) their concurrent requests fall on
+// the same memory channels; a plain reader with this access pattern gains 9 % from the padding (measured on MI355X).
+//
 // F16: both operands are fp16 (the projections whose input is a normalised activation or an attention output, which are
 // bounded whatever the model and gain three significant bits over bf16 that way).  Their weights were converted from bf16
 // at creation, times a power of two per matrix that places the largest weight near 2^13 (the conversion is then exact
@@ -147,7 +151,8 @@ __device__ __forceinline__ void loader_wave(uint4 *lds, const uint4 *__restrict_
 template <int MT, int EPI, int D, bool F16, int NCW>
 __global__ __launch_bounds__(64 * (NCW + NLD)) void k_gemm(const void *__restrict__ Wp, uint32_t wbytes, const uint4 *__restrict__ Ap,
                                               void *__restrict__ out, int N, int KB, int Mt_total, int M, int Mpad,
-                                              int S, int nchunks, int KBo, int NBv, int MB, float oscale, int NT) {
+                                              int S, int nchunks, int KBo, int NBv, int MB, float oscale, int NT, uint32_t strip_bytes) {
+  // strip_bytes: distance between the weight strips of consecutive 32-feature tiles (K / 16 KiB of operands plus padding)
   // NCW: compute waves of the block (the block has NCW + NLD waves); NT: weight strips the matrix holds
   extern __shared__ uint4 lds[];
   constexpr int CHU = MT * KC * 64;  // 16-byte units of one activation chunk
@@ -191,7 +196,7 @@ __global__ __launch_bounds__(64 * (NCW + NLD)) void k_gemm(const void *__restric
     }
   }
   const __amdgpu_buffer_rsrc_t wrs = __builtin_amdgcn_make_buffer_rsrc((void *)Wp, 0, wbytes, 0x00020000);
-  const uint32_t wbase = ((uint32_t)nt * (uint32_t)KB * 64u + (uint32_t)lane) * 16u;
+  const uint32_t wbase = (uint32_t)nt * strip_bytes + (uint32_t)lane * 16u;
   constexpr uint32_t OOB = 0xFFFF0000u;  // a chunk beyond the K range: the descriptor returns zeros, no memory traffic
   bf16x8_t wb[D + 1][KC];   // sixteen bytes of operand per lane; the element type only matters to the MFMA below
   auto issue = [&](int it, bf16x8_t(&dst)[KC]) {
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(64 * (NCW + NLD)) void k_gemm(const void *__restric
 template <int MT, int EPI>
 int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, const void *Ap, void *out, int N, int KB, int Mt,
              int M, int Mpad, int splits, int nchunks, int KBo, int NB, int mblocks, int f16, float oscale, int ncw, int NT,
-             hipStream_t st) {
+             uint32_t strip_bytes, hipStream_t st) {
   // Weight chunks in flight per wave ahead of the one in use.  Measured on MI355X, one is best: with two to four the
   // bytes in flight across the chip approach the size of the L2s they pass through and the achieved bandwidth drops.
   constexpr int D = 1;
@@ -271,7 +276,7 @@ int launch_t(fsv_ctx *c, int cls, dim3 grid, const void *Wp, uint32_t wbytes, co
   fsv_prof_scope ps(c, st, cls, (double)N * KB * 32.0, true);
 #define FSV_GEMM_GO(F16V, NCWV, OSC)                                                                                          \
   hipExtLaunchKernelGGL((k_gemm<MT, EPI, D, F16V, NCWV>), grid, dim3(64 * (NCWV + NLD)), ldsb, st, ps.start(), ps.stop(), 0, Wp, \
-                        wbytes, (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, OSC, NT)
+                        wbytes, (const uint4 *)Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, OSC, NT, strip_bytes)
   if (f16) {
     if (ncw == 4) FSV_GEMM_GO(true, 4, oscale);
     else if (ncw == 3) FSV_GEMM_GO(true, 3, oscale);
@@ -294,13 +299,14 @@ int launch_e(fsv_ctx *c, int cls, const void *Wp, const void *Ap, void *out, int
   // six-wave block may use), the tiles spread evenly over them (five tiles are taken as 3 + 2, not 4 + 1: a block
   // works on its full tile count whatever the number of real rows)
   const int mblocks = fsv_ceil_div(Mt, 4), mt_blk = fsv_ceil_div(Mt, mblocks);
-  const size_t wbytes = (size_t)NTpad * KB * 1024;
+  const uint32_t strip_bytes = (uint32_t)KB * 1024u + (uint32_t)c->strip_pad_bytes;
+  const size_t wbytes = (size_t)NTpad * strip_bytes;
   if (wbytes > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
   if (splits < 1 || splits > nchunks) FSV_FAIL(c, FSV_E_INVALID_ARG, "bad split count %d for %d granules", splits, nchunks);
   // one-dimensional grid, decoded in the kernel; feature blocks padded to a multiple of eight when the splits are not
   const int NB = fsv_ceil_div(NTpad, ncw), NBg = (splits % 8 == 0) ? NB : (NB + 7) / 8 * 8;
   dim3 grid((unsigned)NBg * splits * mblocks, 1, 1);
-#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, f16, oscale, ncw, NTpad, st
+#define FSV_ARGS c, cls, grid, Wp, (uint32_t)wbytes, Ap, out, N, KB, Mt, M, Mpad, splits, nchunks, KBo, NB, mblocks, f16, oscale, ncw, NTpad, strip_bytes, st
   switch (mt_blk) {
     case 1: return launch_t<1, EPI>(FSV_ARGS);
     case 2: return launch_t<2, EPI>(FSV_ARGS);

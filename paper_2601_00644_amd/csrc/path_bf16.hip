@@ -31,11 +31,17 @@ namespace {
 // gate and up interleaved in groups of 8 (rows 0-7 gate f0-7, 8-15 up f0-7, 16-23 gate f8-15, 24-31 up f8-15),
 // so that after the MFMA one lane owns gate and up of the same four features.
 __global__ void k_pack_w(const uint16_t *__restrict__ W, int N, int K, int NTpad, int mode, int F, uint4 *__restrict__ out,
-                         int f16, float wscale) {
+                         int f16, float wscale, int strip_units) {
+  // strip_units: 16-byte units from one strip of 32 features to the next (K / 16 * 64 of operands, then padding)
   const size_t unit = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   const int KB = K / 16;
-  if (unit >= (size_t)NTpad * KB * 64) return;
-  const int lane = unit & 63, kb = (unit >> 6) % KB, nt = (unit >> 6) / KB;
+  if (unit >= (size_t)NTpad * strip_units) return;
+  const int nt = (int)(unit / strip_units), rem = (int)(unit % strip_units);
+  if (rem >= KB * 64) {   // padding between strips
+    out[unit] = make_uint4(0, 0, 0, 0);
+    return;
+  }
+  const int lane = rem & 63, kb = rem >> 6;
   const int np = nt * 32 + (lane & 31), k0 = kb * 16 + 8 * (lane >> 5);
   int src = -1;
   if (mode == 0) {
@@ -649,7 +655,8 @@ gemm_launch pick_launch(const fsv_ctx *c, const gemm_shape &s, int Mt, bool allo
 // matrix), and nothing overflows.  *oscale receives 2^-s, which the projection multiplies its fp32 sums by.
 int pack_weight(fsv_ctx *c, const void *src, int which, void **dst, float *oscale = nullptr) {
   gemm_shape s = shape_of(c, which);
-  const size_t units = (size_t)s.NTpad * (s.K / 16) * 64;
+  const int strip_units = (s.K / 16) * 64 + c->strip_pad_bytes / 16;
+  const size_t units = (size_t)s.NTpad * strip_units;
   if (units * 16 > 0xFFFF0000ull) FSV_FAIL(c, FSV_E_UNSUPPORTED, "a weight matrix must stay below 4 GiB");
   float wscale = 1.0f;
   if (s.f16) {
@@ -669,7 +676,7 @@ int pack_weight(fsv_ctx *c, const void *src, int which, void **dst, float *oscal
   }
   FSV_HIP(c, hipMalloc(dst, units * 16));
   hipLaunchKernelGGL(k_pack_w, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, 0, (const uint16_t *)src, s.N, s.K,
-                     s.NTpad, s.mode, c->d.d_ffn, (uint4 *)*dst, s.f16, wscale);
+                     s.NTpad, s.mode, c->d.d_ffn, (uint4 *)*dst, s.f16, wscale, strip_units);
   FSV_HIP(c, hipGetLastError());
   return FSV_OK;
 }
@@ -702,6 +709,10 @@ int fsv_bf16_create(fsv_ctx *c, const fsv_weights *w) {
     FSV_HIP(c, hipGetDevice(&dev));
     FSV_HIP(c, hipDeviceGetAttribute(&c->n_cus, hipDeviceAttributeMultiprocessorCount, dev));
     if (c->n_cus < 1) c->n_cus = 1;
+  }
+  if (const char *e = getenv("FSV_STRIP_PAD_KIB")) {   // measurement knob; read before any matrix is re-tiled
+    const int v = atoi(e);
+    if (v >= 0 && v <= 64) c->strip_pad_bytes = v * 1024;
   }
   if (const char *e = getenv("FSV_GEMM_NCW")) {   // read before anything is sized by pick_launch
     const int v = atoi(e);
