@@ -75,7 +75,9 @@ typedef struct {
  * converted once, times a power of two per matrix that puts its largest weight near 2^13, so that every
  * weight down to 2^-31 of the largest converts exactly (smaller ones round on the fp16 subnormal grid of the
  * scaled matrix), and the fp32 sums are multiplied by the inverse power.  The down projection (its input,
- * the SwiGLU output, has no bound) and the KV cache stay bf16.
+ * the SwiGLU output, has no bound) and the KV cache stay bf16.  The conversion of the two fp16 tensors
+ * saturates: a normalised activation or an attention output beyond +-65504 (gains in the thousands, or cached
+ * values of that size) is held there instead of becoming an infinity; NaN stays NaN.
  */
 typedef struct {
   const void *embed;             /* [vocab][d_model]                                          */
